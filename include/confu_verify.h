@@ -1,0 +1,200 @@
+/*
+ * confu_verify.h - C ABI of the MI355X (gfx950) tree-verification library.
+ *
+ * Two operations of one speculative-decoding iteration's target-model pass:
+ *
+ *   tree_verify_attention  attention of the M = T + C new rows (T draft-tree nodes,
+ *                          C contemplate rows) over the cached prefix and over their
+ *                          own tree ancestors, one call per transformer layer;
+ *   tree_accept            temperature softmax over the vocabulary and the tree
+ *                          acceptance walk that returns the accepted path and the
+ *                          bonus / residual token.
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device memory owned by the caller (for instance the
+ *     data_ptr() of a PyTorch tensor); "host" pointers are ordinary host memory.
+ *     The library never frees or retains them.
+ *   - Scratch memory comes from the caller's workspace (device); its size is given by
+ *     the matching *_workspace_bytes query for the same descriptor.  The workspace
+ *     may be reused by the next call on the same stream; concurrent calls on
+ *     different streams need different workspaces.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without synchronising.
+ *   - Return value: TV_OK, or an error found on the host before anything was
+ *     enqueued.  Errors that depend on device data (a malformed tree, a token id out
+ *     of range, a prefix length out of range) are reported per sequence in the
+ *     device array `status`, and that sequence's outputs are then zeros
+ *     (attention) or -1 (acceptance).
+ *   - No global mutable state apart from a cached device-property query; calls are
+ *     thread-safe for distinct streams and workspaces.
+ */
+#ifndef CONFU_VERIFY_H
+#define CONFU_VERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- return codes ------------------------------------------------------------ */
+#define TV_OK                 0
+#define TV_ERR_INVALID_ARG    1   /* null pointer, size out of range, bad struct_size */
+#define TV_ERR_WORKSPACE      2   /* workspace missing or too small */
+#define TV_ERR_LAUNCH         3   /* HIP reported an error at launch */
+#define TV_ERR_UNSUPPORTED    4   /* valid request this build has no kernel for */
+
+/* ---- per-sequence status bits written to `status` (device) --------------------- */
+#define TV_STATUS_OK            0
+#define TV_STATUS_BAD_PARENT    1   /* parent[i] outside [-1, i), or root missing */
+#define TV_STATUS_BAD_KIND      2   /* kind not 0/1, or a draft node hangs off a contemplate row */
+#define TV_STATUS_BAD_PREFIX    4   /* prefix_len < soft_len, < 0 or > max_prefix_len */
+#define TV_STATUS_BAD_TOKEN     8   /* token id outside [0, V) */
+
+/* ---- limits -------------------------------------------------------------------- */
+#define TV_MAX_ROWS   128          /* M (attention) and T (acceptance) */
+
+/* ---- enums ---------------------------------------------------------------------- */
+#define TV_DTYPE_F32   0
+#define TV_DTYPE_BF16  1
+
+#define TV_KIND_NODE         0     /* a draft-tree node (row 0 of a sequence is the root) */
+#define TV_KIND_CONTEMPLATE  1     /* a contemplate row: may attend to the soft-prompt slots */
+
+#define TV_RULE_GREEDY         0   /* temperature 0: a child is accepted iff it is the argmax */
+#define TV_RULE_DETERMINISTIC  1   /* temp > 0, no draft law: each child is a point-mass proposal */
+#define TV_RULE_DRAFT_WOR      2   /* temp > 0, siblings drawn from the draft law without replacement */
+#define TV_RULE_DRAFT_WR       3   /* temp > 0, siblings drawn independently (with replacement) */
+
+#define TV_FINAL_BONUS     0       /* nothing was rejected at the stop node: token from the target law */
+#define TV_FINAL_RESIDUAL  1       /* at least one child was rejected there: token from the corrected law */
+
+/* =================================================================================
+ * tree_verify_attention
+ *
+ * Operation (paper: Section 2, tree attention over the draft tree; Section 3.1,
+ * contemplate rows appended to the tree and soft-prompt slots at the head of the KV
+ * cache that only contemplate rows may attend to; Figure 4).
+ *
+ * For sequence b, query row i (0 <= i < M) and query head h (KV head g = h / (Hq/Hkv)):
+ *
+ *   visible cached rows   [soft_len, P_b) if kind[i] = NODE, [0, P_b) if CONTEMPLATE
+ *   visible new rows      j in {i, parent[i], parent[parent[i]], ..., root}
+ *   out[b,i,h,:] = sum_k softmax_k(softmax_scale * q[b,i,h,:] . K[k,g,:]) * V[k,g,:]
+ *
+ * The KV pool holds for sequence b the rows kv_offset[b] .. kv_offset[b]+P_b+M-1:
+ * the P_b cached rows (the first soft_len of them are the soft-prompt slots) followed
+ * by this step's M new rows, already written by the caller.  Row r, KV head g starts
+ * at element r*kv_token_stride + g*kv_head_stride; its D elements are contiguous.
+ * ================================================================================= */
+typedef struct tv_attn_desc {
+    uint32_t struct_size;      /* sizeof(tv_attn_desc), checked */
+    int32_t  dtype;            /* TV_DTYPE_F32 (D in {64,128}) or TV_DTYPE_BF16 (D = 128) */
+    int32_t  B;                /* sequences, >= 1 */
+    int32_t  M;                /* query rows per sequence, 1..TV_MAX_ROWS */
+    int32_t  Hq;               /* query heads */
+    int32_t  Hkv;              /* KV heads, divides Hq; Hq/Hkv <= 16 */
+    int32_t  D;                /* head dimension */
+    int32_t  soft_len;         /* s: leading cached rows that are soft-prompt slots, >= 0 */
+    int32_t  max_prefix_len;   /* host-known upper bound of prefix_len[b] (sizes the launch) */
+    float    softmax_scale;    /* usually 1/sqrt(D) */
+    int64_t  kv_token_stride;  /* elements between consecutive rows of the pool; 0 = Hkv*D */
+    int64_t  kv_head_stride;   /* elements between KV heads of one row; 0 = D */
+    int32_t  num_splits;       /* 0 = library decides how many ranges the keys are cut into */
+    int32_t  reserved;         /* must be 0 */
+} tv_attn_desc;
+
+/* host: writes the workspace size (bytes) tree_verify_attention needs for *desc.
+ * Returns TV_OK / TV_ERR_INVALID_ARG / TV_ERR_UNSUPPORTED. */
+int tv_attention_workspace_bytes(const tv_attn_desc* desc, size_t* out_bytes);
+
+int tree_verify_attention(
+    const tv_attn_desc* desc,      /* host */
+    const void*    q,              /* device [B, M, Hq, D], dtype, contiguous */
+    const void*    k_pool,         /* device, dtype, layout above */
+    const void*    v_pool,         /* device, dtype, same layout as k_pool */
+    const int64_t* kv_offset,      /* device [B]: first pool row of sequence b */
+    const int32_t* prefix_len,     /* device [B]: P_b, soft-prompt slots included */
+    const int32_t* parent,         /* device [B, M]: parent row, -1 for the root, parent[i] < i */
+    const uint8_t* kind,           /* device [B, M]: TV_KIND_* */
+    void*          out,            /* device [B, M, Hq, D], dtype */
+    float*         lse,            /* device [B, Hq, M] natural-log sum of exp of the scaled visible scores, or NULL */
+    int32_t*       status,         /* device [B]: TV_STATUS_* bits, written by the call */
+    void*          workspace,      /* device, 256-byte aligned, may be NULL if 0 bytes are needed */
+    size_t         workspace_bytes,
+    void*          hip_stream);
+
+/* =================================================================================
+ * tree_accept
+ *
+ * Operation (paper: Section 2 steps 3-4, drafts are checked in order and the first
+ * rejected one is replaced by a token from the target's corrected distribution; tree
+ * form: the longest accepted path; Section 3.1: the future prediction of the last
+ * accepted node is kept; Section 4: temperatures 0 / 0.7 / 1.0, tau counts the bonus
+ * token).  With p = softmax(target_logits[node]/temperature) and, for the DRAFT rules,
+ * q = softmax(draft_logits[node]/temperature), starting at the root:
+ *
+ *   for each child c of the current node, in increasing index, x = token[c]:
+ *     DETERMINISTIC  accept iff u[c] < p(x);        on reject p(x) = 0, p renormalised
+ *     DRAFT_WOR/WR   accept iff u[c]*q(x) < p(x);   on reject p = norm(max(p - q, 0));
+ *                    DRAFT_WOR also removes x from q and renormalises q
+ *     GREEDY         accept iff x = argmax target_logits[node] (lowest index on ties)
+ *     an accepted child becomes the current node;
+ *   when no child is accepted: final_token = first v whose running sum of p exceeds
+ *   u[T + node] (GREEDY: the argmax), final_kind says whether p had been corrected.
+ * ================================================================================= */
+typedef struct tv_accept_desc {
+    uint32_t struct_size;        /* sizeof(tv_accept_desc), checked */
+    int32_t  B;                  /* sequences, >= 1 */
+    int32_t  T;                  /* draft nodes per sequence (root included), 1..TV_MAX_ROWS */
+    int32_t  V;                  /* vocabulary size, >= 1 */
+    int32_t  C;                  /* entries of con_anchor per sequence (0 if con_anchor is NULL) */
+    int32_t  rule;               /* TV_RULE_* */
+    float    temperature;        /* > 0 unless rule = GREEDY */
+    int64_t  logits_row_stride;  /* elements between consecutive rows of the logits; 0 = V */
+    int32_t  reserved[2];        /* must be 0 */
+} tv_accept_desc;
+
+int tv_accept_workspace_bytes(const tv_accept_desc* desc, size_t* out_bytes);
+
+int tree_accept(
+    const tv_accept_desc* desc,     /* host */
+    const float*   target_logits,   /* device [B, T, V] fp32 (rows logits_row_stride apart) */
+    const float*   draft_logits,    /* device [B, T, V] fp32; required by the DRAFT rules, else NULL */
+    const int32_t* token,           /* device [B, T]: token drafted at each node (token[0]: the root's) */
+    const int32_t* parent,          /* device [B, T]: parent node, -1 for the root, parent[i] < i */
+    const float*   uniforms,        /* device [B, 2T]: u[c] tests node c, u[T+n] draws the final token at stop node n; unused by GREEDY (may be NULL) */
+    const int32_t* con_anchor,      /* device [B, C]: node each contemplate row belongs to, or NULL */
+    int32_t*       path,            /* device [B, T]: accepted nodes, root first, then -1 */
+    int32_t*       n_accepted,      /* device [B]: accepted draft tokens (root not counted) */
+    int32_t*       final_token,     /* device [B] */
+    int32_t*       final_kind,      /* device [B]: TV_FINAL_* */
+    int32_t*       last_node,       /* device [B]: path[n_accepted] */
+    int32_t*       selected_con,    /* device [B]: first c with con_anchor[c] == last_node, else -1; may be NULL */
+    int32_t*       status,          /* device [B]: TV_STATUS_* bits */
+    void*          workspace,       /* device, 256-byte aligned */
+    size_t         workspace_bytes,
+    void*          hip_stream);
+
+/* =================================================================================
+ * Host helpers
+ * ================================================================================= */
+
+/* host: checks a parent/kind pair and writes the ancestor-closure bit mask the attention
+ * kernels build on the device: bit j of bits[2*i + j/64] is set iff row i may attend to new
+ * row j (Section 3.1 / Figure 4).  All pointers are host memory; bits holds 2*M words
+ * (pass NULL to validate only).  Returns TV_OK, TV_ERR_INVALID_ARG, or -(TV_STATUS_* bits)
+ * when the tree is malformed. */
+int tv_build_mask_host(const int32_t* parent, const uint8_t* kind, int M, uint64_t* bits);
+
+/* host: static text for a return code. */
+const char* tv_error_string(int code);
+
+/* host: library version, major*100 + minor. */
+int tv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONFU_VERIFY_H */

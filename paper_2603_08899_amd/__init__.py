@@ -1,0 +1,162 @@
+"""Python binding of libconfu_verify.so (MI355X / gfx950 tree-verification library).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.
+PyTorch is used for device memory and streams.  There is no CPU fallback: if the
+shared library has not been built, importing the entry points raises.
+
+    from paper_2603_08899_amd import tree_verify_attention, tree_accept
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libconfu_verify.so")
+
+TV_OK, TV_ERR_INVALID_ARG, TV_ERR_WORKSPACE, TV_ERR_LAUNCH, TV_ERR_UNSUPPORTED = 0, 1, 2, 3, 4
+TV_STATUS_BAD_PARENT, TV_STATUS_BAD_KIND, TV_STATUS_BAD_PREFIX, TV_STATUS_BAD_TOKEN = 1, 2, 4, 8
+TV_MAX_ROWS = 128
+TV_DTYPE_F32, TV_DTYPE_BF16 = 0, 1
+TV_KIND_NODE, TV_KIND_CONTEMPLATE = 0, 1
+TV_RULE_GREEDY, TV_RULE_DETERMINISTIC, TV_RULE_DRAFT_WOR, TV_RULE_DRAFT_WR = 0, 1, 2, 3
+TV_FINAL_BONUS, TV_FINAL_RESIDUAL = 0, 1
+
+EXPORTED_SYMBOLS = (
+    "tv_attention_workspace_bytes", "tree_verify_attention",
+    "tv_accept_workspace_bytes", "tree_accept",
+    "tv_build_mask_host", "tv_error_string", "tv_version",
+)
+
+
+class tv_attn_desc(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32), ("dtype", ctypes.c_int32),
+        ("B", ctypes.c_int32), ("M", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+        ("D", ctypes.c_int32), ("soft_len", ctypes.c_int32), ("max_prefix_len", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float),
+        ("kv_token_stride", ctypes.c_int64), ("kv_head_stride", ctypes.c_int64),
+        ("num_splits", ctypes.c_int32), ("reserved", ctypes.c_int32),
+    ]
+
+
+class tv_accept_desc(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32), ("B", ctypes.c_int32), ("T", ctypes.c_int32),
+        ("V", ctypes.c_int32), ("C", ctypes.c_int32), ("rule", ctypes.c_int32),
+        ("temperature", ctypes.c_float), ("logits_row_stride", ctypes.c_int64),
+        ("reserved", ctypes.c_int32 * 2),
+    ]
+
+
+class ConfuVerifyError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        msg = lib().tv_error_string(code).decode() if _lib is not None else str(code)
+        super().__init__(f"{where}: {msg} (code {code})")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the shared library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2603_08899_amd.build` "
+                "(hipcc, gfx950). There is no CPU fallback.")
+        l = ctypes.CDLL(LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        l.tv_version.restype = ctypes.c_int
+        l.tv_error_string.restype = ctypes.c_char_p
+        l.tv_error_string.argtypes = [ctypes.c_int]
+        l.tv_build_mask_host.restype = ctypes.c_int
+        l.tv_build_mask_host.argtypes = [vp, vp, ctypes.c_int, vp]
+        l.tv_attention_workspace_bytes.restype = ctypes.c_int
+        l.tv_attention_workspace_bytes.argtypes = [ctypes.POINTER(tv_attn_desc), ctypes.POINTER(sz)]
+        l.tree_verify_attention.restype = ctypes.c_int
+        l.tree_verify_attention.argtypes = [ctypes.POINTER(tv_attn_desc)] + [vp] * 11 + [sz, vp]
+        l.tv_accept_workspace_bytes.restype = ctypes.c_int
+        l.tv_accept_workspace_bytes.argtypes = [ctypes.POINTER(tv_accept_desc), ctypes.POINTER(sz)]
+        l.tree_accept.restype = ctypes.c_int
+        l.tree_accept.argtypes = [ctypes.POINTER(tv_accept_desc)] + [vp] * 14 + [sz, vp]
+        _lib = l
+    return _lib
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_handle(stream) -> Optional[int]:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream or None
+
+
+def make_attn_desc(*, dtype: int, B: int, M: int, Hq: int, Hkv: int, D: int, soft_len: int,
+                   max_prefix_len: int, softmax_scale: float, kv_token_stride: int = 0,
+                   kv_head_stride: int = 0, num_splits: int = 0) -> tv_attn_desc:
+    return tv_attn_desc(ctypes.sizeof(tv_attn_desc), dtype, B, M, Hq, Hkv, D, soft_len, max_prefix_len,
+                        softmax_scale, kv_token_stride, kv_head_stride, num_splits, 0)
+
+
+def make_accept_desc(*, B: int, T: int, V: int, C: int, rule: int, temperature: float,
+                     logits_row_stride: int = 0) -> tv_accept_desc:
+    return tv_accept_desc(ctypes.sizeof(tv_accept_desc), B, T, V, C, rule, temperature, logits_row_stride,
+                          (ctypes.c_int32 * 2)(0, 0))
+
+
+def tv_attention_workspace_bytes(desc: tv_attn_desc) -> int:
+    n = ctypes.c_size_t(0)
+    rc = lib().tv_attention_workspace_bytes(ctypes.byref(desc), ctypes.byref(n))
+    if rc:
+        raise ConfuVerifyError(rc, "tv_attention_workspace_bytes")
+    return int(n.value)
+
+
+def tv_accept_workspace_bytes(desc: tv_accept_desc) -> int:
+    n = ctypes.c_size_t(0)
+    rc = lib().tv_accept_workspace_bytes(ctypes.byref(desc), ctypes.byref(n))
+    if rc:
+        raise ConfuVerifyError(rc, "tv_accept_workspace_bytes")
+    return int(n.value)
+
+
+def tv_build_mask_host(parent, kind):
+    """numpy int32[M], uint8[M] -> uint64[M, 2] ancestor bit mask (raises on a malformed tree)."""
+    import numpy as np
+    parent = np.ascontiguousarray(parent, dtype=np.int32)
+    kind = np.ascontiguousarray(kind, dtype=np.uint8)
+    bits = np.zeros((len(parent), 2), dtype=np.uint64)
+    rc = lib().tv_build_mask_host(parent.ctypes.data, kind.ctypes.data, len(parent), bits.ctypes.data)
+    if rc:
+        raise ConfuVerifyError(rc, "tv_build_mask_host")
+    return bits
+
+
+def tree_verify_attention(desc: tv_attn_desc, q, k_pool, v_pool, kv_offset, prefix_len, parent, kind,
+                          out, lse, status, workspace, stream=None) -> None:
+    """All tensor arguments are torch CUDA tensors (lse / workspace may be None); see
+    include/confu_verify.h for shapes.  Enqueues on `stream` (default: torch's current stream)."""
+    rc = lib().tree_verify_attention(
+        ctypes.byref(desc), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(kv_offset), _ptr(prefix_len),
+        _ptr(parent), _ptr(kind), _ptr(out), _ptr(lse), _ptr(status), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if rc:
+        raise ConfuVerifyError(rc, "tree_verify_attention")
+
+
+def tree_accept(desc: tv_accept_desc, target_logits, draft_logits, token, parent, uniforms, con_anchor,
+                path, n_accepted, final_token, final_kind, last_node, selected_con, status, workspace,
+                stream=None) -> None:
+    rc = lib().tree_accept(
+        ctypes.byref(desc), _ptr(target_logits), _ptr(draft_logits), _ptr(token), _ptr(parent),
+        _ptr(uniforms), _ptr(con_anchor), _ptr(path), _ptr(n_accepted), _ptr(final_token),
+        _ptr(final_kind), _ptr(last_node), _ptr(selected_con), _ptr(status), _ptr(workspace),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
+    if rc:
+        raise ConfuVerifyError(rc, "tree_accept")

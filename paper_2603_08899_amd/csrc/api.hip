@@ -1,0 +1,231 @@
+// C ABI of libconfu_verify.so: argument checks on host scalars, launch planning, dispatch.
+#include <atomic>
+#include <cstring>
+
+#include "tv_internal.hpp"
+
+namespace tv {
+
+namespace {
+
+int device_cu_count() {
+    static std::atomic<int> cached{0};
+    int n = cached.load(std::memory_order_relaxed);
+    if (n > 0) return n;
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+        prop.multiProcessorCount > 0)
+        n = prop.multiProcessorCount;
+    else
+        n = 256;      // MI355X
+    cached.store(n, std::memory_order_relaxed);
+    return n;
+}
+
+size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+
+int check_attn_desc(const tv_attn_desc* d) {
+    if (!d || d->struct_size != sizeof(tv_attn_desc)) return TV_ERR_INVALID_ARG;
+    if (d->B < 1 || d->M < 1 || d->M > TV_MAX_ROWS || d->Hq < 1 || d->Hkv < 1 || d->Hq % d->Hkv != 0)
+        return TV_ERR_INVALID_ARG;
+    if (d->Hq / d->Hkv > 16) return TV_ERR_INVALID_ARG;
+    if (d->soft_len < 0 || d->max_prefix_len < d->soft_len || d->reserved != 0 || d->num_splits < 0)
+        return TV_ERR_INVALID_ARG;
+    if (!(d->softmax_scale > 0.f)) return TV_ERR_INVALID_ARG;
+    if (d->kv_token_stride < 0 || d->kv_head_stride < 0) return TV_ERR_INVALID_ARG;
+    if (d->dtype == TV_DTYPE_F32) {
+        if (d->D != 64 && d->D != 128) return TV_ERR_UNSUPPORTED;
+    } else if (d->dtype == TV_DTYPE_BF16) {
+        if (d->D != 128) return TV_ERR_UNSUPPORTED;
+    } else {
+        return TV_ERR_INVALID_ARG;
+    }
+    const int64_t hs = d->kv_head_stride ? d->kv_head_stride : d->D;
+    const int64_t ts = d->kv_token_stride ? d->kv_token_stride : (int64_t)d->Hkv * d->D;
+    const int vec = (d->dtype == TV_DTYPE_F32) ? 4 : 8;      // 16-byte loads
+    if (hs < d->D || hs % vec != 0 || ts % vec != 0 || ts < hs) return TV_ERR_INVALID_ARG;
+    return TV_OK;
+}
+
+}  // namespace
+
+int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
+    AttnPlan p{};
+    p.G = d.Hq / d.Hkv;
+    if (d.dtype == TV_DTYPE_F32) {
+        p.row_blocks = (d.M + 15) / 16;
+        p.n_chunks = 1;
+        p.chunk_len = 0;
+        p.total_bytes = 0;
+        *plan = p;
+        return TV_OK;
+    }
+    const int rows = p.G * d.M;
+    p.row_blocks = (rows + 63) / 64;
+    const int64_t base = (int64_t)d.B * d.Hkv * p.row_blocks;
+    const int n_tiles = (d.max_prefix_len + d.M + 31) / 32;
+    int n;
+    if (d.num_splits > 0) {
+        n = d.num_splits;
+    } else {
+        // one workgroup per CU for a single sequence; ragged batches get a few more, smaller ones
+        // so the hardware dispatcher can even them out
+        const int cus = device_cu_count();
+        const int64_t want = (d.B == 1) ? cus : 4 * (int64_t)cus;
+        n = (int)((want + base / 2) / base);
+    }
+    const int max_n = n_tiles / 8 > 1 ? n_tiles / 8 : 1;     // at least two tiles per wave
+    if (n > max_n) n = max_n;
+    if (n > 64) n = 64;
+    if (n < 1) n = 1;
+    p.n_chunks = n;
+    p.chunk_len = 0;
+    if (n > 1) {
+        p.part_o_bytes = up256((size_t)base * n * 64 * 128 * sizeof(float));
+        p.part_ml_bytes = up256((size_t)base * n * 64 * 2 * sizeof(float));
+    }
+    p.total_bytes = p.part_o_bytes + p.part_ml_bytes;
+    *plan = p;
+    return TV_OK;
+}
+
+}  // namespace tv
+
+using namespace tv;
+
+extern "C" {
+
+int tv_version(void) { return 100; }
+
+const char* tv_error_string(int code) {
+    switch (code) {
+        case TV_OK: return "ok";
+        case TV_ERR_INVALID_ARG: return "invalid argument";
+        case TV_ERR_WORKSPACE: return "workspace missing or too small";
+        case TV_ERR_LAUNCH: return "HIP launch error";
+        case TV_ERR_UNSUPPORTED: return "unsupported head dimension or dtype";
+        default: return code < 0 ? "malformed tree" : "unknown error";
+    }
+}
+
+int tv_build_mask_host(const int32_t* parent, const uint8_t* kind, int M, uint64_t* bits) {
+    if (!parent || !kind || M < 1 || M > TV_MAX_ROWS) return TV_ERR_INVALID_ARG;
+    int bad = 0;
+    for (int i = 0; i < M; ++i) {
+        const int p = parent[i];
+        if (p < -1 || p >= i) bad |= TV_STATUS_BAD_PARENT;
+        if (kind[i] != TV_KIND_NODE && kind[i] != TV_KIND_CONTEMPLATE) bad |= TV_STATUS_BAD_KIND;
+        else if (p >= 0 && p < i && kind[i] == TV_KIND_NODE && kind[p] == TV_KIND_CONTEMPLATE)
+            bad |= TV_STATUS_BAD_KIND;
+    }
+    if (bad) return -bad;
+    if (bits) {
+        for (int i = 0; i < M; ++i) {
+            uint64_t w[2] = {0, 0};
+            for (int j = i; j >= 0; j = parent[j]) w[j >> 6] |= (uint64_t)1 << (j & 63);
+            bits[2 * i] = w[0];
+            bits[2 * i + 1] = w[1];
+        }
+    }
+    return TV_OK;
+}
+
+int tv_attention_workspace_bytes(const tv_attn_desc* desc, size_t* out_bytes) {
+    if (!out_bytes) return TV_ERR_INVALID_ARG;
+    const int rc = check_attn_desc(desc);
+    if (rc != TV_OK) return rc;
+    AttnPlan p;
+    plan_attention(*desc, &p);
+    *out_bytes = p.total_bytes;
+    return TV_OK;
+}
+
+int tree_verify_attention(const tv_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
+                          const int64_t* kv_offset, const int32_t* prefix_len, const int32_t* parent,
+                          const uint8_t* kind, void* out, float* lse, int32_t* status, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+    const int rc = check_attn_desc(desc);
+    if (rc != TV_OK) return rc;
+    if (!q || !k_pool || !v_pool || !kv_offset || !prefix_len || !parent || !kind || !out || !status)
+        return TV_ERR_INVALID_ARG;
+    const uintptr_t align_or = (uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)out;
+    if (align_or & 15) return TV_ERR_INVALID_ARG;
+    AttnPlan p;
+    plan_attention(*desc, &p);
+    if (p.total_bytes > 0) {
+        if (!workspace || workspace_bytes < p.total_bytes || ((uintptr_t)workspace & 255)) return TV_ERR_WORKSPACE;
+    }
+    AttnArgs a{};
+    a.q = q; a.k = k_pool; a.v = v_pool;
+    a.kv_offset = kv_offset; a.prefix_len = prefix_len; a.parent = parent; a.kind = kind;
+    a.out = out; a.lse = lse; a.status = status;
+    a.part_o = static_cast<float*>(workspace);
+    a.part_ml = p.total_bytes ? reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + p.part_o_bytes) : nullptr;
+    a.B = desc->B; a.M = desc->M; a.Hq = desc->Hq; a.Hkv = desc->Hkv; a.D = desc->D; a.G = p.G;
+    a.soft_len = desc->soft_len; a.max_prefix_len = desc->max_prefix_len;
+    a.scale = desc->softmax_scale;
+    a.head_stride = desc->kv_head_stride ? desc->kv_head_stride : desc->D;
+    a.tok_stride = desc->kv_token_stride ? desc->kv_token_stride : (int64_t)desc->Hkv * desc->D;
+    a.row_blocks = p.row_blocks; a.n_chunks = p.n_chunks; a.chunk_len = p.chunk_len;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const hipError_t e = (desc->dtype == TV_DTYPE_F32) ? launch_attention_f32(a, s) : launch_attention_bf16(a, s);
+    return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;
+}
+
+static int check_accept_desc(const tv_accept_desc* d) {
+    if (!d || d->struct_size != sizeof(tv_accept_desc)) return TV_ERR_INVALID_ARG;
+    if (d->B < 1 || d->T < 1 || d->T > TV_MAX_ROWS || d->V < 1 || d->C < 0) return TV_ERR_INVALID_ARG;
+    if (d->rule < TV_RULE_GREEDY || d->rule > TV_RULE_DRAFT_WR) return TV_ERR_INVALID_ARG;
+    if (d->rule != TV_RULE_GREEDY && !(d->temperature > 0.f)) return TV_ERR_INVALID_ARG;
+    if (d->logits_row_stride != 0 && d->logits_row_stride < d->V) return TV_ERR_INVALID_ARG;
+    if (d->reserved[0] != 0 || d->reserved[1] != 0) return TV_ERR_INVALID_ARG;
+    if ((int64_t)d->B * d->T > 65535) return TV_ERR_INVALID_ARG;       // grid dimension limits
+    return TV_OK;
+}
+
+int tv_accept_workspace_bytes(const tv_accept_desc* desc, size_t* out_bytes) {
+    if (!out_bytes) return TV_ERR_INVALID_ARG;
+    const int rc = check_accept_desc(desc);
+    if (rc != TV_OK) return rc;
+    AcceptPlan p;
+    plan_accept(*desc, &p);
+    *out_bytes = p.total_bytes;
+    return TV_OK;
+}
+
+int tree_accept(const tv_accept_desc* desc, const float* target_logits, const float* draft_logits,
+                const int32_t* token, const int32_t* parent, const float* uniforms, const int32_t* con_anchor,
+                int32_t* path, int32_t* n_accepted, int32_t* final_token, int32_t* final_kind,
+                int32_t* last_node, int32_t* selected_con, int32_t* status, void* workspace,
+                size_t workspace_bytes, void* hip_stream) {
+    const int rc = check_accept_desc(desc);
+    if (rc != TV_OK) return rc;
+    if (!target_logits || !token || !parent || !path || !n_accepted || !final_token || !final_kind ||
+        !last_node || !status)
+        return TV_ERR_INVALID_ARG;
+    const bool draft_rule = (desc->rule == TV_RULE_DRAFT_WOR || desc->rule == TV_RULE_DRAFT_WR);
+    if (draft_rule && !draft_logits) return TV_ERR_INVALID_ARG;
+    if (desc->rule != TV_RULE_GREEDY && !uniforms) return TV_ERR_INVALID_ARG;
+    if (desc->C > 0 && !con_anchor) return TV_ERR_INVALID_ARG;
+    AcceptPlan p;
+    plan_accept(*desc, &p);
+    if (!workspace || workspace_bytes < p.total_bytes || ((uintptr_t)workspace & 255)) return TV_ERR_WORKSPACE;
+    AcceptArgs a{};
+    a.target = target_logits; a.draft = draft_rule ? draft_logits : nullptr;
+    a.token = token; a.parent = parent; a.uniforms = uniforms; a.con_anchor = con_anchor;
+    a.path = path; a.n_accepted = n_accepted; a.final_token = final_token; a.final_kind = final_kind;
+    a.last_node = last_node; a.selected_con = selected_con; a.status = status;
+    unsigned char* w = static_cast<unsigned char*>(workspace);
+    a.stats = reinterpret_cast<RowStat*>(w);
+    a.chain_z = reinterpret_cast<double*>(w + p.stats_bytes);
+    a.accept_bit = reinterpret_cast<int32_t*>(w + p.stats_bytes + p.chain_bytes);
+    a.B = desc->B; a.T = desc->T; a.V = desc->V; a.C = con_anchor ? desc->C : 0; a.rule = desc->rule;
+    a.temperature = desc->temperature;
+    a.row_stride = desc->logits_row_stride ? desc->logits_row_stride : desc->V;
+    a.splits = p.splits; a.split_len = p.split_len; a.n_mat = p.n_mat;
+    const hipError_t e = launch_accept(a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;
+}
+
+}  // extern "C"

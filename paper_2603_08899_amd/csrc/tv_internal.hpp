@@ -1,0 +1,147 @@
+// Internal declarations shared by the translation units of libconfu_verify.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "confu_verify.h"
+
+namespace tv {
+
+constexpr int kWave = 64;            // CDNA wavefront width
+constexpr int kMaxRows = TV_MAX_ROWS;
+constexpr int kMaskWords = 2;        // 64-bit words of ancestor mask per row (M <= 128)
+
+// ---- attention plan: how one call is cut into workgroups -------------------------------------
+struct AttnPlan {
+    int G;                 // query heads per KV head
+    int row_blocks;        // 64-row blocks of the G*M packed rows of one KV head (bf16 path)
+    int n_chunks;          // key ranges the (prefix + new rows) of a sequence are cut into
+    int chunk_len;         // keys per range (multiple of 128 on the bf16 path)
+    size_t part_o_bytes;   // workspace: partial outputs
+    size_t part_ml_bytes;  // workspace: partial (max, sum) pairs
+    size_t total_bytes;
+};
+
+int plan_attention(const tv_attn_desc& d, AttnPlan* plan);
+
+struct AttnArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    const int64_t* kv_offset;
+    const int32_t* prefix_len;
+    const int32_t* parent;
+    const uint8_t* kind;
+    void* out;
+    float* lse;
+    int32_t* status;
+    float* part_o;
+    float* part_ml;
+    int B, M, Hq, Hkv, D, G;
+    int soft_len, max_prefix_len;
+    float scale;
+    int64_t tok_stride, head_stride;   // elements
+    int row_blocks, n_chunks, chunk_len;
+};
+
+hipError_t launch_attention_f32(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s);
+
+// ---- acceptance ---------------------------------------------------------------------------------
+struct RowStat {          // softmax statistics of one range of one logits row
+    float  max_logit;     // max z over the range
+    int    argmax;        // lowest index attaining it
+    double sum_exp;       // sum exp((z - max_logit) / temperature) over the range
+};
+
+struct AcceptPlan {
+    int splits;           // ranges a logits row is cut into for the statistics pass
+    int split_len;        // elements per range (multiple of 4)
+    int n_mat;            // 1 (target only) or 2 (target and draft)
+    size_t stats_bytes, chain_bytes, bits_bytes, total_bytes;
+};
+
+int plan_accept(const tv_accept_desc& d, AcceptPlan* plan);
+
+struct AcceptArgs {
+    const float* target;
+    const float* draft;
+    const int32_t* token;
+    const int32_t* parent;
+    const float* uniforms;
+    const int32_t* con_anchor;
+    int32_t* path;
+    int32_t* n_accepted;
+    int32_t* final_token;
+    int32_t* final_kind;
+    int32_t* last_node;
+    int32_t* selected_con;
+    int32_t* status;
+    RowStat* stats;       // [B][n_mat][T][splits]
+    double*  chain_z;     // [B][T]: normaliser of the corrected law after rejecting child c
+    int32_t* accept_bit;  // [B][T]
+    int B, T, V, C, rule;
+    float temperature;
+    int64_t row_stride;
+    int splits, split_len, n_mat;
+};
+
+hipError_t launch_accept(const AcceptArgs& a, hipStream_t s);
+
+// ---- small device helpers -------------------------------------------------------------------------
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, kWave));
+    return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
+    return x;
+}
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
+    return x;
+}
+
+// Validates one sequence's parent/kind arrays (already in LDS) with the whole workgroup and
+// returns the TV_STATUS_* bits to every thread.  `flag` is one LDS word.
+__device__ __forceinline__ int validate_tree(const int* parent, const unsigned char* kind, int M,
+                                             int* flag) {
+    if (threadIdx.x == 0) *flag = 0;
+    __syncthreads();
+    for (int i = threadIdx.x; i < M; i += blockDim.x) {
+        int bad = 0;
+        const int p = parent[i];
+        if (p < -1 || p >= i) bad |= TV_STATUS_BAD_PARENT;
+        if (kind) {
+            const int ki = kind[i];
+            if (ki != TV_KIND_NODE && ki != TV_KIND_CONTEMPLATE) bad |= TV_STATUS_BAD_KIND;
+            if (p >= 0 && p < i && ki == TV_KIND_NODE && kind[p] == TV_KIND_CONTEMPLATE) bad |= TV_STATUS_BAD_KIND;
+        } else if (i > 0 && p < 0) {
+            bad |= TV_STATUS_BAD_PARENT;       // acceptance trees have exactly one root
+        }
+        if (bad) atomicOr(flag, bad);
+    }
+    __syncthreads();
+    return *flag;
+}
+
+// Ancestor-closure mask of row i: bit j set iff j is i or one of its ancestors.  parent[] must
+// have passed validate_tree (parent[j] < j), so the walk ends within M steps.
+__device__ __forceinline__ void ancestor_bits(const int* parent, int i, unsigned long long* w0,
+                                              unsigned long long* w1) {
+    unsigned long long a = 0, b = 0;
+    int j = i;
+    while (j >= 0) {
+        if (j < 64) a |= 1ull << j; else b |= 1ull << (j - 64);
+        j = parent[j];
+    }
+    *w0 = a;
+    *w1 = b;
+}
+
+}  // namespace tv

@@ -159,6 +159,7 @@ def make_accept_inputs(
     con_anchor: Optional[np.ndarray] = None,
     draft_target_corr: float = 0.0,
     proposal_noise_std: float = 1.0,
+    child_boost: float = 0.0,
 ) -> AcceptInputs:
     """parent: int32 [B, T] (or [T]).  Logits ~ N(0, logit_std) in float32.
 
@@ -168,6 +169,9 @@ def make_accept_inputs(
     Without draft logits the children are the top-k entries, best first, of a hidden
     proposal row = target row + N(0, proposal_noise_std) noise.
     `draft_target_corr` rho makes draft = rho*target + sqrt(1-rho^2)*noise.
+    `child_boost` is added, after the tokens are picked, to the target (and draft) logit of every
+    drafted token in its parent's row: a knob that lengthens the accepted walks (Gaussian logits
+    over a large vocabulary are nearly flat, so most walks would stop at the root).
     """
     parent = np.asarray(parent, dtype=np.int32)
     if parent.ndim == 1:
@@ -201,6 +205,10 @@ def make_accept_inputs(
                 picks = top[np.argsort(-prop[top])].tolist()
             for c, x in zip(ch[u], picks):
                 token[b, c] = int(x)
+                if child_boost:
+                    target[b, u, int(x)] += np.float32(child_boost)
+                    if draft is not None:
+                        draft[b, u, int(x)] += np.float32(child_boost)
     uniforms = rng.random((B, 2 * T), dtype=np.float32)
     C = 0 if con_anchor is None else int(np.asarray(con_anchor).shape[-1])
     if con_anchor is not None:

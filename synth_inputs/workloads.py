@@ -96,8 +96,11 @@ def attention_case(index: int, *, layer: int = 0, soft_len: int = 0, peaked: boo
     )
 
 
-def accept_case(index: int, mode: int = 0, *, draft_target_corr: float = 0.0,
+def accept_case(index: int, mode: int = 0, *, draft_target_corr: float = 0.0, child_boost: float = 0.0,
                 V_override: Optional[int] = None) -> tensors.AcceptInputs:
+    """Acceptance inputs of workload `index`.  The defaults are the plain recipe (independent
+    Gaussian logits: most walks stop at the root); `draft_target_corr` and `child_boost` are the
+    realism knobs that bring the accepted length into the range the paper reports (Tables 1-3)."""
     w = WORKLOADS[index]
     temperature, rule = w.accept_modes[mode]
     node_parent = _trees_for(w, w.B)
@@ -106,4 +109,5 @@ def accept_case(index: int, mode: int = 0, *, draft_target_corr: float = 0.0,
     return tensors.make_accept_inputs(
         rng, parent=node_parent, V=int(V_override or w.V), temperature=temperature, rule=rule,
         logit_std=w.logit_std, con_anchor=con_anchor, draft_target_corr=draft_target_corr,
+        child_boost=child_boost,
     )

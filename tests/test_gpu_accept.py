@@ -1,0 +1,137 @@
+"""GPU parity: tree_accept (HIP, through the C ABI) against the fp64 CPU oracle on identical
+seeded inputs.  Paths, counts, kinds and tokens must be bit-exact; a disagreement is tolerated
+only when some comparison along the oracle's walk lies within 1e-6 of its threshold, and such
+cases are counted (harness.compare_accept)."""
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs as si
+from synth_inputs import trees
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+RULES = {"greedy": oracle.RULE_GREEDY, "det": oracle.RULE_DETERMINISTIC, "wor": oracle.RULE_DRAFT_WOR,
+         "wr": oracle.RULE_DRAFT_WR}
+
+
+def _batch(seed, *, B, T, V, rule, temp, corr=0.9, max_depth=6, max_children=4, std=2.0, C=0, tree=None, boost=0.0):
+    rng = np.random.default_rng(seed)
+    parents = np.stack([tree if tree is not None else trees.random_tree(rng, T, max_depth, max_children)
+                        for _ in range(B)])
+    ca = None if C == 0 else rng.integers(0, T, size=(B, C)).astype(np.int32)
+    return si.make_accept_inputs(rng, parent=parents, V=V, temperature=temp, rule=rule, logit_std=std,
+                                 con_anchor=ca, draft_target_corr=corr, proposal_noise_std=1.0, child_boost=boost)
+
+
+def _run_and_compare(inp, **kw):
+    got = H.run_accept(inp, **kw)
+    exact, near = H.compare_accept(inp, got)
+    print(f"[accept] B={inp.B} T={inp.T} V={inp.V} rule={inp.rule} temp={inp.temperature}: "
+          f"{exact} exact, {near} within 1e-6 of a threshold")
+    assert near <= max(1, inp.B // 100)
+    return got
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_tiny_workload(mode):
+    _run_and_compare(si.accept_case(0, mode))
+    _run_and_compare(si.accept_case(0, mode, draft_target_corr=0.9))
+
+
+@pytest.mark.parametrize("rule", ["det", "wor", "wr"])
+@pytest.mark.parametrize("temp", [1.0, 0.7])
+def test_many_small_sequences(rule, temp):
+    """256 independent sequences per call; vocabulary size not a multiple of 4."""
+    inp = _batch(21, B=256, T=24, V=5003, rule=RULES[rule], temp=temp, C=3, boost=7.0)
+    got = _run_and_compare(inp)
+    # the walks must be non-trivial for the test to mean anything
+    assert got["n_accepted"].max() >= 3 and (got["final_kind"] == 1).any() and (got["final_kind"] == 0).any()
+
+
+def test_greedy_many_sequences_and_ties():
+    inp = _batch(22, B=128, T=30, V=777, rule=RULES["greedy"], temp=0.0)
+    inp.target_logits[:, :, 5] = inp.target_logits[:, :, 300] = 50.0      # tie: index 5 must win
+    inp.token[:, 1] = 5
+    got = _run_and_compare(inp)
+    assert np.all(got["n_accepted"] >= 1)
+    inp.token[:, 1] = 300
+    _run_and_compare(inp)
+
+
+@pytest.mark.parametrize("rule", ["det", "wor", "wr"])
+def test_uncorrelated_draft_and_wide_star(rule):
+    """Independent draft/target logits (mostly rejections) and a root with 20 children: long
+    sibling chains."""
+    star = np.array([-1] + [0] * 20 + [1, 1, 2], dtype=np.int32)
+    inp = _batch(23, B=32, T=24, V=4096, rule=RULES[rule], temp=1.0, corr=0.0, tree=star)
+    got = _run_and_compare(inp)
+    assert (got["n_accepted"] == 0).any()
+
+
+def test_root_only_and_chain_trees():
+    for rule in ("greedy", "det", "wor"):
+        temp = 0.0 if rule == "greedy" else 1.0
+        _run_and_compare(_batch(24, B=16, T=1, V=1000, rule=RULES[rule], temp=temp))
+        _run_and_compare(_batch(25, B=16, T=12, V=1000, rule=RULES[rule], temp=temp, tree=trees.chain_tree(12)))
+
+
+def test_identical_draft_and_target_accepts_first_child_chain():
+    inp = _batch(26, B=8, T=40, V=2000, rule=RULES["wor"], temp=1.0, corr=1.0)
+    assert np.array_equal(inp.draft_logits, inp.target_logits)
+    got = _run_and_compare(inp)
+    assert np.all(got["final_kind"] == 0)
+
+
+def test_padded_logit_rows():
+    inp = _batch(27, B=4, T=20, V=3001, rule=RULES["wor"], temp=1.0)
+    _run_and_compare(inp, row_stride=3008)
+    _run_and_compare(inp, row_stride=3003)      # rows not 16-byte aligned: scalar loads
+
+
+def test_bad_trees_and_tokens_are_flagged():
+    import paper_2603_08899_amd as tv
+    inp = _batch(28, B=4, T=10, V=500, rule=RULES["det"], temp=1.0)
+    inp.parent[1, 4] = 6
+    inp.token[2, 3] = 500
+    inp.parent[3, 0] = 0
+    got = H.run_accept(inp)
+    assert got["status"][0] == 0 and got["n_accepted"][0] >= 0
+    assert got["status"][1] & tv.TV_STATUS_BAD_PARENT
+    assert got["status"][2] & tv.TV_STATUS_BAD_TOKEN
+    assert got["status"][3] & tv.TV_STATUS_BAD_PARENT
+    for b in (1, 2, 3):
+        assert got["n_accepted"][b] == -1 and got["final_token"][b] == -1 and np.all(got["path"][b] == -1)
+    ref = H.oracle_accept(inp, 0)
+    assert got["final_token"][0] == ref["final_token"] and np.array_equal(got["path"][0], ref["path"])
+
+
+# ---- the named workloads at full size ------------------------------------------------------------------------
+@pytest.mark.parametrize("index,mode,corr,boost", [
+    (1, 0, 0.0, 0.0), (1, 0, 0.9, 5.0), (2, 0, 0.0, 0.0), (2, 0, 0.0, 5.0), (2, 1, 0.0, 0.0), (2, 1, 0.0, 5.0),
+    (4, 0, 0.0, 0.0), (4, 0, 0.9, 5.0)])
+def test_full_vocabulary_single_sequence(index, mode, corr, boost):
+    """V = 128256 (Llama-3) and 151936 (Qwen-3), T = 60; plain recipe and the longer-walk variant."""
+    got = _run_and_compare(si.accept_case(index, mode, draft_target_corr=corr, child_boost=boost))
+    print("accepted", int(got["n_accepted"][0]))
+
+
+def test_full_vocabulary_batch_of_eight():
+    _run_and_compare(si.accept_case(3, 0))
+    got = _run_and_compare(si.accept_case(3, 0, child_boost=5.0))
+    assert got["n_accepted"].max() >= 2
+
+
+def test_many_uniform_draws_on_one_full_size_tree():
+    """One Llama-3-sized tree, 24 different sets of uniforms (as a batch sharing logits by copy)."""
+    base = si.accept_case(1, 0, draft_target_corr=0.9, child_boost=4.0)
+    B = 6
+    rng = np.random.default_rng(3)
+    inp = si.AcceptInputs(
+        B=B, T=base.T, V=base.V, C=base.C, temperature=base.temperature, rule=base.rule,
+        target_logits=np.repeat(base.target_logits, B, axis=0), draft_logits=np.repeat(base.draft_logits, B, axis=0),
+        token=np.repeat(base.token, B, axis=0), parent=np.repeat(base.parent, B, axis=0),
+        uniforms=rng.random((B, 2 * base.T), dtype=np.float32), con_anchor=np.repeat(base.con_anchor, B, axis=0))
+    got = _run_and_compare(inp)
+    assert len(set(got["final_token"].tolist())) > 1

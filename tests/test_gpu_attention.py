@@ -1,0 +1,254 @@
+"""GPU parity: tree_verify_attention (HIP, through the C ABI) against the fp64 CPU oracle on
+identical seeded inputs.  Tolerances (max-abs on the attention output): 1e-5 on the fp32 path,
+2e-2 on the bf16 path; the bf16 cases also bound the error relative to the largest oracle
+output, because the 1/sqrt(D)-scaled draws give outputs far smaller than 2e-2."""
+import numpy as np
+import pytest
+
+import oracle
+import synth_inputs as si
+from synth_inputs import trees
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+# bf16 output rounding is 2^-9 relative to the value; inputs are exact; P is rounded to bf16 before
+# the PV product (2^-9 relative per weight, averaging down over many keys)
+REL_TOL_BF16 = 1.5e-2
+
+
+def _check(inp, out, lse, status, *, seqs=None, rel=True):
+    worst = 0.0
+    for b in (range(inp.B) if seqs is None else seqs):
+        assert status[b] == 0
+        ref, ref_lse = H.oracle_attention(inp, b)
+        err = np.abs(out[b] - ref).max()
+        assert np.isfinite(out[b]).all()
+        assert err <= TOL[inp.dtype], f"seq {b}: max-abs {err:.3e}"
+        if inp.dtype == "bf16" and rel:
+            assert err <= REL_TOL_BF16 * np.abs(ref).max(), f"seq {b}: {err:.3e} vs scale {np.abs(ref).max():.3e}"
+        if lse is not None:
+            lerr = np.abs(lse[b] - ref_lse).max()
+            assert lerr <= (1e-5 * max(1.0, np.abs(ref_lse).max()) if inp.dtype == "f32" else 2e-2), f"lse err {lerr:.3e}"
+        worst = max(worst, err)
+    return worst
+
+
+def _case(seed, *, dtype, Hq, Hkv, D, P, T, C=4, s=0, layout="appended", q_std=1.0, kv_std=1.0, B=1,
+          max_depth=8, max_children=8, pad=0):
+    rng = np.random.default_rng(seed)
+    par, kin = [], []
+    for b in range(B):
+        pn = trees.random_tree(rng, T, max_depth, max_children)
+        if layout == "interleaved":
+            p, k, _, _ = trees.interleave_contemplates_per_node(pn)
+        else:
+            p, k, _ = trees.append_contemplates_chained(pn, C, anchor=int(rng.integers(0, T)))
+        par.append(p)
+        kin.append(k)
+    return si.make_attention_inputs(rng, dtype=dtype, Hq=Hq, Hkv=Hkv, D=D, prefix_len=P, parent=np.stack(par),
+                                    kind=np.stack(kin), soft_len=s, q_std=q_std, kv_std=kv_std,
+                                    pool_pad_tokens=pad)
+
+
+# ---- fp32 path ----------------------------------------------------------------------------------------
+@pytest.mark.parametrize("s", [0, 16])
+def test_tiny_fp32_workload(s):
+    inp = si.attention_case(0, soft_len=s)
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st)
+
+
+@pytest.mark.parametrize("D,Hq,Hkv,M_T,P", [(64, 8, 2, 29, 77), (128, 6, 2, 17, 130), (64, 4, 4, 60, 0),
+                                             (128, 3, 1, 1, 5)])
+def test_fp32_shapes(D, Hq, Hkv, M_T, P):
+    inp = _case(5, dtype="f32", Hq=Hq, Hkv=Hkv, D=D, P=P, T=M_T, C=3, s=min(P, 3))
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st)
+
+
+def test_fp32_paper_layout_two_rows_per_node():
+    inp = _case(6, dtype="f32", Hq=8, Hkv=2, D=64, P=100, T=30, layout="interleaved", s=16)
+    assert inp.M == 60
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st)
+
+
+# ---- bf16 MFMA path -------------------------------------------------------------------------------------
+@pytest.mark.parametrize("Hq,Hkv,T,C,P,s", [
+    (8, 2, 60, 4, 300, 0),        # G=4, M=64: one query head per row block, ragged last tile
+    (6, 2, 60, 4, 517, 16),       # G=3: three row blocks
+    (8, 2, 33, 4, 200, 5),        # G*M = 148: ragged last row block, heads straddle blocks
+    (4, 1, 7, 2, 64, 0),          # 36 packed rows in one block
+    (8, 8, 20, 1, 1000, 40),      # G=1 (multi-head attention), soft prompts longer than a tile
+    (16, 1, 5, 3, 96, 0),         # G=16
+])
+@pytest.mark.parametrize("peaked", [False, True])
+def test_bf16_shapes(Hq, Hkv, T, C, P, s, peaked):
+    std = 1.0 if peaked else 1.0 / np.sqrt(128)
+    inp = _case(11, dtype="bf16", Hq=Hq, Hkv=Hkv, D=128, P=P, T=T, C=C, s=s, q_std=std, kv_std=std)
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st)
+
+
+def test_bf16_paper_layout_120_rows_and_soft_prompts():
+    """One contemplate row per node (2T = 120 rows, two mask words) and s = 16 soft-prompt slots."""
+    inp = _case(12, dtype="bf16", Hq=8, Hkv=2, D=128, P=700, T=60, layout="interleaved", s=16)
+    assert inp.M == 120
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st)
+    inp = _case(13, dtype="bf16", Hq=4, Hkv=2, D=128, P=90, T=64, layout="interleaved", s=16)
+    assert inp.M == 128
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st)
+
+
+@pytest.mark.parametrize("P", [0, 1, 31, 32, 33, 160])
+@pytest.mark.parametrize("splits", [0, 1, 2, 5])
+def test_bf16_short_prefixes_and_forced_splits(P, splits):
+    inp = _case(14 + P, dtype="bf16", Hq=8, Hkv=2, D=128, P=P, T=60, C=4, q_std=1.0, kv_std=1.0)
+    out, lse, st = H.run_attention(inp, num_splits=splits)
+    _check(inp, out, lse, st)
+
+
+def test_bf16_split_counts_agree_closely():
+    inp = _case(15, dtype="bf16", Hq=8, Hkv=2, D=128, P=2048, T=60, C=4, q_std=1.0, kv_std=1.0)
+    o1, l1, _ = H.run_attention(inp, num_splits=1)
+    for n in (2, 3, 8, 16):
+        on, ln, st = H.run_attention(inp, num_splits=n)
+        _check(inp, on, ln, st)
+        assert np.abs(on - o1).max() <= 2e-2
+
+
+def test_bf16_ragged_batch_with_poisoned_padding():
+    """Sequences of different length in one pool; the unused rows between them hold huge values,
+    so any read past a sequence's last row shows up in the output."""
+    inp = _case(16, dtype="bf16", Hq=8, Hkv=2, D=128, P=[70, 1, 333, 0, 129], T=20, C=3, B=5, pad=3,
+                q_std=1.0, kv_std=1.0)
+    big = si.f32_to_bf16_bits(np.full((3, 2, 128), 3e38, np.float32))
+    for b in range(inp.B):
+        end = int(inp.kv_offset[b]) + int(inp.prefix_len[b]) + inp.M
+        inp.k_pool[end:end + 3] = big
+        inp.v_pool[end:end + 3] = big
+    for splits in (0, 1, 3):
+        out, lse, st = H.run_attention(inp, num_splits=splits)
+        _check(inp, out, lse, st)
+
+
+def test_bf16_invisible_keys_do_not_change_the_output_bitwise():
+    inp = _case(17, dtype="bf16", Hq=8, Hkv=2, D=128, P=100, T=30, C=2, s=8, q_std=1.0, kv_std=1.0)
+    base, _, _ = H.run_attention(inp, num_splits=2)
+    vis = oracle.visibility_matrix(inp.parent[0], inp.kind[0], 100, 8)
+    rng = np.random.default_rng(0)
+    # change the soft-prompt slots: node rows must not move at all, contemplate rows must
+    k2 = inp.k_pool.copy()
+    v2 = inp.v_pool.copy()
+    k2[:8] = si.f32_to_bf16_bits(rng.standard_normal((8, 2, 128)).astype(np.float32) * 4)
+    v2[:8] = si.f32_to_bf16_bits(rng.standard_normal((8, 2, 128)).astype(np.float32) * 4)
+    inp2 = si.AttnInputs(**{**inp.__dict__, "k_pool": k2, "v_pool": v2})
+    out2, _, _ = H.run_attention(inp2, num_splits=2)
+    nodes = np.flatnonzero(inp.kind[0] == 0)
+    cons = np.flatnonzero(inp.kind[0] == 1)
+    assert np.array_equal(out2[0, nodes], base[0, nodes])
+    assert not np.array_equal(out2[0, cons], base[0, cons])
+    # change one leaf's K/V: only that row may move
+    leaf = max(i for i in nodes if not any(inp.parent[0][j] == i for j in range(inp.M)))
+    k3, v3 = inp.k_pool.copy(), inp.v_pool.copy()
+    k3[100 + leaf] = si.f32_to_bf16_bits(rng.standard_normal((2, 128)).astype(np.float32) * 4)
+    v3[100 + leaf] = si.f32_to_bf16_bits(rng.standard_normal((2, 128)).astype(np.float32) * 4)
+    out3, _, _ = H.run_attention(si.AttnInputs(**{**inp.__dict__, "k_pool": k3, "v_pool": v3}), num_splits=2)
+    others = [i for i in range(inp.M) if vis[i, 100 + leaf] == 0]
+    assert np.array_equal(out3[0, others], base[0, others])
+    assert not np.array_equal(out3[0, leaf], base[0, leaf])
+
+
+def test_results_are_run_to_run_identical():
+    inp = _case(18, dtype="bf16", Hq=8, Hkv=2, D=128, P=900, T=60, C=4, q_std=1.0, kv_std=1.0)
+    a, la, _ = H.run_attention(inp)
+    b, lb, _ = H.run_attention(inp)
+    assert np.array_equal(a, b) and np.array_equal(la, lb)
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
+def test_malformed_sequences_are_flagged_and_zeroed(dtype, D):
+    import paper_2603_08899_amd as tv
+    inp = _case(19, dtype=dtype, Hq=4, Hkv=2, D=D, P=[50, 60, 70, 80], T=10, C=2, B=4, q_std=1.0, kv_std=1.0)
+    inp.parent[1, 5] = 7                 # forward reference
+    inp.kind[2, 3] = 1                   # a draft node now hangs off a contemplate row (if it has children)
+    kids = [j for j in range(inp.M) if inp.parent[2, j] == 3 and inp.kind[2, j] == 0]
+    for splits in (1, 2):
+        out, lse, st = H.run_attention(inp, num_splits=splits, max_prefix_len=75)   # sequence 3 exceeds the bound
+        assert st[0] == 0
+        assert st[1] & tv.TV_STATUS_BAD_PARENT
+        assert (st[2] & tv.TV_STATUS_BAD_KIND) if kids else st[2] == 0
+        assert st[3] & tv.TV_STATUS_BAD_PREFIX
+        for b in (1, 3):
+            assert np.all(out[b] == 0)
+        _check(inp, out, lse, st, seqs=[0])
+
+
+# ---- the named workloads at full size -----------------------------------------------------------------------
+@pytest.mark.parametrize("index,peaked", [(1, False), (1, True), (2, False), (2, True)])
+def test_full_size_single_sequence_workloads(index, peaked):
+    """Llama-3.2-3B-shaped (G=3, P=2048) and Llama-3.1-8B-shaped (G=4, P=4096) layers, all outputs."""
+    inp = si.attention_case(index, peaked=peaked)
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st)
+
+
+def test_full_size_long_context_sampled_heads():
+    """Qwen3-4B-shaped, P=16384: every row of four query heads (one per distinct KV head)."""
+    inp = si.attention_case(4, peaked=True)
+    out, _, st = H.run_attention(inp, want_lse=False)
+    assert st[0] == 0
+    rows = range(inp.M)
+    ref = H.oracle_attention_rows(inp, 0, rows, heads=[0, 9, 18, 31])
+    for (i, h), r in ref.items():
+        assert np.abs(out[0, i, h] - r).max() <= 2e-2
+        assert np.abs(out[0, i, h] - r).max() <= REL_TOL_BF16 * np.abs(r).max() + 1e-4
+
+
+def test_full_size_ragged_batch_sampled_heads():
+    """Eight sequences, prefix lengths 512..8192, one pool: two heads of every sequence."""
+    inp = si.attention_case(3, peaked=True)
+    out, _, st = H.run_attention(inp, want_lse=False)
+    assert np.all(st == 0)
+    for b in range(inp.B):
+        ref = H.oracle_attention_rows(inp, b, range(inp.M), heads=[(5 * b) % 32, 31 - b])
+        for (i, h), r in ref.items():
+            assert np.abs(out[b, i, h] - r).max() <= 2e-2
+            assert np.abs(out[b, i, h] - r).max() <= REL_TOL_BF16 * np.abs(r).max() + 1e-4
+
+
+def test_layers_from_one_pool_back_to_back():
+    """Several layers' K/V in one allocation, one launch per layer on one stream without host
+    synchronisation in between (the 32-layer benchmark configuration, shortened)."""
+    import torch
+    import paper_2603_08899_amd as tv
+    w = si.WORKLOADS[2]
+    layers = [si.attention_case(2, layer=l, peaked=True) for l in range(3)]
+    L0 = layers[0]
+    rows = L0.k_pool.shape[0]
+    kpool = torch.stack([H.to_device_storage(x.k_pool, "bf16") for x in layers])
+    vpool = torch.stack([H.to_device_storage(x.v_pool, "bf16") for x in layers])
+    qs = [H.to_device_storage(x.q, "bf16") for x in layers]
+    desc = tv.make_attn_desc(dtype=tv.TV_DTYPE_BF16, B=1, M=L0.M, Hq=w.Hq, Hkv=w.Hkv, D=128, soft_len=0,
+                             max_prefix_len=int(L0.prefix_len[0]), softmax_scale=L0.scale)
+    ws = torch.empty(max(tv.tv_attention_workspace_bytes(desc), 256), device="cuda", dtype=torch.uint8)
+    kv_off = torch.zeros(1, dtype=torch.int64, device="cuda")
+    plen = torch.from_numpy(L0.prefix_len).cuda()
+    parent = torch.from_numpy(L0.parent).cuda()
+    kind = torch.from_numpy(L0.kind).cuda()
+    outs = [torch.empty_like(qs[0]) for _ in layers]
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for l in range(len(layers)):
+        tv.tree_verify_attention(desc, qs[l], kpool[l], vpool[l], kv_off, plen, parent, kind, outs[l], None,
+                                 status, ws)
+    torch.cuda.synchronize()
+    assert rows == kpool.shape[1]
+    for l, inp in enumerate(layers):
+        ref = H.oracle_attention(inp, 0, want_lse=False)
+        got = outs[l].float().cpu().numpy()[0].astype(np.float64)
+        assert np.abs(got - ref).max() <= 2e-2
+        assert np.abs(got - ref).max() <= REL_TOL_BF16 * np.abs(ref).max()

@@ -1,0 +1,115 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares,
+its host helpers agree with the oracle, and host-detectable errors are reported without a GPU."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2603_08899_amd as tv
+from synth_inputs import trees
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "confu_verify.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"^\s*(?:int|const char\*)\s+(\w+)\s*\(", text, flags=re.M))
+    return names
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    l = tv.lib()
+    declared = _declared_functions()
+    assert declared == set(tv.EXPORTED_SYMBOLS), declared ^ set(tv.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(l, name) is not None
+    assert l.tv_version() >= 100
+    assert l.tv_error_string(0) == b"ok"
+
+
+def test_struct_layouts_match_header_sizes():
+    # the library checks struct_size itself: a wrong python-side layout is rejected
+    d = tv.make_attn_desc(dtype=tv.TV_DTYPE_BF16, B=1, M=64, Hq=32, Hkv=8, D=128, soft_len=0,
+                          max_prefix_len=4096, softmax_scale=0.1)
+    assert tv.tv_attention_workspace_bytes(d) > 0
+    d.struct_size += 4
+    with pytest.raises(tv.ConfuVerifyError):
+        tv.tv_attention_workspace_bytes(d)
+    a = tv.make_accept_desc(B=1, T=60, V=128256, C=4, rule=tv.TV_RULE_DRAFT_WOR, temperature=1.0)
+    assert tv.tv_accept_workspace_bytes(a) > 0
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_host_mask_builder_matches_oracle_ancestor_matrix(seed):
+    rng = np.random.default_rng(seed)
+    T = int(rng.integers(1, 61))
+    pn = trees.random_tree(rng, T, 8, 8)
+    if seed % 2:
+        parent, kind, _, _ = trees.interleave_contemplates_per_node(pn)
+    else:
+        parent, kind, _ = trees.append_contemplates_chained(pn, 4, anchor=int(rng.integers(0, T)))
+    bits = tv.tv_build_mask_host(parent, kind)
+    anc = oracle.ancestor_matrix(parent, kind)
+    M = len(parent)
+    for i in range(M):
+        for j in range(M):
+            assert ((int(bits[i, j // 64]) >> (j % 64)) & 1) == anc[i, j]
+
+
+@pytest.mark.parametrize("parent,kind,bit", [
+    ([-1, 1], [0, 0], tv.TV_STATUS_BAD_PARENT),
+    ([-1, 2, 0], [0, 0, 0], tv.TV_STATUS_BAD_PARENT),
+    ([-1, 0, 1], [0, 1, 0], tv.TV_STATUS_BAD_KIND),
+    ([-1, 0], [0, 3], tv.TV_STATUS_BAD_KIND),
+])
+def test_host_mask_builder_rejects_what_the_oracle_rejects(parent, kind, bit):
+    with pytest.raises(tv.ConfuVerifyError) as e:
+        tv.tv_build_mask_host(parent, kind)
+    assert e.value.code == -bit
+    with pytest.raises(oracle.OracleError):
+        oracle.ancestor_matrix(parent, kind)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(M=0), dict(M=129), dict(Hq=7), dict(D=96), dict(softmax_scale=0.0), dict(soft_len=-1),
+    dict(max_prefix_len=3, soft_len=16), dict(kv_head_stride=100), dict(kv_token_stride=1028), dict(B=0),
+    dict(dtype=5),
+])
+def test_attention_descriptor_errors_on_host(kw):
+    base = dict(dtype=tv.TV_DTYPE_BF16, B=1, M=64, Hq=32, Hkv=8, D=128, soft_len=0, max_prefix_len=4096,
+                softmax_scale=0.1)
+    base.update(kw)
+    with pytest.raises(tv.ConfuVerifyError) as e:
+        tv.tv_attention_workspace_bytes(tv.make_attn_desc(**base))
+    assert e.value.code in (tv.TV_ERR_INVALID_ARG, tv.TV_ERR_UNSUPPORTED)
+
+
+@pytest.mark.parametrize("kw", [dict(T=0), dict(T=129), dict(V=0), dict(rule=9), dict(temperature=0.0),
+                                dict(logits_row_stride=5)])
+def test_accept_descriptor_errors_on_host(kw):
+    base = dict(B=1, T=60, V=1000, C=0, rule=tv.TV_RULE_DETERMINISTIC, temperature=1.0)
+    base.update(kw)
+    with pytest.raises(tv.ConfuVerifyError):
+        tv.tv_accept_workspace_bytes(tv.make_accept_desc(**base))
+
+
+def test_null_pointers_are_rejected_before_any_launch():
+    # no device work is enqueued: the checks run on host scalars and pointer values only
+    d = tv.make_attn_desc(dtype=tv.TV_DTYPE_F32, B=1, M=4, Hq=2, Hkv=1, D=64, soft_len=0,
+                          max_prefix_len=8, softmax_scale=0.1)
+    rc = tv.lib().tree_verify_attention(ctypes.byref(d), *([None] * 11), 0, None)
+    assert rc == tv.TV_ERR_INVALID_ARG
+    a = tv.make_accept_desc(B=1, T=4, V=10, C=0, rule=tv.TV_RULE_GREEDY, temperature=0.0)
+    rc = tv.lib().tree_accept(ctypes.byref(a), *([None] * 14), 0, None)
+    assert rc == tv.TV_ERR_INVALID_ARG
+
+
+def test_workspace_grows_with_split_count():
+    mk = lambda n: tv.tv_attention_workspace_bytes(tv.make_attn_desc(
+        dtype=tv.TV_DTYPE_BF16, B=1, M=64, Hq=32, Hkv=8, D=128, soft_len=0, max_prefix_len=4096,
+        softmax_scale=0.1, num_splits=n))
+    assert mk(1) == 0 and mk(2) > 0 and mk(4) == 2 * mk(2)
