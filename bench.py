@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the tree-verification hot path on one MI355X.
+
+A step is one verification pass of the Llama-3.1-8B-shaped workload: tree_verify_attention
+for all 32 layers back to back from one KV pool (batch 1, 32 query / 8 KV heads, head dim 128,
+prefix 4096, 60 draft nodes + 4 contemplate rows, bf16) followed by one tree_accept over a
+128256-entry vocabulary at temperature 1.0.  Inputs are seeded and synthetic and resident in
+HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-graph] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+WORKLOAD_INDEX = 2              # llama3.1-8b-32layers
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
+    ap.add_argument("--splits", type=int, default=0, help="key ranges per sequence (0 = library decides)")
+    ap.add_argument("--wg-row-blocks", type=int, default=0, help="row blocks sharing a key stream (0 = library decides)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the path has no multi-GPU part); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2603_08899_amd as tv
+    import synth_inputs as si
+    from tests import harness as H
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = si.WORKLOADS[WORKLOAD_INDEX]
+    L = args.layers or w.n_layers
+
+    # ---- inputs, resident in HBM -------------------------------------------------------------------
+    t0 = time.time()
+    layer0 = si.attention_case(WORKLOAD_INDEX, layer=0)
+    M, P = layer0.M, int(layer0.prefix_len[0])
+    rows = P + M
+    kpool = torch.empty((L, rows, w.Hkv, w.D), device="cuda", dtype=torch.bfloat16)
+    vpool = torch.empty_like(kpool)
+    qs = torch.empty((L, 1, M, w.Hq, w.D), device="cuda", dtype=torch.bfloat16)
+    for l in range(L):
+        x = layer0 if l == 0 else si.attention_case(WORKLOAD_INDEX, layer=l)
+        kpool[l].copy_(H.to_device_storage(x.k_pool, "bf16"))
+        vpool[l].copy_(H.to_device_storage(x.v_pool, "bf16"))
+        qs[l].copy_(H.to_device_storage(x.q, "bf16"))
+    outs = torch.empty_like(qs)
+    kv_off = torch.zeros(1, dtype=torch.int64, device="cuda")
+    plen = torch.from_numpy(layer0.prefix_len).cuda()
+    parent = torch.from_numpy(layer0.parent).cuda()
+    kind = torch.from_numpy(layer0.kind).cuda()
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    adesc = tv.make_attn_desc(dtype=tv.TV_DTYPE_BF16, B=1, M=M, Hq=w.Hq, Hkv=w.Hkv, D=w.D, soft_len=0,
+                              max_prefix_len=P, softmax_scale=layer0.scale, num_splits=args.splits,
+                              wg_row_blocks=args.wg_row_blocks)
+    aws = torch.empty(max(tv.tv_attention_workspace_bytes(adesc), 256), device="cuda", dtype=torch.uint8)
+
+    acc = si.accept_case(WORKLOAD_INDEX, 1, child_boost=5.0)      # temperature 1.0, no draft logits
+    cdesc = tv.make_accept_desc(B=1, T=acc.T, V=acc.V, C=acc.C, rule=acc.rule, temperature=acc.temperature)
+    tl = torch.from_numpy(acc.target_logits).cuda()
+    token = torch.from_numpy(acc.token).cuda()
+    aparent = torch.from_numpy(acc.parent).cuda()
+    un = torch.from_numpy(acc.uniforms).cuda()
+    ca = torch.from_numpy(acc.con_anchor).cuda()
+    i32 = dict(device="cuda", dtype=torch.int32)
+    path = torch.zeros((1, acc.T), **i32)
+    o_n, o_tok, o_kind, o_last, o_con, o_st = (torch.zeros(1, **i32) for _ in range(6))
+    cws = torch.empty(max(tv.tv_accept_workspace_bytes(cdesc), 256), device="cuda", dtype=torch.uint8)
+    gacc = si.accept_case(WORKLOAD_INDEX, 0, child_boost=5.0)     # temperature 0
+    gdesc = tv.make_accept_desc(B=1, T=gacc.T, V=gacc.V, C=gacc.C, rule=gacc.rule, temperature=0.0)
+    gtl = torch.from_numpy(gacc.target_logits).cuda()
+    gtoken = torch.from_numpy(gacc.token).cuda()
+    setup_s = time.time() - t0
+
+    def attention_layers():
+        for l in range(L):
+            tv.tree_verify_attention(adesc, qs[l], kpool[l], vpool[l], kv_off, plen, parent, kind, outs[l], None,
+                                     status, aws)
+
+    def accept():
+        tv.tree_accept(cdesc, tl, None, token, aparent, un, ca, path, o_n, o_tok, o_kind, o_last, o_con, o_st, cws)
+
+    def accept_greedy():
+        tv.tree_accept(gdesc, gtl, None, gtoken, aparent, None, ca, path, o_n, o_tok, o_kind, o_last, o_con, o_st, cws)
+
+    def full_step():
+        attention_layers()
+        accept()
+
+    stream = torch.cuda.Stream()          # default priority
+
+    def timed(fn, steps, warmup):
+        """Average milliseconds per call of fn over `steps` calls, HIP events on the launch stream."""
+        with torch.cuda.stream(stream):
+            runner = fn
+            if not args.no_graph:
+                fn()                      # first call sets kernel attributes outside the capture
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    fn()
+                runner = g.replay
+            for _ in range(warmup):
+                runner()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(steps):
+                runner()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / steps
+
+    ms_step = timed(full_step, args.steps, args.warmup)
+    ms_attn = timed(attention_layers, args.steps, args.warmup)
+    ms_accept = timed(accept, args.steps * 4, args.warmup)
+    ms_greedy = timed(accept_greedy, args.steps * 4, args.warmup)
+    us_layer = ms_attn * 1e3 / L
+
+    # ---- sampled parity on what was just computed (layer 0, two heads; the acceptance result) -----------
+    torch.cuda.synchronize()
+    got0 = outs[0].float().cpu().numpy()[0].astype(np.float64)
+    ref = H.oracle_attention_rows(layer0, 0, range(M), heads=[0, 21])
+    attn_err = max(float(np.abs(got0[i, h] - r).max()) for (i, h), r in ref.items())
+    with torch.cuda.stream(stream):
+        accept()
+    torch.cuda.synchronize()
+    aref = H.oracle_accept(acc, 0)
+    accept_ok = (int(o_tok[0]) == aref["final_token"] and int(o_n[0]) == aref["n_accepted"]
+                 and np.array_equal(path.cpu().numpy()[0], aref["path"]))
+
+    # ---- roofline of the dominant kernel (attention) ------------------------------------------------------
+    bytes_layer = 2 * (P + M) * w.Hkv * w.D * 2 + 2 * M * w.Hq * w.D * 2
+    flops_layer = 4 * M * w.Hq * (P + M) * w.D
+    achieved = bytes_layer / (us_layer * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "kernel": "attn_bf16_kernel (+ combine), per layer launch",
+                "algorithmic_bytes_per_launch": bytes_layer,
+                "mfma_frac_of_bf16_peak": round(flops_layer / (us_layer * 1e-6) / 2.5e15, 4)}
+
+    # ---- CPU oracle on the host cores, bounded sample: one of the 32 layers + one acceptance ---------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        q64, k64, v64 = layer0.q_f64(0), layer0.k_f64(0), layer0.v_f64(0)
+        t1 = time.time()
+        oracle.tree_attention(q64, k64, v64, layer0.parent[0], layer0.kind[0], soft_len=0, scale=layer0.scale)
+        cpu_layer_s = time.time() - t1
+        t1 = time.time()
+        for _ in range(3):
+            H.oracle_accept(acc, 0)
+        cpu_accept_s = (time.time() - t1) / 3
+        cpu = {"value": round(cpu_layer_s * 1e6, 1), "unit": "us/layer", "cores": oracle.num_threads(),
+               "kind": "oracle", "sample": "1 of the 32 layers (fp64, all rows and heads) and 3 tree_accept walks",
+               "tree_accept_steps_per_s": round(1.0 / cpu_accept_s, 2)}
+
+    line = {
+        "metric": "verify-attn us/layer (60 nodes + 4 contemplate rows); tree_accept steps/sec reported alongside",
+        "value": round(us_layer, 3), "unit": "us/layer", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "layers": L, "batch": 1, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "prefix": P,
+                   "tree_nodes": w.T, "contemplate_rows": w.C, "vocab": w.V,
+                   "launch": "eager" if args.no_graph else "hip-graph replay"},
+        "tree_accept_steps_per_s": {"temp1.0_deterministic": round(1e3 / ms_accept, 1),
+                                    "temp0_greedy": round(1e3 / ms_greedy, 1)},
+        "verify_steps_per_s": round(1e3 / ms_step, 2),
+        "attention_tb_per_s": round(achieved / 1e3, 3),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "parity_sample": {"attention_max_abs_err_layer0_heads_0_21": attn_err, "accept_matches_oracle": bool(accept_ok)},
+        "setup_seconds": round(setup_s, 1),
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -102,7 +102,7 @@ typedef struct tv_attn_desc {
     int64_t  kv_token_stride;  /* elements between consecutive rows of the pool; 0 = Hkv*D */
     int64_t  kv_head_stride;   /* elements between KV heads of one row; 0 = D */
     int32_t  num_splits;       /* 0 = library decides how many ranges the keys are cut into */
-    int32_t  reserved;         /* must be 0 */
+    int32_t  wg_row_blocks;    /* bf16 path: 64-row blocks that share one key stream in a workgroup; 0 = library decides, else 1, 2 or 4 */
 } tv_attn_desc;
 
 /* host: writes the workspace size (bytes) tree_verify_attention needs for *desc.

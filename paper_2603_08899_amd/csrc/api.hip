@@ -30,7 +30,8 @@ int check_attn_desc(const tv_attn_desc* d) {
     if (d->B < 1 || d->M < 1 || d->M > TV_MAX_ROWS || d->Hq < 1 || d->Hkv < 1 || d->Hq % d->Hkv != 0)
         return TV_ERR_INVALID_ARG;
     if (d->Hq / d->Hkv > 16) return TV_ERR_INVALID_ARG;
-    if (d->soft_len < 0 || d->max_prefix_len < d->soft_len || d->reserved != 0 || d->num_splits < 0)
+    if (d->soft_len < 0 || d->max_prefix_len < d->soft_len || d->num_splits < 0) return TV_ERR_INVALID_ARG;
+    if (d->wg_row_blocks != 0 && d->wg_row_blocks != 1 && d->wg_row_blocks != 2 && d->wg_row_blocks != 4)
         return TV_ERR_INVALID_ARG;
     if (!(d->softmax_scale > 0.f)) return TV_ERR_INVALID_ARG;
     if (d->kv_token_stride < 0 || d->kv_head_stride < 0) return TV_ERR_INVALID_ARG;
@@ -45,6 +46,9 @@ int check_attn_desc(const tv_attn_desc* d) {
     const int64_t ts = d->kv_token_stride ? d->kv_token_stride : (int64_t)d->Hkv * d->D;
     const int vec = (d->dtype == TV_DTYPE_F32) ? 4 : 8;      // 16-byte loads
     if (hs < d->D || hs % vec != 0 || ts % vec != 0 || ts < hs) return TV_ERR_INVALID_ARG;
+    // byte offsets inside one sequence are formed in 32 bits
+    const int elem = (d->dtype == TV_DTYPE_F32) ? 4 : 2;
+    if (((int64_t)d->max_prefix_len + d->M) * ts * elem >= ((int64_t)1 << 32)) return TV_ERR_INVALID_ARG;
     return TV_OK;
 }
 
@@ -62,8 +66,11 @@ int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
         return TV_OK;
     }
     const int rows = p.G * d.M;
-    p.row_blocks = (rows + 63) / 64;
-    const int64_t base = (int64_t)d.B * d.Hkv * p.row_blocks;
+    const int rb_needed = (rows + 63) / 64;
+    // waves of a workgroup that share one key stream (the rest of the 4 waves split the keys)
+    p.rb_per_wg = d.wg_row_blocks ? d.wg_row_blocks : (rb_needed >= 2 ? 2 : 1);
+    p.row_blocks = (rb_needed + p.rb_per_wg - 1) / p.rb_per_wg * p.rb_per_wg;
+    const int64_t base = (int64_t)d.B * d.Hkv * (p.row_blocks / p.rb_per_wg);
     const int n_tiles = (d.max_prefix_len + d.M + 31) / 32;
     int n;
     if (d.num_splits > 0) {
@@ -82,8 +89,9 @@ int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
     p.n_chunks = n;
     p.chunk_len = 0;
     if (n > 1) {
-        p.part_o_bytes = up256((size_t)base * n * 64 * 128 * sizeof(float));
-        p.part_ml_bytes = up256((size_t)base * n * 64 * 2 * sizeof(float));
+        const size_t blocks = (size_t)d.B * d.Hkv * p.row_blocks * n;
+        p.part_o_bytes = up256(blocks * 64 * 128 * 2);       // bf16
+        p.part_ml_bytes = up256(blocks * 64 * 2 * sizeof(float));
     }
     p.total_bytes = p.part_o_bytes + p.part_ml_bytes;
     *plan = p;
@@ -160,14 +168,15 @@ int tree_verify_attention(const tv_attn_desc* desc, const void* q, const void* k
     a.q = q; a.k = k_pool; a.v = v_pool;
     a.kv_offset = kv_offset; a.prefix_len = prefix_len; a.parent = parent; a.kind = kind;
     a.out = out; a.lse = lse; a.status = status;
-    a.part_o = static_cast<float*>(workspace);
+    a.part_o = workspace;
     a.part_ml = p.total_bytes ? reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + p.part_o_bytes) : nullptr;
     a.B = desc->B; a.M = desc->M; a.Hq = desc->Hq; a.Hkv = desc->Hkv; a.D = desc->D; a.G = p.G;
     a.soft_len = desc->soft_len; a.max_prefix_len = desc->max_prefix_len;
     a.scale = desc->softmax_scale;
+    a.inv_M = 1.0f / (float)desc->M;
     a.head_stride = desc->kv_head_stride ? desc->kv_head_stride : desc->D;
     a.tok_stride = desc->kv_token_stride ? desc->kv_token_stride : (int64_t)desc->Hkv * desc->D;
-    a.row_blocks = p.row_blocks; a.n_chunks = p.n_chunks; a.chunk_len = p.chunk_len;
+    a.row_blocks = p.row_blocks; a.n_chunks = p.n_chunks; a.chunk_len = p.chunk_len; a.rb_per_wg = p.rb_per_wg;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const hipError_t e = (desc->dtype == TV_DTYPE_F32) ? launch_attention_f32(a, s) : launch_attention_bf16(a, s);
     return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;

@@ -1,25 +1,28 @@
 // bf16 tree-verification attention for gfx950 (head dimension 128): MFMA 32x32x16 with fp32
-// accumulation, online softmax, split over the keys with a second small combine kernel.
+// accumulation, online softmax, keys split over workgroups with a small combine kernel.
 //
 // What is computed: Section 2 (tree attention over the draft tree) and Section 3.1 (contemplate
 // rows as extra tree rows; only they may attend to the soft-prompt slots) of the paper.
 //
 // Mapping
 //   - The G = Hq/Hkv query heads of one KV head times the M rows are packed into G*M rows
-//     r = head_in_group*M + row; a workgroup owns 64 consecutive packed rows of one KV head and
-//     one of n_chunks ranges of the sequence's keys.  All four waves work on the same 64 rows;
-//     the keys of the range are dealt to the waves in contiguous runs of 32-key tiles, so K and V
-//     are read from HBM once per row block and each wave streams its own tiles through its own
-//     LDS buffers (no workgroup barrier inside the loop).  The four waves' (max, sum, O) are
-//     merged through LDS at the end.
-//   - Scores are formed transposed, S^T = K Q^T: A = K tile (keys x d) read from LDS, B = Q^T held
-//     in registers for the whole kernel.  In the 32x32 accumulator a lane then holds one query
-//     (column) and 16 keys (rows), which is exactly the B-operand layout of O^T += V^T P^T, so the
-//     probabilities never leave registers; V^T is read with the LDS transpose load.  The softmax
-//     row reductions are in-lane plus one exchange between the wave's halves.
-//   - The mask touches only tiles that overlap the soft-prompt slots or the new rows; all other
-//     tiles run mask-free.  The ancestor mask is two 64-bit words per row, built in the prologue
-//     from the parent array.
+//     r = head_in_group*M + row, cut into row blocks of 64.  A wave owns one row block: Q^T for its
+//     64 rows stays in registers as the MFMA B operand for the whole kernel.
+//   - A workgroup has 4 waves = RB row blocks x NS key streams (RB*NS = 4).  The keys of a sequence
+//     are cut into n_chunks ranges (one per workgroup) and each range into NS contiguous runs of
+//     32-key tiles (one per stream).  The RB waves of a stream consume the same K/V tiles from LDS,
+//     so K/V is fetched RB-times less often than with one row block per workgroup.
+//   - K/V tiles go HBM -> LDS directly (global_load_lds, 16 bytes per lane, no registers), several
+//     tiles ahead, into a ring of stages per stream.  Rows are 256 bytes; bank conflicts are avoided
+//     by an XOR swizzle of the 16-byte segments which is applied on the global-address side.
+//   - Scores are formed transposed, S^T = K Q^T (A = K tile from LDS).  In the 32x32 accumulator a
+//     lane then holds one query (column) and 16 keys (rows): exactly the B-operand layout of
+//     O^T += V^T P^T, so probabilities stay in registers; V^T comes from the LDS transpose load.
+//     Softmax row reductions are in-lane plus one exchange between the wave's halves.
+//   - Only tiles overlapping the soft-prompt slots, the new rows or the tail are masked, with a
+//     32-bit visibility word per (lane, query) derived from the two-word ancestor mask.
+//   - Streams are merged through LDS; with n_chunks > 1 partial (max, sum, O) go to the workspace
+//     and attn_bf16_combine_kernel finishes.
 #include <atomic>
 
 #include "tv_internal.hpp"
@@ -28,34 +31,29 @@ namespace tv {
 
 namespace {
 
-// memory is reinterpreted between these vector types (global <-> LDS <-> MFMA operands)
+// memory is reinterpreted between these vector types (LDS <-> MFMA operands <-> global)
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8), may_alias));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4), may_alias));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4), may_alias));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4), may_alias));
 
 constexpr int kD = 128;
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
-constexpr int kQRows = 64;                 // packed query rows per workgroup
+constexpr int kQRows = 64;                 // packed query rows per wave
 constexpr int kTK = 32;                    // keys per tile
-constexpr int kKStride = 272;              // bytes per K row in LDS (256 + 16: conflict-free 16-byte reads down a column of keys)
-constexpr int kVStride = 288;              // bytes per V row in LDS (256 + 32: conflict-free transposed 8-byte reads)
-constexpr int kKTile = kTK * kKStride;
-constexpr int kVTile = kTK * kVStride;
-constexpr int kStages = 2;
-constexpr int kWaveLds = kStages * (kKTile + kVTile);      // 35840
-constexpr int kOStride = kD + 4;           // floats per row of the merge buffer
-constexpr int kMergeBytes = kWaves * kQRows * kOStride * 4;   // 135168
-constexpr int kStreamBytes = kWaves * kWaveLds;              // 143360
-constexpr int kBigBytes = kStreamBytes > kMergeBytes ? kStreamBytes : kMergeBytes;
+constexpr int kRowBytes = 256;             // one K or V row of one head in LDS
+constexpr int kTileBytes = kTK * kRowBytes;          // 8192: one K tile or one V tile
+constexpr int kStageBytes = 2 * kTileBytes;          // K then V
+constexpr int kRingBytes = 128 * 1024;               // all stages of all streams
+constexpr int kMergeBytes = kWaves * kQRows * kD * 4;         // 131072: the streams' O, merged through LDS
+constexpr int kBigBytes = kMergeBytes > kRingBytes ? kMergeBytes : kRingBytes;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kTau = 8.f;                // the running max is only raised when it lags by more than 2^kTau
 
 struct Bf16Smem {
-    unsigned char big[kBigBytes];          // per-wave K/V stages, later the merge buffer
+    unsigned char big[kBigBytes];          // K/V stage ring, later the merge buffer
     float ml[kWaves][kQRows][2];
     int parent[kMaxRows];
     unsigned char kind[kMaxRows];
@@ -63,7 +61,7 @@ struct Bf16Smem {
 };
 
 __device__ __forceinline__ float cross_half_max(float x) {
-    // lanes l and l^32 exchange: result0 = [x.lo, x.lo], result1 = [x.hi, x.hi]
+    // permlane32_swap(a, b) returns {[a.lo, b.lo], [a.hi, b.hi]}: with a = b = x both halves see both values
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
@@ -72,74 +70,232 @@ __device__ __forceinline__ float cross_half_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// s_waitcnt vmcnt(n) only (gfx9 encoding: vmcnt = bits [3:0] and [15:14], expcnt [6:4], lgkmcnt [11:8])
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | (((N >> 4) & 3) << 14));
+}
+
+// One direct-to-LDS load: every lane fetches 16 bytes from sbase + voff (sbase wave-uniform) and the
+// 64 x 16 bytes land contiguously at LDS byte address lds_addr (wave-uniform), lane l at lds_addr + 16*l.
+// Written as inline assembly on purpose: the loads stay invisible to the compiler's wait-count
+// insertion, which would otherwise put a conservative vmcnt(0) in front of LDS reads and so wait for
+// the tiles that were just requested.  Completion is tracked by hand with wait_vmcnt (these loads
+// retire in order on the vector-memory counter).
+__device__ __forceinline__ void dma16(unsigned lds_addr, unsigned long long sbase, unsigned voff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+// A wave-uniform pointer as a scalar value the assembler operand above accepts (pins it to SGPRs even when
+// the compiler cannot prove uniformity).
+__device__ __forceinline__ unsigned long long scalar_base(const void* p) {
+    const unsigned long long v = (unsigned long long)(uintptr_t)p;
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return ((unsigned long long)hi << 32) | lo;
+}
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+    return (unsigned)(uintptr_t)(const void __attribute__((address_space(3)))*)p;
+}
+
+// Parks an MFMA A/B operand in the accumulation registers (an empty asm with an 'a' constraint): the matrix
+// instructions read operands from there as well as from ordinary VGPRs, and the ordinary ones are needed for
+// the accumulators (kept there so that the softmax arithmetic works on them in place).
+__device__ __forceinline__ void park(bf16x8& x) { asm("" : "+a"(x)); }
+
+// Visibility of the 32 keys of the tile starting at k0 for one query row (bit kk = key k0+kk).
+__device__ __forceinline__ unsigned tile_visibility(int k0, int P, int soft_len, bool is_con,
+                                                    unsigned long long b0, unsigned long long b1) {
+    // cached rows: [soft_len, P) for draft nodes, [0, P) for contemplate rows
+    const int lo = is_con ? 0 : max(0, soft_len - k0);
+    const int hi = min(32, P - k0);
+    unsigned pm = 0;
+    if (hi > 0) {
+        const unsigned below_hi = (hi >= 32) ? 0xffffffffu : ((1u << hi) - 1u);
+        const unsigned below_lo = (lo >= 32) ? 0xffffffffu : ((1u << lo) - 1u);
+        pm = below_hi & ~below_lo;
+    }
+    // new rows: bit (k0 + kk - P) of the ancestor mask
+    const int sh = k0 - P;
+    unsigned nm;
+    if (sh >= 128) nm = 0;
+    else if (sh >= 64) nm = (unsigned)(b1 >> (sh - 64));
+    else if (sh > 0) nm = (unsigned)((b0 >> sh) | (b1 << (64 - sh)));
+    else if (sh == 0) nm = (unsigned)b0;
+    else nm = (sh > -32) ? (unsigned)(b0 << (-sh)) : 0u;
+    return pm | nm;
+}
+
+template <int RB>
 __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
+    constexpr int NS = kWaves / RB;                    // key streams per workgroup
+    constexpr int S = kRingBytes / (NS * kStageBytes); // stages per stream: 2, 4 or 8 (= 2*RB)
+    constexpr int PER = 16 / RB;                       // direct-to-LDS loads per tile per wave
     extern __shared__ __align__(16) unsigned char smem_raw[];
     Bf16Smem& sm = *reinterpret_cast<Bf16Smem*>(smem_raw);
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int ln = lane & 31, hf = lane >> 5;
-    // blockIdx.x = g + Hkv * (rb + row_blocks * chunk): consecutive workgroups (hence the XCDs they are
-    // dealt to round-robin) differ in KV head first, so each XCD's L2 sees few heads
+    const int rbw = wave % RB, st = wave / RB;
+    // blockIdx.x = g + Hkv * (rbg + row_groups * chunk): neighbouring workgroups (dealt round-robin to
+    // the XCDs) differ in KV head first, so one XCD's L2 serves few heads
     int bx = blockIdx.x;
     const int g = bx % a.Hkv; bx /= a.Hkv;
-    const int rb = bx % a.row_blocks;
-    const int chunk = bx / a.row_blocks;
+    const int row_groups = a.row_blocks / RB;
+    const int rbg = bx % row_groups;
+    const int chunk = bx / row_groups;
+    const int rb = rbg * RB + rbw;                     // this wave's row block
     const int b = blockIdx.y;
     const int M = a.M, G = a.G;
+    const int n_rows = G * M;
+    unsigned char* ring = sm.big + st * (S * kStageBytes);
+    const unsigned ring_addr = lds_address(ring);
+    const int l_row = lane >> 4, l_seg = lane & 15;    // a direct-to-LDS load lands lane l at row l/16, segment l%16
 
+    // ---- Q for this wave's 64 rows: HBM -> LDS (the upper half of the ring is free at this point) ------
+    // Laid out like two K tiles (query block 0, then 1) with the same segment swizzle.
+    const unsigned q_stage = __builtin_amdgcn_readfirstlane(ring_addr + (S / 2 + rbw) * kStageBytes);
+    {
+        const unsigned long long q_sbase =
+            scalar_base(static_cast<const unsigned char*>(a.q) + (int64_t)b * M * a.Hq * (kD * 2));
+        int r = rb * kQRows + l_row;                  // packed row of instruction 0; +4 per instruction
+        int hl = (int)(((float)r + 0.5f) * a.inv_M);  // r / M (exact for these sizes)
+        int i = r - hl * M;                           // (head in group, tree row) of packed row r
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int row = 4 * (j & 7) + l_row;      // row inside the query block: selects the swizzle
+            const bool over = r >= n_rows;            // padding rows re-read the last packed row
+            const int ii = over ? M - 1 : i, hh = over ? G - 1 : hl;
+            const unsigned off = (unsigned)((ii * a.Hq + g * G + hh) * (kD * 2) + ((l_seg ^ (row & 15)) * 16));
+            dma16(q_stage + j * 1024, q_sbase, off);
+            r += 4;
+            i += 4;
+            while (i >= M) { i -= M; ++hl; }
+        }
+    }
+
+    // ---- key range, first K/V tiles (they depend on the prefix length only) ---------------------------
+    const int P = a.prefix_len[b];
+    const bool bad_prefix = (P < a.soft_len || P < 0 || P > a.max_prefix_len);
+    const int Lk = bad_prefix ? M : P + M;
+    const int n_tiles = (Lk + kTK - 1) / kTK;
+    const int n_slots = a.n_chunks * NS;
+    const int slot0 = chunk * NS;
+    // slot u gets tiles_per_slot tiles, the first `extra` slots one more (one 32-bit division)
+    const int tiles_per_slot = (int)((unsigned)n_tiles / (unsigned)n_slots);
+    const int extra = n_tiles - tiles_per_slot * n_slots;
+    const int slot = slot0 + st;
+    const int t_begin = slot * tiles_per_slot + min(slot, extra);
+    const int n_my = bad_prefix ? 0 : tiles_per_slot + (slot < extra ? 1 : 0);
+    // the longest stream of the workgroup is its first one
+    const int n_iter = bad_prefix ? 0 : tiles_per_slot + (slot0 < extra ? 1 : 0);
+
+    const int64_t seq_base = (a.kv_offset[b] * a.tok_stride + (int64_t)g * a.head_stride) * 2;
+    const unsigned char* kbase = static_cast<const unsigned char*>(a.k) + seq_base;
+    const unsigned char* vbase = static_cast<const unsigned char*>(a.v) + seq_base;
+    const unsigned tok_bytes = (unsigned)(a.tok_stride * 2);
+
+    // One tile: instruction j (0..7 K, 8..15 V) moves rows 4j..4j+3; lane l lands at byte 16*l of that 1 KB
+    // block and fetches the logical segment that the swizzle stores there.  This wave issues the
+    // instructions j = jj*RB + rbw: the first PER/2 of them are K rows, the rest V rows.  The per-lane part of
+    // the address is constant; the tile only moves the (scalar) base.
+    unsigned lane_off[PER];
+#pragma unroll
+    for (int jj = 0; jj < PER; ++jj) {
+        const int j = jj * RB + rbw;
+        const int row = 4 * (j & 7) + l_row;
+        const int seg = (j < 8) ? (l_seg ^ (row & 15)) : (l_seg ^ (l_row << 2));
+        lane_off[jj] = (unsigned)row * tok_bytes + (unsigned)(seg * 16);
+    }
+    auto issue_half = [&](int t, int stage, int half) {      // half 0: K rows, half 1: V rows
+        const int k0 = t * kTK;
+        const unsigned dst = __builtin_amdgcn_readfirstlane(ring_addr + stage * kStageBytes + half * kTileBytes);
+        const unsigned char* base = half ? vbase : kbase;
+        if (k0 + kTK <= Lk) {
+            const unsigned long long tile_base = scalar_base(base + (size_t)k0 * tok_bytes);
+#pragma unroll
+            for (int jj = 0; jj < PER / 2; ++jj) {
+                const int j = (half * (PER / 2) + jj) * RB + rbw;
+                dma16(dst + (j & 7) * 1024, tile_base, lane_off[half * (PER / 2) + jj]);
+            }
+        } else {                                             // last tile: never read past the sequence's rows
+#pragma unroll
+            for (int jj = 0; jj < PER / 2; ++jj) {
+                const int j = (half * (PER / 2) + jj) * RB + rbw;
+                const int row = 4 * (j & 7) + l_row;
+                const unsigned key = (unsigned)min(k0 + row, Lk - 1);
+                const int seg = half ? (l_seg ^ (l_row << 2)) : (l_seg ^ (row & 15));
+                dma16(dst + (j & 7) * 1024, scalar_base(base), key * tok_bytes + (unsigned)(seg * 16));
+            }
+        }
+    };
+    auto issue_tile = [&](int t, int stage) { issue_half(t, stage, 0); issue_half(t, stage, 1); };
+#pragma unroll
+    for (int i = 0; i < S / 2; ++i)
+        if (i < n_my) issue_tile(t_begin + i, i);
+
+    // ---- tree, validation (ordinary loads: the wait the compiler puts before the LDS writes also covers
+    //      everything requested above, which is needed next anyway) ---------------------------------------
     for (int i = tid; i < M; i += kThreads) {
         sm.parent[i] = a.parent[(int64_t)b * M + i];
         sm.kind[i] = a.kind[(int64_t)b * M + i];
     }
+    wait_vmcnt<0>();
     __syncthreads();
     int bad = validate_tree(sm.parent, sm.kind, M, &sm.flag);
-    const int P = a.prefix_len[b];
-    if (P < a.soft_len || P < 0 || P > a.max_prefix_len) bad |= TV_STATUS_BAD_PREFIX;
+    if (bad_prefix) bad |= TV_STATUS_BAD_PREFIX;
     if (blockIdx.x == 0 && tid == 0) a.status[b] = bad;
-    const int n_rows = G * M;
     unsigned short* out16 = static_cast<unsigned short*>(a.out);
     if (bad) {
         if (a.n_chunks == 1) {       // otherwise the combine kernel writes the zeros
-            for (int idx = tid; idx < kQRows * kD; idx += kThreads) {
-                const int r = rb * kQRows + idx / kD;
+            for (int idx = tid; idx < RB * kQRows * kD; idx += kThreads) {
+                const int r = rbg * RB * kQRows + idx / kD;
                 if (r < n_rows)
                     out16[(((int64_t)b * M + r % M) * a.Hq + g * G + r / M) * kD + idx % kD] = 0;
             }
-            if (a.lse && tid < kQRows && rb * kQRows + tid < n_rows) {
-                const int r = rb * kQRows + tid;
-                a.lse[((int64_t)b * a.Hq + g * G + r / M) * M + r % M] = 0.f;
+            for (int idx = tid; idx < RB * kQRows; idx += kThreads) {
+                const int r = rbg * RB * kQRows + idx;
+                if (a.lse && r < n_rows) a.lse[((int64_t)b * a.Hq + g * G + r / M) * M + r % M] = 0.f;
             }
         }
         return;
     }
 
-    // ---- this lane's two queries (column ln of query block 0 and 1) --------------------------------
-    bf16x8 qreg[2][8];
-    bool is_con[2];
-    unsigned long long bits0[2], bits1[2];
-    const unsigned short* q16 = static_cast<const unsigned short*>(a.q);
+    // per-lane LDS offsets of the MFMA operands inside a tile
+    unsigned k_off[8];       // K (A operand of S^T): row ln, logical segment 2*ks + hf
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const int r = min(rb * kQRows + qb * 32 + ln, n_rows - 1);
-        const int i = r % M, h = g * G + r / M;
-        const unsigned short* qp = q16 + (((int64_t)b * M + i) * a.Hq + h) * kD + hf * 8;
+    for (int ks = 0; ks < 8; ++ks) k_off[ks] = (unsigned)(ln * kRowBytes + (((2 * ks + hf) ^ (ln & 15)) << 4));
+    unsigned v_off[4];       // V^T (A operand of O^T): transposed 8-byte reads, 4 keys x 16 d per 16 lanes
+    {
+        const int g16 = lane >> 4, i16 = lane & 15;
+        const int row = 4 * (g16 >> 1) + (i16 >> 2);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qreg[qb][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
-        is_con[qb] = (sm.kind[i] == TV_KIND_CONTEMPLATE);
-        ancestor_bits(sm.parent, i, &bits0[qb], &bits1[qb]);
+        for (int dt = 0; dt < 4; ++dt) {
+            const int seg = (4 * (dt ^ (i16 >> 2))) + (g16 & 1) * 2 + ((i16 & 3) >> 1);
+            v_off[dt] = (unsigned)(kTileBytes + row * kRowBytes + seg * 16 + (i16 & 1) * 8);
+        }
     }
 
-    // ---- this wave's run of tiles -----------------------------------------------------------------------
-    const int Lk = P + M;
-    const int n_tiles = (Lk + kTK - 1) / kTK;
-    const int n_slots = a.n_chunks * kWaves;
-    const int slot = chunk * kWaves + wave;
-    const int t_begin = (int)((int64_t)slot * n_tiles / n_slots);
-    const int t_end = (int)((int64_t)(slot + 1) * n_tiles / n_slots);
-
-    const int64_t tok_bytes = a.tok_stride * 2;
-    const unsigned char* kbase = static_cast<const unsigned char*>(a.k) + (a.kv_offset[b] * a.tok_stride + (int64_t)g * a.head_stride) * 2;
-    const unsigned char* vbase = static_cast<const unsigned char*>(a.v) + (a.kv_offset[b] * a.tok_stride + (int64_t)g * a.head_stride) * 2;
-    unsigned char* my_lds = sm.big + wave * kWaveLds;
+    // ---- this lane's two queries (column ln of query block 0 and 1): B operands of S^T, kept in registers
+    bf16x8 qreg[2][8];
+    int tree_row[2];         // tree row of the two queries (the mask of a tile is derived from it on demand)
+    {
+        const unsigned char* qs = ring + (S / 2 + rbw) * kStageBytes;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                qreg[qb][ks] = *reinterpret_cast<const bf16x8*>(qs + qb * kTileBytes + k_off[ks]);
+                park(qreg[qb][ks]);
+            }
+            const int r = min(rb * kQRows + qb * 32 + ln, n_rows - 1);
+            tree_row[qb] = r - (int)(((float)r + 0.5f) * a.inv_M) * M;      // r % M (exact: r < 2^16)
+        }
+    }
+    __syncthreads();         // the Q staging area goes back to the ring
+#pragma unroll
+    for (int i = S / 2; i < S - 1; ++i)
+        if (i < n_my) issue_tile(t_begin + i, i);
 
     const float c = a.scale * kLog2e;
     float m_run[2] = {-INFINITY, -INFINITY};    // running max, in log2 units (score * c)
@@ -152,69 +308,80 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) o[dt][qb][j] = 0.f;
 
-    u32x4 kst[8], vst[8];      // one tile in flight from HBM
-    const int ld_row = lane >> 4, ld_seg = lane & 15;
-    auto issue_loads = [&](int t) {
-        const int k0 = t * kTK;
+    // The product O^T += V^T P^T of a tile is issued one tile late, next to the exponentials of the
+    // following tile, so that the matrix pipe and the vector ALU work at the same time.  Carried over:
+    // the V^T operands (va) and the probabilities (pb) of the previous tile.
+    bf16x8 va[8], pb[2][2];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int key = min(k0 + 4 * j + ld_row, Lk - 1);      // never read past the sequence's rows
-            const int64_t off = (int64_t)key * tok_bytes + ld_seg * 16;
-            kst[j] = *reinterpret_cast<const u32x4*>(kbase + off);
-            vst[j] = *reinterpret_cast<const u32x4*>(vbase + off);
-        }
-    };
-    auto stash = [&](int stage) {
-        unsigned char* kd = my_lds + stage * (kKTile + kVTile);
-        unsigned char* vd = kd + kKTile;
+    for (int e = 0; e < 8; ++e) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            *reinterpret_cast<u32x4*>(kd + (4 * j + ld_row) * kKStride + ld_seg * 16) = kst[j];
-            *reinterpret_cast<u32x4*>(vd + (4 * j + ld_row) * kVStride + ld_seg * 16) = vst[j];
-        }
+        for (int x = 0; x < 8; ++x) va[e][x] = (__bf16)0.f;
+    }
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int x = 0; x < 8; ++x) pb[qb][ks][x] = (__bf16)0.f;
+
+    auto pv_mfma = [&]() {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                o[dt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks * 4 + dt], pb[0][ks], o[dt][0], 0, 0, 0);
+                o[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks * 4 + dt], pb[1][ks], o[dt][1], 0, 0, 0);
+            }
     };
 
-    if (t_begin < t_end) {
-        issue_loads(t_begin);
-        stash(0);
-    }
-    for (int t = t_begin; t < t_end; ++t) {
-        const int stage = (t - t_begin) & 1;
-        if (t + 1 < t_end) issue_loads(t + 1);
-        // one wave writes and reads its own buffers; LDS operations of a wave complete in order
-        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        const unsigned char* kt = my_lds + stage * (kKTile + kVTile);
-        const unsigned char* vt = kt + kKTile;
-        const int k0 = t * kTK;
+    for (int it = 0; it < n_iter; ++it) {
+        const bool live = it < n_my;
+        if (live) {                                                     // this wave's part of tile `it` has landed
+            if (n_my - 1 - it >= S - 2) wait_vmcnt<(S - 2) * PER>();    // steady state: S-2 younger tiles in flight
+            else wait_vmcnt<0>();                                       // tail: fewer were issued, wait for all
+        }
+        if (RB > 1) __syncthreads();                                    // ... and so have the other waves' parts
+        else {
+            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+        }
+        const bool more = it + S - 1 < n_my;          // another tile to request, into the stage freed last round
+        if (more) issue_half(t_begin + it + S - 1, (it + S - 1) % S, 0);
+        if (!live) continue;
+        const unsigned char* stg = ring + (it % S) * kStageBytes;
+        const int k0 = (t_begin + it) * kTK;
 
         // S^T = K Q^T
+        bf16x8 ka[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            ka[ks] = *reinterpret_cast<const bf16x8*>(stg + k_off[ks]);
+            park(ka[ks]);
+        }
         f32x16 s[2];
 #pragma unroll
         for (int j = 0; j < 16; ++j) { s[0][j] = 0.f; s[1][j] = 0.f; }
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 ka = *reinterpret_cast<const bf16x8*>(kt + ln * kKStride + ks * 32 + hf * 16);
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[0][ks], s[0], 0, 0, 0);
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[1][ks], s[1], 0, 0, 0);
+            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], s[0], 0, 0, 0);
+            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], s[1], 0, 0, 0);
         }
 
+        if (more) issue_half(t_begin + it + S - 1, (it + S - 1) % S, 1);      // spread the requests: they queue in the texture path
+
         // mask (only tiles touching the soft-prompt slots, the new rows or the tail)
-        const bool need_mask = (k0 < a.soft_len) || (k0 + kTK > P);
-        if (need_mask) {
+        if ((k0 < a.soft_len) || (k0 + kTK > P)) {
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
+            for (int qb = 0; qb < 2; ++qb) {
+                // rare (a few tiles per sequence): rebuild the row's ancestor mask from the parent array
+                unsigned long long bits0, bits1;
+                ancestor_bits(sm.parent, tree_row[qb], &bits0, &bits1);
+                const bool is_con = (sm.kind[tree_row[qb]] == TV_KIND_CONTEMPLATE);
+                const unsigned vis = tile_visibility(k0, P, a.soft_len, is_con, bits0, bits1) >> (4 * hf);
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int kg = k0 + 8 * (j >> 2) + 4 * hf + (j & 3);
-                    bool vis;
-                    if (kg < P) vis = (kg >= a.soft_len) || is_con[qb];
-                    else if (kg < Lk) {
-                        const int jj = kg - P;
-                        vis = ((jj < 64 ? (bits0[qb] >> jj) : (bits1[qb] >> (jj - 64))) & 1ull) != 0;
-                    } else vis = false;
-                    s[qb][j] = vis ? s[qb][j] : -INFINITY;
-                }
+                for (int j = 0; j < 16; ++j)
+                    s[qb][j] = (vis & (1u << (8 * (j >> 2) + (j & 3)))) ? s[qb][j] : -INFINITY;
+            }
         }
 
         // online softmax; the max is raised lazily (probabilities may reach 2^kTau, harmless in fp32/bf16)
@@ -226,22 +393,36 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
             for (int j = 1; j < 16; ++j) x = fmaxf(x, s[qb][j]);
             tmax[qb] = cross_half_max(x) * c;
         }
-        const bool raise0 = tmax[0] > m_run[0] + kTau, raise1 = tmax[1] > m_run[1] + kTau;
-        if (__any(raise0 || raise1)) {
+        if (it == 0) {
+            // nothing accumulated yet: adopt the tile's max as the reference
+            m_run[0] = tmax[0];
+            m_run[1] = tmax[1];
+        } else {
+            const bool raise0 = tmax[0] > m_run[0] + kTau, raise1 = tmax[1] > m_run[1] + kTau;
+            if (__any(raise0 || raise1)) {
+                // rare: bring O up to date with the pending product, then rescale it to the new reference
+                pv_mfma();
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
-                const bool raise = qb ? raise1 : raise0;
-                const float m_new = raise ? tmax[qb] : m_run[qb];
-                const float alpha = raise ? __builtin_amdgcn_exp2f(m_run[qb] - m_new) : 1.f;   // exp2(-inf) = 0
-                m_run[qb] = m_new;
-                l_run[qb] *= alpha;
+                for (int qb = 0; qb < 2; ++qb) {
 #pragma unroll
-                for (int dt = 0; dt < 4; ++dt)
+                    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) o[dt][qb][j] *= alpha;
+                        for (int x = 0; x < 8; ++x) pb[qb][ks][x] = (__bf16)0.f;
+                    const bool raise = qb ? raise1 : raise0;
+                    const float m_new = raise ? tmax[qb] : m_run[qb];
+                    const float alpha = raise ? __builtin_amdgcn_exp2f(m_run[qb] - m_new) : 1.f;   // exp2(-inf) = 0
+                    m_run[qb] = m_new;
+                    l_run[qb] *= alpha;
+#pragma unroll
+                    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) o[dt][qb][j] *= alpha;
+                }
             }
         }
-        bf16x8 pb[2][2];
+
+        // previous tile's O^T += V^T P^T (matrix pipe) next to this tile's exponentials (vector ALU)
+        pv_mfma();
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             const float mc = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
@@ -255,31 +436,26 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
             l_run[qb] += sum;
         }
 
-        // O^T += V^T P^T
-        const int g16 = lane >> 4, i16 = lane & 15;
-        const unsigned char* vrow = vt + (4 * (g16 >> 1) + (i16 >> 2)) * kVStride + ((g16 & 1) * 16 + (i16 & 3) * 4) * 2;
+        // this tile's V^T operands, used one round later
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
-                const unsigned char* p0 = vrow + (16 * ks) * kVStride + dt * 64;
-                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                    (bf16x4 __attribute__((address_space(3)))*)(p0));
+                const unsigned char* p0 = stg + v_off[dt] + ks * (16 * kRowBytes);
+                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(p0));
                 const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                    (bf16x4 __attribute__((address_space(3)))*)(p0 + 8 * kVStride));
-                bf16x8 va;
-                va[0] = lo[0]; va[1] = lo[1]; va[2] = lo[2]; va[3] = lo[3];
-                va[4] = hi[0]; va[5] = hi[1]; va[6] = hi[2]; va[7] = hi[3];
-                o[dt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[0][ks], o[dt][0], 0, 0, 0);
-                o[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[1][ks], o[dt][1], 0, 0, 0);
+                    (bf16x4 __attribute__((address_space(3)))*)(p0 + 8 * kRowBytes));
+                va[ks * 4 + dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                park(va[ks * 4 + dt]);
             }
-        }
-        if (t + 1 < t_end) stash(stage ^ 1);
     }
+    pv_mfma();               // the last tile's product
 
-    // ---- merge the four waves through LDS -------------------------------------------------------------
-    __syncthreads();       // every wave is done with its stage buffers
-    float* mbuf = reinterpret_cast<float*>(sm.big);
+    // ---- merge the streams through LDS -------------------------------------------------------------------
+    // Merge buffer: [wave][64 rows][32 float4], float4 column c of row r stored at column c ^ (r & 31).
+    wait_vmcnt<0>();
+    __syncthreads();       // every wave is done with the stage ring
+    f32x4* mbuf = reinterpret_cast<f32x4*>(sm.big);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const float l_tot = cross_half_sum(l_run[qb]);
@@ -287,62 +463,61 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
             sm.ml[wave][qb * 32 + ln][0] = m_run[qb];
             sm.ml[wave][qb * 32 + ln][1] = l_tot;
         }
-        float* orow = mbuf + ((wave * kQRows) + qb * 32 + ln) * kOStride;
+        f32x4* orow = mbuf + (wave * kQRows + qb * 32 + ln) * 32;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
             for (int jg = 0; jg < 4; ++jg) {
                 f32x4 x = {o[dt][qb][4 * jg], o[dt][qb][4 * jg + 1], o[dt][qb][4 * jg + 2], o[dt][qb][4 * jg + 3]};
-                *reinterpret_cast<f32x4*>(orow + dt * 32 + 8 * jg + 4 * hf) = x;
+                orow[(dt * 8 + 2 * jg + hf) ^ ln] = x;
             }
     }
     __syncthreads();
-    {
-        const int qi = tid >> 2, dq = tid & 3;       // query row of the block, 32-wide column slice
-        float mw[kWaves], mx = -INFINITY;
+    // 64*RB rows of 128 values leave as bf16: 16 lanes cover one 256-byte row, so a store instruction of the
+    // wave writes 1 KB of consecutive memory (4 rows of a partial result; rows of the output are 256-byte runs)
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) { mw[w] = sm.ml[w][qi][0]; mx = fmaxf(mx, mw[w]); }
+    for (int k = 0; k < 4 * RB; ++k) {
+        const int idx = k * kThreads + tid;
+        const int row_l = idx >> 4, c16 = idx & 15;       // row of the workgroup, 16-byte column of the row
+        const int w_rb = row_l / kQRows, qi = row_l % kQRows;
+        float mw[NS], mx = -INFINITY;
+#pragma unroll
+        for (int s2 = 0; s2 < NS; ++s2) { mw[s2] = sm.ml[s2 * RB + w_rb][qi][0]; mx = fmaxf(mx, mw[s2]); }
         const float mxs = (mx == -INFINITY) ? 0.f : mx;
-        float wgt[kWaves], L = 0.f;
+        float wgt[NS], L = 0.f;
 #pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            wgt[w] = __builtin_amdgcn_exp2f(mw[w] - mxs);
-            L += wgt[w] * sm.ml[w][qi][1];
+        for (int s2 = 0; s2 < NS; ++s2) {
+            wgt[s2] = __builtin_amdgcn_exp2f(mw[s2] - mxs);
+            L += wgt[s2] * sm.ml[s2 * RB + w_rb][qi][1];
         }
-        const int r = rb * kQRows + qi;
-        const bool live = r < n_rows;
-        const int i = live ? r % M : 0, h = g * G + (live ? r / M : 0);
-        if (a.n_chunks == 1) {
-            const float inv = 1.f / L;
-            unsigned short* dst = out16 + (((int64_t)b * M + i) * a.Hq + h) * kD + dq * 32;
+        const int rbo = rbg * RB + w_rb;
+        const int r = rbo * kQRows + qi;
+        const bool row_live = r < n_rows;
+        const int hl = row_live ? (int)(((float)r + 0.5f) * a.inv_M) : 0;
+        const int i = row_live ? r - hl * M : 0, h = g * G + hl;
+        // final output, or this key range's partial result: O / L in bf16 next to (max, L) in fp32
+        const float inv = (L > 0.f) ? 1.f / L : 0.f;
+        const int64_t blk = (((int64_t)b * a.n_chunks + chunk) * a.Hkv + g) * a.row_blocks + rbo;
+        unsigned short* dst16 = (a.n_chunks == 1)
+            ? out16 + (((int64_t)b * M + i) * a.Hq + h) * kD + c16 * 8
+            : static_cast<unsigned short*>(a.part_o) + (blk * kQRows + qi) * kD + c16 * 8;
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int e = 0; e < 32; e += 4) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int w = 0; w < kWaves; ++w) {
-                    const f32x4 x = *reinterpret_cast<const f32x4*>(mbuf + (w * kQRows + qi) * kOStride + dq * 32 + e);
-                    acc += x * wgt[w];
-                }
-                bf16x4 ob;
-                ob[0] = (__bf16)(acc[0] * inv); ob[1] = (__bf16)(acc[1] * inv);
-                ob[2] = (__bf16)(acc[2] * inv); ob[3] = (__bf16)(acc[3] * inv);
-                if (live) *reinterpret_cast<bf16x4*>(dst + e) = ob;
-            }
-            if (a.lse && live && dq == 0) a.lse[((int64_t)b * a.Hq + h) * M + i] = (mx + log2f(L)) * kLn2;
-        } else {
-            const int64_t blk = (((int64_t)b * a.n_chunks + chunk) * a.Hkv + g) * a.row_blocks + rb;
-            float* dst = a.part_o + (blk * kQRows + qi) * kD + dq * 32;
-#pragma unroll
-            for (int e = 0; e < 32; e += 4) {
-                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int w = 0; w < kWaves; ++w) {
-                    const f32x4 x = *reinterpret_cast<const f32x4*>(mbuf + (w * kQRows + qi) * kOStride + dq * 32 + e);
-                    acc += x * wgt[w];
-                }
-                *reinterpret_cast<f32x4*>(dst + e) = acc;
-            }
-            if (dq == 0) {
+        for (int s2 = 0; s2 < NS; ++s2) {
+            const f32x4* prow = mbuf + ((s2 * RB + w_rb) * kQRows + qi) * 32;
+            acc0 += prow[(2 * c16) ^ (qi & 31)] * wgt[s2];
+            acc1 += prow[(2 * c16 + 1) ^ (qi & 31)] * wgt[s2];
+        }
+        bf16x8 ob;
+        ob[0] = (__bf16)(acc0[0] * inv); ob[1] = (__bf16)(acc0[1] * inv);
+        ob[2] = (__bf16)(acc0[2] * inv); ob[3] = (__bf16)(acc0[3] * inv);
+        ob[4] = (__bf16)(acc1[0] * inv); ob[5] = (__bf16)(acc1[1] * inv);
+        ob[6] = (__bf16)(acc1[2] * inv); ob[7] = (__bf16)(acc1[3] * inv);
+        if (row_live || a.n_chunks > 1) *reinterpret_cast<bf16x8*>(dst16) = ob;
+        if (c16 == 0) {
+            if (a.n_chunks == 1) {
+                if (a.lse && row_live) a.lse[((int64_t)b * a.Hq + h) * M + i] = (mx + log2f(L)) * kLn2;
+            } else {
                 a.part_ml[(blk * kQRows + qi) * 2 + 0] = mx;
                 a.part_ml[(blk * kQRows + qi) * 2 + 1] = L;
             }
@@ -368,18 +543,38 @@ __global__ __launch_bounds__(256) void attn_bf16_combine_kernel(AttnArgs a) {
     }
     const int g = h / a.G, r = (h % a.G) * a.M + i;
     const int rb = r / kQRows, qi = r % kQRows;
-    float mx = -INFINITY;
-    for (int ch = 0; ch < a.n_chunks; ++ch) {
-        const int64_t blk = (((int64_t)b * a.n_chunks + ch) * a.Hkv + g) * a.row_blocks + rb;
-        mx = fmaxf(mx, a.part_ml[(blk * kQRows + qi) * 2]);
-    }
+    const int64_t blk0 = ((int64_t)b * a.n_chunks * a.Hkv + g) * a.row_blocks + rb;
+    const int64_t blk_step = (int64_t)a.Hkv * a.row_blocks;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    float L = 0.f;
-    for (int ch = 0; ch < a.n_chunks; ++ch) {
-        const int64_t blk = (((int64_t)b * a.n_chunks + ch) * a.Hkv + g) * a.row_blocks + rb;
-        const float w = __builtin_amdgcn_exp2f(a.part_ml[(blk * kQRows + qi) * 2] - mx);
-        L += w * a.part_ml[(blk * kQRows + qi) * 2 + 1];
-        acc += *reinterpret_cast<const f32x4*>(a.part_o + (blk * kQRows + qi) * kD + d0) * w;
+    float L = 0.f, mx = -INFINITY;
+    for (int ch0 = 0; ch0 < a.n_chunks; ch0 += 8) {
+        // up to 8 partials at a time: all loads of a batch are issued before any is used
+        float mm[8], ll[8];
+        bf16x4 oo[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const bool ok = ch0 + e < a.n_chunks;
+            const int64_t blk = blk0 + (int64_t)(ok ? ch0 + e : ch0) * blk_step;
+            mm[e] = ok ? a.part_ml[(blk * kQRows + qi) * 2] : -INFINITY;
+            ll[e] = a.part_ml[(blk * kQRows + qi) * 2 + 1];
+            oo[e] = *reinterpret_cast<const bf16x4*>(static_cast<const unsigned short*>(a.part_o) + (blk * kQRows + qi) * kD + d0);
+        }
+        float bm = mx;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bm = fmaxf(bm, mm[e]);
+        const float bms = (bm == -INFINITY) ? 0.f : bm;
+        const float resc = __builtin_amdgcn_exp2f(mx - bms);        // 0 on the first batch
+        acc *= resc;
+        L *= resc;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float w = __builtin_amdgcn_exp2f(mm[e] - bms);    // 0 for absent partials
+            const float wl = w * ll[e];                             // the partial holds O / L
+            L += wl;
+            acc[0] += wl * (float)oo[e][0]; acc[1] += wl * (float)oo[e][1];
+            acc[2] += wl * (float)oo[e][2]; acc[3] += wl * (float)oo[e][3];
+        }
+        mx = bm;
     }
     const float inv = 1.f / L;
     bf16x4 ob;
@@ -389,23 +584,33 @@ __global__ __launch_bounds__(256) void attn_bf16_combine_kernel(AttnArgs a) {
     if (a.lse && d0 == 0) a.lse[((int64_t)b * a.Hq + h) * a.M + i] = (mx + log2f(L)) * kLn2;
 }
 
-}  // namespace
-
-hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
-    static std::atomic<unsigned> attr_done{0};
+template <int RB>
+hipError_t launch_rb(const AttnArgs& a, hipStream_t s) {
+    static std::atomic<unsigned> attr_done{0};       // one bit per device
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     const unsigned bit = 1u << (dev & 31);
     if (!(attr_done.load(std::memory_order_acquire) & bit)) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<RB>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Bf16Smem));
         if (e != hipSuccess) return e;
         attr_done.fetch_or(bit, std::memory_order_release);
     }
-    const dim3 grid(a.Hkv * a.row_blocks * a.n_chunks, a.B);
-    attn_bf16_kernel<<<grid, kThreads, sizeof(Bf16Smem), s>>>(a);
-    e = hipGetLastError();
+    const dim3 grid(a.Hkv * (a.row_blocks / RB) * a.n_chunks, a.B);
+    attn_bf16_kernel<RB><<<grid, kThreads, sizeof(Bf16Smem), s>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
+    hipError_t e;
+    switch (a.rb_per_wg) {
+        case 1: e = launch_rb<1>(a, s); break;
+        case 2: e = launch_rb<2>(a, s); break;
+        default: e = launch_rb<4>(a, s); break;
+    }
     if (e != hipSuccess) return e;
     if (a.n_chunks > 1) {
         const int64_t rows = (int64_t)a.B * a.M * a.Hq;

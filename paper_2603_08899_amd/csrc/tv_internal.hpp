@@ -16,7 +16,8 @@ constexpr int kMaskWords = 2;        // 64-bit words of ancestor mask per row (M
 // ---- attention plan: how one call is cut into workgroups -------------------------------------
 struct AttnPlan {
     int G;                 // query heads per KV head
-    int row_blocks;        // 64-row blocks of the G*M packed rows of one KV head (bf16 path)
+    int row_blocks;        // 64-row blocks of the G*M packed rows of one KV head (bf16 path), padded to a multiple of rb_per_wg
+    int rb_per_wg;         // row blocks (waves) that share one key stream inside a workgroup: 1, 2 or 4
     int n_chunks;          // key ranges the (prefix + new rows) of a sequence are cut into
     int chunk_len;         // keys per range (multiple of 128 on the bf16 path)
     size_t part_o_bytes;   // workspace: partial outputs
@@ -37,13 +38,14 @@ struct AttnArgs {
     void* out;
     float* lse;
     int32_t* status;
-    float* part_o;
+    void* part_o;      // partial outputs, bf16, each already divided by its own sum
     float* part_ml;
     int B, M, Hq, Hkv, D, G;
     int soft_len, max_prefix_len;
     float scale;
+    float inv_M;                       // 1 / M
     int64_t tok_stride, head_stride;   // elements
-    int row_blocks, n_chunks, chunk_len;
+    int row_blocks, n_chunks, chunk_len, rb_per_wg;
 };
 
 hipError_t launch_attention_f32(const AttnArgs& a, hipStream_t s);

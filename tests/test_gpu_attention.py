@@ -85,10 +85,14 @@ def test_fp32_paper_layout_two_rows_per_node():
     (16, 1, 5, 3, 96, 0),         # G=16
 ])
 @pytest.mark.parametrize("peaked", [False, True])
-def test_bf16_shapes(Hq, Hkv, T, C, P, s, peaked):
+@pytest.mark.parametrize("wg", [1, 2, 4])
+def test_bf16_shapes(Hq, Hkv, T, C, P, s, peaked, wg):
+    """wg = 64-row blocks sharing one key stream per workgroup (the three kernel instantiations)."""
     std = 1.0 if peaked else 1.0 / np.sqrt(128)
     inp = _case(11, dtype="bf16", Hq=Hq, Hkv=Hkv, D=128, P=P, T=T, C=C, s=s, q_std=std, kv_std=std)
-    out, lse, st = H.run_attention(inp)
+    out, lse, st = H.run_attention(inp, wg_row_blocks=wg)
+    _check(inp, out, lse, st)
+    out, lse, st = H.run_attention(inp, wg_row_blocks=wg, num_splits=3)
     _check(inp, out, lse, st)
 
 
@@ -108,8 +112,9 @@ def test_bf16_paper_layout_120_rows_and_soft_prompts():
 @pytest.mark.parametrize("splits", [0, 1, 2, 5])
 def test_bf16_short_prefixes_and_forced_splits(P, splits):
     inp = _case(14 + P, dtype="bf16", Hq=8, Hkv=2, D=128, P=P, T=60, C=4, q_std=1.0, kv_std=1.0)
-    out, lse, st = H.run_attention(inp, num_splits=splits)
-    _check(inp, out, lse, st)
+    for wg in (1, 2, 4):
+        out, lse, st = H.run_attention(inp, num_splits=splits, wg_row_blocks=wg)
+        _check(inp, out, lse, st)
 
 
 def test_bf16_split_counts_agree_closely():
@@ -132,8 +137,9 @@ def test_bf16_ragged_batch_with_poisoned_padding():
         inp.k_pool[end:end + 3] = big
         inp.v_pool[end:end + 3] = big
     for splits in (0, 1, 3):
-        out, lse, st = H.run_attention(inp, num_splits=splits)
-        _check(inp, out, lse, st)
+        for wg in (1, 2, 4):
+            out, lse, st = H.run_attention(inp, num_splits=splits, wg_row_blocks=wg)
+            _check(inp, out, lse, st)
 
 
 def test_bf16_invisible_keys_do_not_change_the_output_bitwise():
@@ -193,8 +199,9 @@ def test_malformed_sequences_are_flagged_and_zeroed(dtype, D):
 def test_full_size_single_sequence_workloads(index, peaked):
     """Llama-3.2-3B-shaped (G=3, P=2048) and Llama-3.1-8B-shaped (G=4, P=4096) layers, all outputs."""
     inp = si.attention_case(index, peaked=peaked)
-    out, lse, st = H.run_attention(inp)
-    _check(inp, out, lse, st)
+    for wg in (0, 1, 4):
+        out, lse, st = H.run_attention(inp, wg_row_blocks=wg)
+        _check(inp, out, lse, st)
 
 
 def test_full_size_long_context_sampled_heads():
