@@ -31,8 +31,10 @@ int check_attn_desc(const tv_attn_desc* d) {
         return TV_ERR_INVALID_ARG;
     if (d->Hq / d->Hkv > 16) return TV_ERR_INVALID_ARG;
     if (d->soft_len < 0 || d->max_prefix_len < d->soft_len || d->num_splits < 0) return TV_ERR_INVALID_ARG;
-    if (d->wg_row_blocks != 0 && d->wg_row_blocks != 1 && d->wg_row_blocks != 2 && d->wg_row_blocks != 4)
-        return TV_ERR_INVALID_ARG;
+    {
+        const int rbw = d->wg_row_blocks & 0xff;
+        if ((d->wg_row_blocks & ~0x1ff) != 0 || (rbw != 0 && rbw != 1 && rbw != 2 && rbw != 4)) return TV_ERR_INVALID_ARG;
+    }
     if (!(d->softmax_scale > 0.f)) return TV_ERR_INVALID_ARG;
     if (d->kv_token_stride < 0 || d->kv_head_stride < 0) return TV_ERR_INVALID_ARG;
     if (d->dtype == TV_DTYPE_F32) {
@@ -45,7 +47,7 @@ int check_attn_desc(const tv_attn_desc* d) {
     const int64_t hs = d->kv_head_stride ? d->kv_head_stride : d->D;
     const int64_t ts = d->kv_token_stride ? d->kv_token_stride : (int64_t)d->Hkv * d->D;
     const int vec = (d->dtype == TV_DTYPE_F32) ? 4 : 8;      // 16-byte loads
-    if (hs < d->D || hs % vec != 0 || ts % vec != 0 || ts < hs) return TV_ERR_INVALID_ARG;
+    if (hs < d->D || ts < d->D || hs % vec != 0 || ts % vec != 0) return TV_ERR_INVALID_ARG;   // token-major and head-major pools both fit
     // byte offsets inside one sequence are formed in 32 bits
     const int elem = (d->dtype == TV_DTYPE_F32) ? 4 : 2;
     if (((int64_t)d->max_prefix_len + d->M) * ts * elem >= ((int64_t)1 << 32)) return TV_ERR_INVALID_ARG;
@@ -68,7 +70,8 @@ int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
     const int rows = p.G * d.M;
     const int rb_needed = (rows + 63) / 64;
     // waves of a workgroup that share one key stream (the rest of the 4 waves split the keys)
-    p.rb_per_wg = d.wg_row_blocks ? d.wg_row_blocks : (rb_needed >= 2 ? 2 : 1);
+    p.rb_per_wg = (d.wg_row_blocks & 0xff) ? (d.wg_row_blocks & 0xff) : 1;
+    p.wave_rows = (d.wg_row_blocks & 0x100) ? 64 : 32;
     p.row_blocks = (rb_needed + p.rb_per_wg - 1) / p.rb_per_wg * p.rb_per_wg;
     const int64_t base = (int64_t)d.B * d.Hkv * (p.row_blocks / p.rb_per_wg);
     const int n_tiles = (d.max_prefix_len + d.M + 31) / 32;
@@ -176,7 +179,7 @@ int tree_verify_attention(const tv_attn_desc* desc, const void* q, const void* k
     a.inv_M = 1.0f / (float)desc->M;
     a.head_stride = desc->kv_head_stride ? desc->kv_head_stride : desc->D;
     a.tok_stride = desc->kv_token_stride ? desc->kv_token_stride : (int64_t)desc->Hkv * desc->D;
-    a.row_blocks = p.row_blocks; a.n_chunks = p.n_chunks; a.chunk_len = p.chunk_len; a.rb_per_wg = p.rb_per_wg;
+    a.row_blocks = p.row_blocks; a.n_chunks = p.n_chunks; a.chunk_len = p.chunk_len; a.rb_per_wg = p.rb_per_wg; a.wave_rows = p.wave_rows;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const hipError_t e = (desc->dtype == TV_DTYPE_F32) ? launch_attention_f32(a, s) : launch_attention_bf16(a, s);
     return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;

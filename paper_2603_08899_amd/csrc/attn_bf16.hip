@@ -6,23 +6,23 @@
 //
 // Mapping
 //   - The G = Hq/Hkv query heads of one KV head times the M rows are packed into G*M rows
-//     r = head_in_group*M + row, cut into row blocks of 64.  A wave owns one row block: Q^T for its
-//     64 rows stays in registers as the MFMA B operand for the whole kernel.
-//   - A workgroup has 4 waves = RB row blocks x NS key streams (RB*NS = 4).  The keys of a sequence
-//     are cut into n_chunks ranges (one per workgroup) and each range into NS contiguous runs of
-//     32-key tiles (one per stream).  The RB waves of a stream consume the same K/V tiles from LDS,
-//     so K/V is fetched RB-times less often than with one row block per workgroup.
-//   - K/V tiles go HBM -> LDS directly (global_load_lds, 16 bytes per lane, no registers), several
-//     tiles ahead, into a ring of stages per stream.  Rows are 256 bytes; bank conflicts are avoided
-//     by an XOR swizzle of the 16-byte segments which is applied on the global-address side.
+//     r = head_in_group*M + row.  A wave owns NQB blocks of 32 consecutive packed rows (32 or 64 rows):
+//     Q^T for its rows stays in registers as the MFMA B operand for the whole kernel.
+//   - A workgroup covers RB*64 packed rows and one of n_chunks ranges of the sequence's keys.  Its waves
+//     (8 waves of 32 rows, two per SIMD so that one wave's softmax arithmetic runs under the other's matrix
+//     instructions; or 4 waves of 64 rows) form NS key streams: the range is cut into NS contiguous runs of
+//     32-key tiles, and the waves of a stream - one per row slice - consume the same K/V tiles from LDS.
+//   - K/V tiles and the Q block go HBM -> LDS directly (global_load_lds, 16 bytes per lane, no registers),
+//     tiles several steps ahead into a ring of stages per stream.  Rows are 256 bytes; bank conflicts are
+//     avoided by an XOR swizzle of the 16-byte segments which is applied on the global-address side.
 //   - Scores are formed transposed, S^T = K Q^T (A = K tile from LDS).  In the 32x32 accumulator a
 //     lane then holds one query (column) and 16 keys (rows): exactly the B-operand layout of
 //     O^T += V^T P^T, so probabilities stay in registers; V^T comes from the LDS transpose load.
 //     Softmax row reductions are in-lane plus one exchange between the wave's halves.
 //   - Only tiles overlapping the soft-prompt slots, the new rows or the tail are masked, with a
 //     32-bit visibility word per (lane, query) derived from the two-word ancestor mask.
-//   - Streams are merged through LDS; with n_chunks > 1 partial (max, sum, O) go to the workspace
-//     and attn_bf16_combine_kernel finishes.
+//   - Streams are merged through LDS; with n_chunks > 1 partial results (O / L in bf16, max and L in fp32)
+//     go to the workspace and attn_bf16_combine_kernel finishes.
 #include <atomic>
 
 #include "tv_internal.hpp"
@@ -38,23 +38,20 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4), may_alias));
 
 constexpr int kD = 128;
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / kWave;
-constexpr int kQRows = 64;                 // packed query rows per wave
+constexpr int kQRows = 64;                 // packed query rows per row block (unit of the workspace layout)
 constexpr int kTK = 32;                    // keys per tile
 constexpr int kRowBytes = 256;             // one K or V row of one head in LDS
 constexpr int kTileBytes = kTK * kRowBytes;          // 8192: one K tile or one V tile
 constexpr int kStageBytes = 2 * kTileBytes;          // K then V
-constexpr int kRingBytes = 128 * 1024;               // all stages of all streams
-constexpr int kMergeBytes = kWaves * kQRows * kD * 4;         // 131072: the streams' O, merged through LDS
-constexpr int kBigBytes = kMergeBytes > kRingBytes ? kMergeBytes : kRingBytes;
+constexpr int kRingBytes = 128 * 1024;               // all stages of all streams; later the merge buffer
+constexpr int kWgRows = 256;                         // rows x streams held by the waves of a workgroup
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kTau = 8.f;                // the running max is only raised when it lags by more than 2^kTau
 
 struct Bf16Smem {
-    unsigned char big[kBigBytes];          // K/V stage ring, later the merge buffer
-    float ml[kWaves][kQRows][2];
+    unsigned char big[kRingBytes];         // K/V stage ring, later the merge buffer [256 rows][32 float4]
+    float ml[kWgRows][2];                  // (max, sum) of every wave's rows
     int parent[kMaxRows];
     unsigned char kind[kMaxRows];
     int flag;
@@ -126,17 +123,24 @@ __device__ __forceinline__ unsigned tile_visibility(int k0, int P, int soft_len,
     return pm | nm;
 }
 
-template <int RB>
-__global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
-    constexpr int NS = kWaves / RB;                    // key streams per workgroup
+// RB:  64-row blocks covered by one workgroup (1, 2 or 4)
+// NQB: 32-row query blocks per wave: 1 (eight waves, two per SIMD) or 2 (four waves)
+template <int RB, int NQB>
+__global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
+    constexpr int NW = 8 / NQB;                        // waves per workgroup
+    constexpr int kThreads = NW * kWave;
+    constexpr int WROWS = 32 * NQB;                    // packed rows per wave
+    constexpr int WPS = (kQRows * RB) / WROWS;         // waves per key stream (one per row slice)
+    constexpr int NS = NW / WPS;                       // key streams per workgroup
     constexpr int S = kRingBytes / (NS * kStageBytes); // stages per stream: 2, 4 or 8 (= 2*RB)
-    constexpr int PER = 16 / RB;                       // direct-to-LDS loads per tile per wave
+    constexpr int PER = 16 / WPS;                      // direct-to-LDS loads per tile per wave
+    static_assert(S == 2 * RB && PER >= 2, "stage ring layout");
     extern __shared__ __align__(16) unsigned char smem_raw[];
     Bf16Smem& sm = *reinterpret_cast<Bf16Smem*>(smem_raw);
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int ln = lane & 31, hf = lane >> 5;
-    const int rbw = wave % RB, st = wave / RB;
+    const int wsub = wave % WPS, st = wave / WPS;      // row slice and key stream of this wave
     // blockIdx.x = g + Hkv * (rbg + row_groups * chunk): neighbouring workgroups (dealt round-robin to
     // the XCDs) differ in KV head first, so one XCD's L2 serves few heads
     int bx = blockIdx.x;
@@ -144,7 +148,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
     const int row_groups = a.row_blocks / RB;
     const int rbg = bx % row_groups;
     const int chunk = bx / row_groups;
-    const int rb = rbg * RB + rbw;                     // this wave's row block
+    const int row0 = rbg * RB * kQRows + wsub * WROWS; // this wave's first packed row
     const int b = blockIdx.y;
     const int M = a.M, G = a.G;
     const int n_rows = G * M;
@@ -152,17 +156,18 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
     const unsigned ring_addr = lds_address(ring);
     const int l_row = lane >> 4, l_seg = lane & 15;    // a direct-to-LDS load lands lane l at row l/16, segment l%16
 
-    // ---- Q for this wave's 64 rows: HBM -> LDS (the upper half of the ring is free at this point) ------
-    // Laid out like two K tiles (query block 0, then 1) with the same segment swizzle.
-    const unsigned q_stage = __builtin_amdgcn_readfirstlane(ring_addr + (S / 2 + rbw) * kStageBytes);
+    // ---- Q for this wave's rows: HBM -> LDS (the upper half of the stream's ring is free at this point) -
+    // Each 32-row query block is laid out like a K tile, with the same segment swizzle.
+    const int q_off = (S / 2) * kStageBytes + wsub * (NQB * kTileBytes);
     {
+        const unsigned q_stage = __builtin_amdgcn_readfirstlane(ring_addr + q_off);
         const unsigned long long q_sbase =
             scalar_base(static_cast<const unsigned char*>(a.q) + (int64_t)b * M * a.Hq * (kD * 2));
-        int r = rb * kQRows + l_row;                  // packed row of instruction 0; +4 per instruction
+        int r = row0 + l_row;                         // packed row of instruction 0; +4 per instruction
         int hl = (int)(((float)r + 0.5f) * a.inv_M);  // r / M (exact for these sizes)
         int i = r - hl * M;                           // (head in group, tree row) of packed row r
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
+        for (int j = 0; j < 8 * NQB; ++j) {
             const int row = 4 * (j & 7) + l_row;      // row inside the query block: selects the swizzle
             const bool over = r >= n_rows;            // padding rows re-read the last packed row
             const int ii = over ? M - 1 : i, hh = over ? G - 1 : hl;
@@ -197,12 +202,12 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
 
     // One tile: instruction j (0..7 K, 8..15 V) moves rows 4j..4j+3; lane l lands at byte 16*l of that 1 KB
     // block and fetches the logical segment that the swizzle stores there.  This wave issues the
-    // instructions j = jj*RB + rbw: the first PER/2 of them are K rows, the rest V rows.  The per-lane part of
-    // the address is constant; the tile only moves the (scalar) base.
+    // instructions j = jj*WPS + wsub: the first PER/2 of them are K rows, the rest V rows.  The per-lane part
+    // of the address is constant; the tile only moves the (scalar) base.
     unsigned lane_off[PER];
 #pragma unroll
     for (int jj = 0; jj < PER; ++jj) {
-        const int j = jj * RB + rbw;
+        const int j = jj * WPS + wsub;
         const int row = 4 * (j & 7) + l_row;
         const int seg = (j < 8) ? (l_seg ^ (row & 15)) : (l_seg ^ (l_row << 2));
         lane_off[jj] = (unsigned)row * tok_bytes + (unsigned)(seg * 16);
@@ -215,13 +220,13 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
             const unsigned long long tile_base = scalar_base(base + (size_t)k0 * tok_bytes);
 #pragma unroll
             for (int jj = 0; jj < PER / 2; ++jj) {
-                const int j = (half * (PER / 2) + jj) * RB + rbw;
+                const int j = (half * (PER / 2) + jj) * WPS + wsub;
                 dma16(dst + (j & 7) * 1024, tile_base, lane_off[half * (PER / 2) + jj]);
             }
         } else {                                             // last tile: never read past the sequence's rows
 #pragma unroll
             for (int jj = 0; jj < PER / 2; ++jj) {
-                const int j = (half * (PER / 2) + jj) * RB + rbw;
+                const int j = (half * (PER / 2) + jj) * WPS + wsub;
                 const int row = 4 * (j & 7) + l_row;
                 const unsigned key = (unsigned)min(k0 + row, Lk - 1);
                 const int seg = half ? (l_seg ^ (l_row << 2)) : (l_seg ^ (row & 15));
@@ -276,21 +281,18 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
         }
     }
 
-    // ---- this lane's two queries (column ln of query block 0 and 1): B operands of S^T, kept in registers
-    bf16x8 qreg[2][8];
-    int tree_row[2];         // tree row of the two queries (the mask of a tile is derived from it on demand)
-    {
-        const unsigned char* qs = ring + (S / 2 + rbw) * kStageBytes;
+    // ---- this lane's queries (column ln of each query block): B operands of S^T, kept in registers ------
+    bf16x8 qreg[NQB][8];
+    int tree_row[NQB];       // tree row of the queries (the mask of a tile is derived from it on demand)
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < NQB; ++qb) {
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                qreg[qb][ks] = *reinterpret_cast<const bf16x8*>(qs + qb * kTileBytes + k_off[ks]);
-                park(qreg[qb][ks]);
-            }
-            const int r = min(rb * kQRows + qb * 32 + ln, n_rows - 1);
-            tree_row[qb] = r - (int)(((float)r + 0.5f) * a.inv_M) * M;      // r % M (exact: r < 2^16)
+        for (int ks = 0; ks < 8; ++ks) {
+            qreg[qb][ks] = *reinterpret_cast<const bf16x8*>(ring + q_off + qb * kTileBytes + k_off[ks]);
+            park(qreg[qb][ks]);
         }
+        const int r = min(row0 + qb * 32 + ln, n_rows - 1);
+        tree_row[qb] = r - (int)(((float)r + 0.5f) * a.inv_M) * M;      // r % M
     }
     __syncthreads();         // the Q staging area goes back to the ring
 #pragma unroll
@@ -298,27 +300,29 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
         if (i < n_my) issue_tile(t_begin + i, i);
 
     const float c = a.scale * kLog2e;
-    float m_run[2] = {-INFINITY, -INFINITY};    // running max, in log2 units (score * c)
-    float l_run[2] = {0.f, 0.f};                // this lane's share of the running sum
-    f32x16 o[4][2];
+    float m_run[NQB], l_run[NQB];       // running max in log2 units (score * c); this lane's share of the sum
+    f32x16 o[4][NQB];
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int qb = 0; qb < NQB; ++qb) {
+        m_run[qb] = -INFINITY;
+        l_run[qb] = 0.f;
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
             for (int j = 0; j < 16; ++j) o[dt][qb][j] = 0.f;
+    }
 
     // The product O^T += V^T P^T of a tile is issued one tile late, next to the exponentials of the
     // following tile, so that the matrix pipe and the vector ALU work at the same time.  Carried over:
     // the V^T operands (va) and the probabilities (pb) of the previous tile.
-    bf16x8 va[8], pb[2][2];
+    bf16x8 va[8], pb[NQB][2];
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
 #pragma unroll
         for (int x = 0; x < 8; ++x) va[e][x] = (__bf16)0.f;
     }
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -328,10 +332,10 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt) {
-                o[dt][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks * 4 + dt], pb[0][ks], o[dt][0], 0, 0, 0);
-                o[dt][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks * 4 + dt], pb[1][ks], o[dt][1], 0, 0, 0);
-            }
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int qb = 0; qb < NQB; ++qb)
+                    o[dt][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks * 4 + dt], pb[qb][ks], o[dt][qb], 0, 0, 0);
     };
 
     for (int it = 0; it < n_iter; ++it) {
@@ -340,7 +344,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
             if (n_my - 1 - it >= S - 2) wait_vmcnt<(S - 2) * PER>();    // steady state: S-2 younger tiles in flight
             else wait_vmcnt<0>();                                       // tail: fewer were issued, wait for all
         }
-        if (RB > 1) __syncthreads();                                    // ... and so have the other waves' parts
+        if (WPS > 1) __syncthreads();                                   // ... and so have the other waves' parts
         else {
             __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -358,21 +362,29 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
             ka[ks] = *reinterpret_cast<const bf16x8*>(stg + k_off[ks]);
             park(ka[ks]);
         }
-        f32x16 s[2];
+        // (two accumulation chains per query block, summed afterwards: consecutive matrix instructions
+        //  then never wait for each other's result)
+        f32x16 s[NQB], s_odd[NQB];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) { s[0][j] = 0.f; s[1][j] = 0.f; }
+        for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[0][ks], s[0], 0, 0, 0);
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[1][ks], s[1], 0, 0, 0);
-        }
+            for (int j = 0; j < 16; ++j) { s[qb][j] = 0.f; s_odd[qb][j] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 8; ks += 2)
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) {
+                s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[qb][ks], s[qb], 0, 0, 0);
+                s_odd[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks + 1], qreg[qb][ks + 1], s_odd[qb], 0, 0, 0);
+            }
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) s[qb] += s_odd[qb];
 
         if (more) issue_half(t_begin + it + S - 1, (it + S - 1) % S, 1);      // spread the requests: they queue in the texture path
 
         // mask (only tiles touching the soft-prompt slots, the new rows or the tail)
         if ((k0 < a.soft_len) || (k0 + kTK > P)) {
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb) {
+            for (int qb = 0; qb < NQB; ++qb) {
                 // rare (a few tiles per sequence): rebuild the row's ancestor mask from the parent array
                 unsigned long long bits0, bits1;
                 ancestor_bits(sm.parent, tree_row[qb], &bits0, &bits1);
@@ -385,9 +397,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
         }
 
         // online softmax; the max is raised lazily (probabilities may reach 2^kTau, harmless in fp32/bf16)
-        float tmax[2];
+        float tmax[NQB];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < NQB; ++qb) {
             float x = s[qb][0];
 #pragma unroll
             for (int j = 1; j < 16; ++j) x = fmaxf(x, s[qb][j]);
@@ -395,22 +407,26 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
         }
         if (it == 0) {
             // nothing accumulated yet: adopt the tile's max as the reference
-            m_run[0] = tmax[0];
-            m_run[1] = tmax[1];
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) m_run[qb] = tmax[qb];
         } else {
-            const bool raise0 = tmax[0] > m_run[0] + kTau, raise1 = tmax[1] > m_run[1] + kTau;
-            if (__any(raise0 || raise1)) {
+            bool raise[NQB], any = false;
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) {
+                raise[qb] = tmax[qb] > m_run[qb] + kTau;
+                any = any || raise[qb];
+            }
+            if (__any(any)) {
                 // rare: bring O up to date with the pending product, then rescale it to the new reference
                 pv_mfma();
 #pragma unroll
-                for (int qb = 0; qb < 2; ++qb) {
+                for (int qb = 0; qb < NQB; ++qb) {
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                         for (int x = 0; x < 8; ++x) pb[qb][ks][x] = (__bf16)0.f;
-                    const bool raise = qb ? raise1 : raise0;
-                    const float m_new = raise ? tmax[qb] : m_run[qb];
-                    const float alpha = raise ? __builtin_amdgcn_exp2f(m_run[qb] - m_new) : 1.f;   // exp2(-inf) = 0
+                    const float m_new = raise[qb] ? tmax[qb] : m_run[qb];
+                    const float alpha = raise[qb] ? __builtin_amdgcn_exp2f(m_run[qb] - m_new) : 1.f;   // exp2(-inf) = 0
                     m_run[qb] = m_new;
                     l_run[qb] *= alpha;
 #pragma unroll
@@ -424,7 +440,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
         // previous tile's O^T += V^T P^T (matrix pipe) next to this tile's exponentials (vector ALU)
         pv_mfma();
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < NQB; ++qb) {
             const float mc = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
             float sum = 0.f;
 #pragma unroll
@@ -452,18 +468,19 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
     pv_mfma();               // the last tile's product
 
     // ---- merge the streams through LDS -------------------------------------------------------------------
-    // Merge buffer: [wave][64 rows][32 float4], float4 column c of row r stored at column c ^ (r & 31).
+    // Merge buffer: [wave][its rows][32 float4]; float4 column c of a wave's row r is stored at column c ^ (r & 31).
     wait_vmcnt<0>();
     __syncthreads();       // every wave is done with the stage ring
     f32x4* mbuf = reinterpret_cast<f32x4*>(sm.big);
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < NQB; ++qb) {
         const float l_tot = cross_half_sum(l_run[qb]);
+        const int mrow = wave * WROWS + qb * 32 + ln;
         if (hf == 0) {
-            sm.ml[wave][qb * 32 + ln][0] = m_run[qb];
-            sm.ml[wave][qb * 32 + ln][1] = l_tot;
+            sm.ml[mrow][0] = m_run[qb];
+            sm.ml[mrow][1] = l_tot;
         }
-        f32x4* orow = mbuf + (wave * kQRows + qb * 32 + ln) * 32;
+        f32x4* orow = mbuf + mrow * 32;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -476,22 +493,22 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
     // 64*RB rows of 128 values leave as bf16: 16 lanes cover one 256-byte row, so a store instruction of the
     // wave writes 1 KB of consecutive memory (4 rows of a partial result; rows of the output are 256-byte runs)
 #pragma unroll
-    for (int k = 0; k < 4 * RB; ++k) {
+    for (int k = 0; k < (kQRows * RB * 16) / kThreads; ++k) {
         const int idx = k * kThreads + tid;
         const int row_l = idx >> 4, c16 = idx & 15;       // row of the workgroup, 16-byte column of the row
-        const int w_rb = row_l / kQRows, qi = row_l % kQRows;
+        const int rs = row_l / WROWS, lr = row_l % WROWS; // row slice (wave within a stream), row inside the slice
         float mw[NS], mx = -INFINITY;
 #pragma unroll
-        for (int s2 = 0; s2 < NS; ++s2) { mw[s2] = sm.ml[s2 * RB + w_rb][qi][0]; mx = fmaxf(mx, mw[s2]); }
+        for (int s2 = 0; s2 < NS; ++s2) { mw[s2] = sm.ml[(s2 * WPS + rs) * WROWS + lr][0]; mx = fmaxf(mx, mw[s2]); }
         const float mxs = (mx == -INFINITY) ? 0.f : mx;
         float wgt[NS], L = 0.f;
 #pragma unroll
         for (int s2 = 0; s2 < NS; ++s2) {
             wgt[s2] = __builtin_amdgcn_exp2f(mw[s2] - mxs);
-            L += wgt[s2] * sm.ml[s2 * RB + w_rb][qi][1];
+            L += wgt[s2] * sm.ml[(s2 * WPS + rs) * WROWS + lr][1];
         }
-        const int rbo = rbg * RB + w_rb;
-        const int r = rbo * kQRows + qi;
+        const int r = rbg * RB * kQRows + row_l;          // packed row
+        const int rbo = r / kQRows, qi = r % kQRows;      // its 64-row block and row inside the block
         const bool row_live = r < n_rows;
         const int hl = row_live ? (int)(((float)r + 0.5f) * a.inv_M) : 0;
         const int i = row_live ? r - hl * M : 0, h = g * G + hl;
@@ -504,9 +521,9 @@ __global__ __launch_bounds__(kThreads, 1) void attn_bf16_kernel(AttnArgs a) {
         f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s2 = 0; s2 < NS; ++s2) {
-            const f32x4* prow = mbuf + ((s2 * RB + w_rb) * kQRows + qi) * 32;
-            acc0 += prow[(2 * c16) ^ (qi & 31)] * wgt[s2];
-            acc1 += prow[(2 * c16 + 1) ^ (qi & 31)] * wgt[s2];
+            const f32x4* prow = mbuf + ((s2 * WPS + rs) * WROWS + lr) * 32;
+            acc0 += prow[(2 * c16) ^ (lr & 31)] * wgt[s2];
+            acc1 += prow[(2 * c16 + 1) ^ (lr & 31)] * wgt[s2];
         }
         bf16x8 ob;
         ob[0] = (__bf16)(acc0[0] * inv); ob[1] = (__bf16)(acc0[1] * inv);
@@ -584,21 +601,21 @@ __global__ __launch_bounds__(256) void attn_bf16_combine_kernel(AttnArgs a) {
     if (a.lse && d0 == 0) a.lse[((int64_t)b * a.Hq + h) * a.M + i] = (mx + log2f(L)) * kLn2;
 }
 
-template <int RB>
-hipError_t launch_rb(const AttnArgs& a, hipStream_t s) {
+template <int RB, int NQB>
+hipError_t launch_variant(const AttnArgs& a, hipStream_t s) {
     static std::atomic<unsigned> attr_done{0};       // one bit per device
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     const unsigned bit = 1u << (dev & 31);
     if (!(attr_done.load(std::memory_order_acquire) & bit)) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<RB>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<RB, NQB>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Bf16Smem));
         if (e != hipSuccess) return e;
         attr_done.fetch_or(bit, std::memory_order_release);
     }
     const dim3 grid(a.Hkv * (a.row_blocks / RB) * a.n_chunks, a.B);
-    attn_bf16_kernel<RB><<<grid, kThreads, sizeof(Bf16Smem), s>>>(a);
+    attn_bf16_kernel<RB, NQB><<<grid, 512 / NQB, sizeof(Bf16Smem), s>>>(a);
     return hipGetLastError();
 }
 
@@ -606,10 +623,18 @@ hipError_t launch_rb(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
     hipError_t e;
-    switch (a.rb_per_wg) {
-        case 1: e = launch_rb<1>(a, s); break;
-        case 2: e = launch_rb<2>(a, s); break;
-        default: e = launch_rb<4>(a, s); break;
+    if (a.wave_rows == 64) {
+        switch (a.rb_per_wg) {
+            case 1: e = launch_variant<1, 2>(a, s); break;
+            case 2: e = launch_variant<2, 2>(a, s); break;
+            default: e = launch_variant<4, 2>(a, s); break;
+        }
+    } else {
+        switch (a.rb_per_wg) {
+            case 1: e = launch_variant<1, 1>(a, s); break;
+            case 2: e = launch_variant<2, 1>(a, s); break;
+            default: e = launch_variant<4, 1>(a, s); break;
+        }
     }
     if (e != hipSuccess) return e;
     if (a.n_chunks > 1) {
