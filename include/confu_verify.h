@@ -51,6 +51,7 @@ extern "C" {
 #define TV_STATUS_BAD_KIND      2   /* kind not 0/1, or a draft node hangs off a contemplate row */
 #define TV_STATUS_BAD_PREFIX    4   /* prefix_len < soft_len, < 0 or > max_prefix_len */
 #define TV_STATUS_BAD_TOKEN     8   /* token id outside [0, V) */
+#define TV_STATUS_INTERNAL     16   /* a bounded wait between workgroups ran out (tree_accept, draft rules) */
 
 /* ---- limits -------------------------------------------------------------------- */
 #define TV_MAX_ROWS   128          /* M (attention) and T (acceptance) */

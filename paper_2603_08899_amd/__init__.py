@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libconfu_verify.so")
 
 TV_OK, TV_ERR_INVALID_ARG, TV_ERR_WORKSPACE, TV_ERR_LAUNCH, TV_ERR_UNSUPPORTED = 0, 1, 2, 3, 4
 TV_STATUS_BAD_PARENT, TV_STATUS_BAD_KIND, TV_STATUS_BAD_PREFIX, TV_STATUS_BAD_TOKEN = 1, 2, 4, 8
+TV_STATUS_INTERNAL = 16
 TV_MAX_ROWS = 128
 TV_DTYPE_F32, TV_DTYPE_BF16 = 0, 1
 TV_KIND_NODE, TV_KIND_CONTEMPLATE = 0, 1

@@ -14,8 +14,11 @@
 //                            rejected), so every parent is processed independently: one workgroup per
 //                            parent walks its children in order and needs one vocabulary-wide
 //                            reduction (the corrected law's normaliser) per child.
-//   3. accept_walk_kernel    one workgroup per sequence: follows the accept bits from the root, then
-//                            draws the final token by inverse CDF at the stop node.
+//   3. accept_walk_kernel    a few workgroups per sequence.  Each one repeats the (cheap, LDS-only)
+//                            walk from the root, then sums the final law over its own slice of the
+//                            vocabulary; the workgroup that publishes its slice last finds the slice
+//                            in which the running sum crosses the uniform, rescans that slice in
+//                            vocabulary order and writes the results.
 #include "tv_internal.hpp"
 
 namespace tv {
@@ -23,8 +26,10 @@ namespace tv {
 namespace {
 
 constexpr int kStatThreads = 256;
-constexpr int kWalkThreads = 1024;
-constexpr int kWalkWaves = kWalkThreads / kWave;
+constexpr int kChainThreads = 256;
+constexpr int kChainWaves = kChainThreads / kWave;
+constexpr int kDrawThreads = 256;
+constexpr int kDrawWaves = kDrawThreads / kWave;
 constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -51,14 +56,6 @@ __device__ __forceinline__ Red red_merge(const Red& a, const Red& b, float it_lo
     return r;
 }
 
-__device__ __forceinline__ Red red_shfl_xor(const Red& a, int o) {
-    Red r;
-    r.m = __shfl_xor(a.m, o, kWave);
-    r.am = __shfl_xor(a.am, o, kWave);
-    r.s = __shfl_xor(a.s, o, kWave);
-    return r;
-}
-
 template <bool kGreedy>
 __device__ __forceinline__ void red_push(Red& r, float z, int v, float it_log2e) {
     if (z > r.m) {
@@ -69,6 +66,24 @@ __device__ __forceinline__ void red_push(Red& r, float z, int v, float it_log2e)
     if (!kGreedy) r.s += unnorm_prob(z, r.m, it_log2e);
 }
 
+template <bool kGreedy>
+__device__ __forceinline__ void red_push4(Red& r, const float4 x, int v0, float it) {
+    const float mx = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
+    if (mx > r.m) {
+        if (!kGreedy && r.s != 0.0) r.s *= exp2((double)(r.m - mx) * (double)it);
+        r.m = mx;
+        r.am = (x.x == mx) ? v0 : (x.y == mx) ? v0 + 1 : (x.z == mx) ? v0 + 2 : v0 + 3;
+    }
+    if (!kGreedy) {
+        r.s += unnorm_prob(x.x, r.m, it);
+        r.s += unnorm_prob(x.y, r.m, it);
+        r.s += unnorm_prob(x.z, r.m, it);
+        r.s += unnorm_prob(x.w, r.m, it);
+    }
+}
+
+__device__ __forceinline__ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
 // ---- 1. statistics -----------------------------------------------------------------------------------
 template <bool kGreedy>
 __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a) {
@@ -76,41 +91,53 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a
     const int mat = blockIdx.y / a.T;
     const int row = blockIdx.y % a.T;
     const int b = blockIdx.z;
+    // the kernels that follow on the stream count arriving workgroups from zero
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        if (blockIdx.y == 0) a.arrivals[b] = 0u;
+        if (a.n_mat == 2 && mat == 0) a.chain_arrivals[(int64_t)b * a.T + row] = 0u;
+        if (a.n_mat == 2 && blockIdx.y == 0 && b == 0) *a.chain_fail = 0;
+    }
     const float* base = (mat == 0 ? a.target : a.draft) + ((int64_t)b * a.T + row) * a.row_stride;
     const int begin = split * a.split_len;
     const int end = min(a.V, begin + a.split_len);
     const float it = kGreedy ? 0.f : kLog2e / a.temperature;
 
     Red r{-INFINITY, 0x7fffffff, 0.0};
-    const bool vec_ok = ((reinterpret_cast<uintptr_t>(base + begin) & 15) == 0);
     int v = begin;
-    if (vec_ok) {
+    if (aligned16(base + begin)) {
         const int n4 = (end - begin) / 4;
         const float4* b4 = reinterpret_cast<const float4*>(base + begin);
-        for (int i = threadIdx.x; i < n4; i += kStatThreads) {
-            const float4 x = b4[i];
-            const int v0 = begin + 4 * i;
-            const float mx = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
-            if (mx > r.m) {
-                if (!kGreedy && r.s != 0.0) r.s *= exp2((double)(r.m - mx) * (double)it);
-                r.m = mx;
-                r.am = (x.x == mx) ? v0 : (x.y == mx) ? v0 + 1 : (x.z == mx) ? v0 + 2 : v0 + 3;
-            }
-            if (!kGreedy) {
-                r.s += unnorm_prob(x.x, r.m, it);
-                r.s += unnorm_prob(x.y, r.m, it);
-                r.s += unnorm_prob(x.z, r.m, it);
-                r.s += unnorm_prob(x.w, r.m, it);
-            }
+        int i = threadIdx.x;
+        for (; i + 3 * kStatThreads < n4; i += 4 * kStatThreads) {      // four loads in flight per lane
+            const float4 x0 = b4[i], x1 = b4[i + kStatThreads], x2 = b4[i + 2 * kStatThreads],
+                         x3 = b4[i + 3 * kStatThreads];
+            red_push4<kGreedy>(r, x0, begin + 4 * i, it);
+            red_push4<kGreedy>(r, x1, begin + 4 * (i + kStatThreads), it);
+            red_push4<kGreedy>(r, x2, begin + 4 * (i + 2 * kStatThreads), it);
+            red_push4<kGreedy>(r, x3, begin + 4 * (i + 3 * kStatThreads), it);
         }
+        for (; i < n4; i += kStatThreads) red_push4<kGreedy>(r, b4[i], begin + 4 * i, it);
         v = begin + 4 * n4;
     }
     for (int i = v + threadIdx.x; i < end; i += kStatThreads) red_push<kGreedy>(r, base[i], i, it);
 
+    // wave reduction: the maximum (lowest index on ties) first, then one rescale per lane and a plain sum
+    float wm = r.m;
+    int wam = r.am;
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) r = red_merge(r, red_shfl_xor(r, o), it);
+    for (int o = 32; o > 0; o >>= 1) {
+        const float om = __shfl_xor(wm, o, kWave);
+        const int oam = __shfl_xor(wam, o, kWave);
+        if (om > wm || (om == wm && oam < wam)) { wm = om; wam = oam; }
+    }
+    double ws = 0.0;
+    if (!kGreedy) {
+        double s = r.s;
+        if (s != 0.0 && r.m != wm) s *= exp2((double)(r.m - wm) * (double)it);
+        ws = wave_sum(s);
+    }
     __shared__ Red wred[kStatThreads / kWave];
-    if ((threadIdx.x & (kWave - 1)) == 0) wred[threadIdx.x / kWave] = r;
+    if ((threadIdx.x & (kWave - 1)) == 0) wred[threadIdx.x / kWave] = Red{wm, wam, ws};
     __syncthreads();
     if (threadIdx.x == 0) {
         Red t = wred[0];
@@ -122,15 +149,36 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a
     }
 }
 
-// Merged statistics of one row, from its ranges.
-__device__ __forceinline__ Red merged_row_stat(const AcceptArgs& a, int b, int mat, int row, float it) {
-    const RowStat* st = a.stats + ((((int64_t)b * a.n_mat + mat) * a.T + row) * a.splits);
-    Red t{st[0].max_logit, st[0].argmax, st[0].sum_exp};
-    for (int s = 1; s < a.splits; ++s) {
-        if (s * a.split_len >= a.V) break;
-        t = red_merge(t, Red{st[s].max_logit, st[s].argmax, st[s].sum_exp}, it);
+// Statistics of one row merged from its ranges by a group of g consecutive lanes of one wave (g a power
+// of two, groups aligned to g; `sub` is the lane's index in its group).  Every lane of the wave calls
+// this; lanes whose group has no row pass active = false.  All lanes of a group return the result.
+__device__ __forceinline__ Red group_row_stat(const AcceptArgs& a, int b, int mat, int row, bool active,
+                                              int sub, int g, float it, bool want_sum) {
+    const RowStat* st = a.stats + ((((int64_t)b * a.n_mat + mat) * a.T + (active ? row : 0)) * a.splits);
+    float m = -INFINITY;
+    int am = 0x7fffffff;
+    if (active)
+        for (int s = sub; s < a.splits; s += g) {
+            const float ms = st[s].max_logit;
+            const int as = st[s].argmax;
+            if (ms > m || (ms == m && as < am)) { m = ms; am = as; }
+        }
+    for (int o = 1; o < g; o <<= 1) {
+        const float om = __shfl_xor(m, o, kWave);
+        const int oam = __shfl_xor(am, o, kWave);
+        if (om > m || (om == m && oam < am)) { m = om; am = oam; }
     }
-    return t;
+    double sum = 0.0;
+    if (want_sum) {
+        if (active)
+            for (int s = sub; s < a.splits; s += g) {
+                const double ss = st[s].sum_exp;
+                const float ms = st[s].max_logit;
+                sum += (ms == m) ? ss : ss * unnorm_prob(ms, m, it);
+            }
+        for (int o = 1; o < g; o <<= 1) sum += __shfl_xor(sum, o, kWave);
+    }
+    return Red{m, am, sum};
 }
 
 // ---- the law at a node after a number of rejections, one vocabulary entry at a time -------------------
@@ -142,109 +190,256 @@ struct ChainStep {        // what rejecting one child did to the laws
 };
 
 template <int kRule>
+__device__ __forceinline__ void law_step(int v, const ChainStep& st, double& p, double& q) {
+    if (kRule == TV_RULE_DETERMINISTIC) {
+        p = (v == st.tok) ? 0.0 : ((st.inv_ps > 0.0) ? p * st.inv_ps : p);
+    } else {
+        const double r = fmax(p - q, 0.0);
+        if (st.inv_z > 0.0) p = r * st.inv_z;
+        if (kRule == TV_RULE_DRAFT_WOR) q = (v == st.tok) ? 0.0 : ((st.inv_qs > 0.0) ? q * st.inv_qs : q);
+    }
+}
+
+template <int kRule>
 __device__ __forceinline__ void law_after(int v, double p0, double q0, const ChainStep* steps, int n,
                                           double* p_out, double* q_out) {
     double p = p0, q = q0;
-    for (int i = 0; i < n; ++i) {
-        const ChainStep st = steps[i];
-        if (kRule == TV_RULE_DETERMINISTIC) {
-            p = (v == st.tok) ? 0.0 : ((st.inv_ps > 0.0) ? p * st.inv_ps : p);
-        } else {
-            const double r = fmax(p - q, 0.0);
-            if (st.inv_z > 0.0) p = r * st.inv_z;
-            if (kRule == TV_RULE_DRAFT_WOR) q = (v == st.tok) ? 0.0 : ((st.inv_qs > 0.0) ? q * st.inv_qs : q);
-        }
-    }
+    for (int i = 0; i < n; ++i) law_step<kRule>(v, steps[i], p, q);
     *p_out = p;
     *q_out = q;
 }
 
-__device__ __forceinline__ double block_sum(double x, double* scratch /* kWalkWaves doubles */) {
+template <int kWaves>
+__device__ __forceinline__ double block_sum(double x, double* scratch /* kWaves doubles */) {
     x = wave_sum(x);
     __syncthreads();
     if ((threadIdx.x & (kWave - 1)) == 0) scratch[threadIdx.x / kWave] = x;
     __syncthreads();
     double t = 0.0;
-    for (int w = 0; w < (int)(blockDim.x / kWave); ++w) t += scratch[w];
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) t += scratch[w];
     return t;
 }
 
 // ---- 2. sibling chains (draft rules) --------------------------------------------------------------------
+// The launch holds a whole number of groups of chain_slices workgroups, no more than fit on the device at
+// once.  A group takes the nodes that have children one after the other; each workgroup holds its slice of
+// the node's two laws in registers and the group steps through the children in order.  One child costs one
+// group-wide reduction (the normaliser of the corrected law): every workgroup publishes its partial sum,
+// counts itself on the node's arrival counter and waits until the count shows the whole group.
+//
+// Forward progress: a workgroup waits only for workgroups of its own launch, and the host sizes the grid so
+// that all of them are resident together.  The wait is bounded all the same: past kSpinLimit polls the
+// workgroup gives up, raises chain_fail (the walk kernel turns it into TV_STATUS_INTERNAL) and exits.
+constexpr int kChainPer = 16;                                  // vocabulary entries per lane
+constexpr int kChainQuads = kChainPer / 4;
+constexpr unsigned kSpinLimit = 1u << 20;
+
+__device__ __forceinline__ double agent_load(const double* p) {
+    return __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<const unsigned long long*>(p),
+                                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+__device__ __forceinline__ void agent_store(double* p, double x) {
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), (unsigned long long)__double_as_longlong(x),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// What workgroups hand to each other inside a kernel goes through agent-scope atomic stores and loads, which
+// pass by the caches that are not coherent across the device; a lane then only has to wait until its stores
+// have completed before it counts itself in.  (A device-wide release fence would write back the whole L2.)
+__device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Four consecutive logits of a row (entries past the end of the row read as -infinity, which the
+// laws map to zero mass).
+__device__ __forceinline__ void load_quad(const float* row, bool vec_ok, int v, int V, float* dst) {
+    if (vec_ok && v + 3 < V) {
+        const float4 x = *reinterpret_cast<const float4*>(row + v);
+        dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dst[e] = (v + e < V) ? row[v + e] : -INFINITY;
+    }
+}
+
 template <int kRule>
-__global__ __launch_bounds__(kWalkThreads) void accept_chain_kernel(AcceptArgs a) {
-    const int u = blockIdx.x;
-    const int b = blockIdx.y;
-    const int T = a.T, V = a.V;
+__global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs a) {
+    const int T = a.T, V = a.V, S = a.chain_slices;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     __shared__ int s_parent[kMaxRows];
     __shared__ int s_token[kMaxRows];
     __shared__ int s_child[kMaxRows];
     __shared__ ChainStep s_steps[kMaxRows];
-    __shared__ double s_red[kWalkWaves];
-    __shared__ int s_flag, s_k;
-    for (int i = threadIdx.x; i < T; i += blockDim.x) {
-        s_parent[i] = a.parent[(int64_t)b * T + i];
-        s_token[i] = a.token[(int64_t)b * T + i];
-    }
+    __shared__ double s_red[kChainWaves];
+    __shared__ Red s_stat[2];
+    __shared__ int s_internal[kMaxRows];
+    __shared__ int s_has[kMaxRows];
+    __shared__ int s_flag, s_k, s_fail, s_nint;
+    const int n_groups = gridDim.x / S;
+    const int group = blockIdx.x / S, slice = blockIdx.x % S;
+    if (group >= n_groups) return;
+    int loaded_b = -1;
+    for (int item = group;; item += n_groups) {
+    const int b = item / T, r = item % T;
+    if (b >= a.B) break;
     __syncthreads();
-    int bad = validate_tree(s_parent, nullptr, T, &s_flag);
-    if (threadIdx.x == 0) {
-        int k = 0, tok_bad = 0;
-        for (int c = 0; c < T; ++c) {
-            if (s_token[c] < 0 || s_token[c] >= V) tok_bad = 1;
-            if (c > u && s_parent[c] == u) s_child[k++] = c;
+    if (b != loaded_b) {
+        loaded_b = b;
+        for (int i = tid; i < T; i += kChainThreads) {
+            s_parent[i] = a.parent[(int64_t)b * T + i];
+            s_token[i] = a.token[(int64_t)b * T + i];
+            s_has[i] = 0;
         }
-        s_k = (tok_bad || bad) ? 0 : k;
+        __syncthreads();
+        int bad = validate_tree(s_parent, nullptr, T, &s_flag);
+        int tok_bad = 0;
+        for (int i = tid; i < T; i += kChainThreads)
+            if (s_token[i] < 0 || s_token[i] >= V) tok_bad = 1;
+        if (tok_bad) atomicOr(&s_flag, TV_STATUS_BAD_TOKEN);
+        __syncthreads();
+        bad = s_flag;
+        if (!bad)
+            for (int i = 1 + tid; i < T; i += kChainThreads) s_has[s_parent[i]] = 1;
+        __syncthreads();
+        if (wave == 0) {        // the nodes that have children, in index order
+            unsigned long long lo = __ballot(lane < T && s_has[lane]);
+            unsigned long long hi = __ballot(lane + kWave < T && s_has[lane + kWave]);
+            if (lane == 0) {
+                int n = 0;
+                while (lo) { s_internal[n++] = __ffsll((long long)lo) - 1; lo &= lo - 1; }
+                while (hi) { s_internal[n++] = kWave + __ffsll((long long)hi) - 1; hi &= hi - 1; }
+                s_nint = bad ? 0 : n;       // malformed input: nothing to do (the walk kernel reports it)
+                s_fail = 0;
+            }
+        }
+        __syncthreads();
+    }
+    if (r >= s_nint) continue;
+    const int u = s_internal[r];
+    if (wave == 0) {            // the children of u, in index order
+        const int par_lo = (lane < T) ? s_parent[lane] : -2;
+        const int par_hi = (lane + kWave < T) ? s_parent[lane + kWave] : -2;
+        unsigned long long kids_lo = __ballot(par_lo == u), kids_hi = __ballot(par_hi == u);
+        if (lane == 0) {
+            int k = 0;
+            while (kids_lo) { s_child[k++] = __ffsll((long long)kids_lo) - 1; kids_lo &= kids_lo - 1; }
+            while (kids_hi) { s_child[k++] = kWave + __ffsll((long long)kids_hi) - 1; kids_hi &= kids_hi - 1; }
+            s_k = k;
+        }
     }
     __syncthreads();
     const int k = s_k;
-    if (k == 0) return;     // leaf, or malformed input (the walk kernel reports it)
 
     const float it = kLog2e / a.temperature;
-    const Red sp = merged_row_stat(a, b, 0, u, it);
-    const Red sq = merged_row_stat(a, b, 1, u, it);
+    if (wave < 2) {         // wave 0: the target row's statistics, wave 1: the draft row's
+        const Red r = group_row_stat(a, b, wave, u, true, lane, kWave, it, true);
+        if (lane == 0) s_stat[wave] = r;
+    }
+    __syncthreads();
+    const Red sp = s_stat[0], sq = s_stat[1];
     const double inv_sp = 1.0 / sp.s, inv_sq = 1.0 / sq.s;
     const float* prow = a.target + ((int64_t)b * T + u) * a.row_stride;
     const float* qrow = a.draft + ((int64_t)b * T + u) * a.row_stride;
+    const bool vec_ok = aligned16(prow) && aligned16(qrow);
+    __shared__ float s_zp[kMaxRows], s_zq[kMaxRows], s_u[kMaxRows];      // per child: its token's logits, its uniform
+    if (tid < k) {
+        const int c = s_child[tid];
+        s_zp[tid] = prow[s_token[c]];
+        s_zq[tid] = qrow[s_token[c]];
+        s_u[tid] = a.uniforms[(int64_t)b * 2 * T + c];
+    }
+    __syncthreads();
 
+    // this lane's entries of the two laws: quad qd covers v = slice_base + (qd * threads + tid) * 4 ...
+    const int slice_base = slice * (kChainThreads * kChainPer);
+    double p[kChainPer], q[kChainPer];
+#pragma unroll
+    for (int qd = 0; qd < kChainQuads; ++qd) {
+        const int v = slice_base + (qd * kChainThreads + tid) * 4;
+        float zp[4], zq[4];
+        if (v < V) {
+            load_quad(prow, vec_ok, v, V, zp);
+            load_quad(qrow, vec_ok, v, V, zq);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { zp[e] = -INFINITY; zq[e] = -INFINITY; }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            p[4 * qd + e] = unnorm_prob(zp[e], sp.m, it) * inv_sp;
+            q[4 * qd + e] = unnorm_prob(zq[e], sq.m, it) * inv_sq;
+        }
+    }
+
+    unsigned* arrived = a.chain_arrivals + (int64_t)b * T + u;
     for (int j = 0; j < k; ++j) {
         const int c = s_child[j];
-        if (threadIdx.x == 0) {
+        if (tid == 0) {
+            // the accept test of child j, as if its earlier siblings were all rejected
             const int x = s_token[c];
-            double p, q;
-            law_after<kRule>(x, unnorm_prob(prow[x], sp.m, it) * inv_sp, unnorm_prob(qrow[x], sq.m, it) * inv_sq,
-                             s_steps, j, &p, &q);
-            const double uc = (double)a.uniforms[(int64_t)b * 2 * T + c];
-            a.accept_bit[(int64_t)b * T + c] = (uc * q < p) ? 1 : 0;
+            double px, qx;
+            law_after<kRule>(x, unnorm_prob(s_zp[j], sp.m, it) * inv_sp, unnorm_prob(s_zq[j], sq.m, it) * inv_sq,
+                             s_steps, j, &px, &qx);
+            if (slice == 0) a.accept_bit[(int64_t)b * T + c] = ((double)s_u[j] * qx < px) ? 1 : 0;
             ChainStep st;
             st.tok = x;
             st.inv_z = 0.0;
             st.inv_ps = 1.0;
-            const double qs = 1.0 - q;      // mass of q left once x is removed
+            const double qs = 1.0 - qx;      // mass of q left once x is removed
             st.inv_qs = (kRule == TV_RULE_DRAFT_WOR && qs > 0.0) ? 1.0 / qs : 0.0;
             s_steps[j] = st;
         }
-        __syncthreads();
-        // normaliser of the corrected law after rejecting child j
+        // normaliser of the corrected law after rejecting child j: this slice's share ...
         double part = 0.0;
-        for (int v = threadIdx.x; v < V; v += blockDim.x) {
-            double p, q;
-            law_after<kRule>(v, unnorm_prob(prow[v], sp.m, it) * inv_sp, unnorm_prob(qrow[v], sq.m, it) * inv_sq,
-                             s_steps, j, &p, &q);
-            part += fmax(p - q, 0.0);
-        }
-        const double z = block_sum(part, s_red);
-        if (threadIdx.x == 0) {
-            s_steps[j].inv_z = (z > 0.0) ? 1.0 / z : 0.0;
-            a.chain_z[(int64_t)b * T + c] = z;
+#pragma unroll
+        for (int e = 0; e < kChainPer; ++e) part += fmax(p[e] - q[e], 0.0);
+        const double mine = block_sum<kChainWaves>(part, s_red);
+        double* parts = a.chain_parts + ((((int64_t)b * T + u) * 2) + (j & 1)) * S;   // two buffers, by parity of j
+        if (tid == 0) {
+            agent_store(parts + slice, mine);
+            stores_done();                                     // publish, then count
+            atomicAdd(arrived, 1u);
+            const unsigned target = (unsigned)(j + 1) * (unsigned)S;
+            unsigned polls = 0;
+            int fail = 0;
+            while (__hip_atomic_load(arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+                __builtin_amdgcn_s_sleep(2);
+                if (++polls > kSpinLimit) { fail = 1; break; }
+            }
+            s_fail = fail;
         }
         __syncthreads();
+        if (s_fail) {
+            if (tid == 0) *a.chain_fail = 1;
+            return;
+        }
+        // ... and the whole: every workgroup of the group adds the shares in the same order
+        if (wave == 0) {
+            double z = 0.0;
+            for (int s = lane; s < S; s += kWave) z += agent_load(parts + s);
+            z = wave_sum(z);
+            if (lane == 0) {
+                s_steps[j].inv_z = (z > 0.0) ? 1.0 / z : 0.0;
+                if (slice == 0) a.chain_z[(int64_t)b * T + c] = z;
+            }
+        }
+        __syncthreads();
+        if (j + 1 < k) {
+            const ChainStep st = s_steps[j];
+#pragma unroll
+            for (int qd = 0; qd < kChainQuads; ++qd) {
+                const int v = slice_base + (qd * kChainThreads + tid) * 4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) law_step<kRule>(v + e, st, p[4 * qd + e], q[4 * qd + e]);
+            }
+        }
     }
+    }   // next node of this group
 }
 
 // ---- 3. walk + final draw ---------------------------------------------------------------------------------
 struct WalkShared {
     int parent[kMaxRows];
     int token[kMaxRows];
+    int path[kMaxRows];
     float unif[2 * kMaxRows];
     float m_p[kMaxRows];
     float m_q[kMaxRows];
@@ -252,30 +447,63 @@ struct WalkShared {
     double inv_s_q[kMaxRows];
     int argmax[kMaxRows];
     float z_tok_p[kMaxRows];      // target logit of node c's token in its parent's row
-    float z_tok_q[kMaxRows];
+    float z_tok_q[kMaxRows];      // draft logit of the same entry
+    int abit[kMaxRows];           // draft rules: the chain kernel's accept bit of node c
+    double chain_z[kMaxRows];     // draft rules: normaliser of the corrected law after rejecting node c
     ChainStep steps[kMaxRows];
-    double red[kWalkWaves];
-    double wave_tot[kWalkWaves];
-    double chunk_tot[2 * kWalkWaves];
-    int last_pos[kWalkWaves];
+    double red[kDrawWaves];
+    double wave_tot[kDrawWaves];
+    double base;                  // mass of the final law in the slices before the chosen one
     int flag, cur, n_steps, rejected_any, len, tok_out;
+    int slice_last, is_last, s_star, hit, seg_last;
 };
 
-template <int kRule>
-__device__ __forceinline__ double final_law(const AcceptArgs& a, const WalkShared& sh, const float* prow,
-                                            const float* qrow, int node, int v, float it) {
-    const double p0 = unnorm_prob(prow[v], sh.m_p[node], it) * sh.inv_s_p[node];
-    double q0 = 0.0;
-    if (kRule == TV_RULE_DRAFT_WOR || kRule == TV_RULE_DRAFT_WR)
-        q0 = unnorm_prob(qrow[v], sh.m_q[node], it) * sh.inv_s_q[node];
-    double p, q;
-    law_after<kRule>(v, p0, q0, sh.steps, sh.n_steps, &p, &q);
-    return p;
+// One lane's contiguous run of vocabulary entries [v0, v0 + 4*quads).  kFind = false: the mass of the
+// final law over the run and the last entry that carries mass.  kFind = true: the running sum starts at
+// *mass and the first entry at which it exceeds u is returned in *found (-1 if none).
+template <int kRule, bool kFind>
+__device__ __forceinline__ void segment_scan(const WalkShared& sh, const float* prow, const float* qrow,
+                                             bool vec_ok, int node, int v0, int quads, int V, float it,
+                                             double u, double* mass, int* last, int* found) {
+    constexpr bool kDraft = (kRule == TV_RULE_DRAFT_WOR || kRule == TV_RULE_DRAFT_WR);
+    double acc = kFind ? *mass : 0.0;
+    int lst = -1, fnd = -1;
+    const float m_p = sh.m_p[node], m_q = kDraft ? sh.m_q[node] : 0.f;
+    const double inv_s_p = sh.inv_s_p[node], inv_s_q = kDraft ? sh.inv_s_q[node] : 0.0;
+    const int n = sh.n_steps;
+    for (int g = 0; g < quads; ++g) {
+        const int v = v0 + 4 * g;
+        if (v >= V) break;
+        float zp[4], zq[4];
+        load_quad(prow, vec_ok, v, V, zp);
+        if (kDraft) load_quad(qrow, vec_ok, v, V, zq);
+        double p[4], q[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            p[e] = unnorm_prob(zp[e], m_p, it) * inv_s_p;
+            q[e] = kDraft ? unnorm_prob(zq[e], m_q, it) * inv_s_q : 0.0;
+        }
+        for (int i = 0; i < n; ++i) {              // one LDS read per rejection, four independent chains
+            const ChainStep st = sh.steps[i];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) law_step<kRule>(v + e, st, p[e], q[e]);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc += p[e];
+            if (p[e] > 0.0) lst = v + e;
+            if (kFind && fnd < 0 && acc > u) fnd = v + e;
+        }
+    }
+    *mass = acc;
+    *last = lst;
+    if (kFind) *found = fnd;
 }
 
 template <int kRule>
-__global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptArgs a) {
-    const int b = blockIdx.x;
+__global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a) {
+    const int sl = blockIdx.x;
+    const int b = blockIdx.y;
     const int T = a.T, V = a.V;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     constexpr bool kGreedy = (kRule == TV_RULE_GREEDY);
@@ -283,7 +511,7 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptArgs a)
     __shared__ WalkShared sh;
     const float it = kGreedy ? 0.f : kLog2e / a.temperature;
 
-    for (int i = tid; i < T; i += blockDim.x) {
+    for (int i = tid; i < T; i += kDrawThreads) {
         sh.parent[i] = a.parent[(int64_t)b * T + i];
         sh.token[i] = a.token[(int64_t)b * T + i];
         if (!kGreedy) {
@@ -295,53 +523,80 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptArgs a)
     int bad = validate_tree(sh.parent, nullptr, T, &sh.flag);
     {
         int tok_bad = 0;
-        for (int i = tid; i < T; i += blockDim.x)
+        for (int i = tid; i < T; i += kDrawThreads)
             if (sh.token[i] < 0 || sh.token[i] >= V) tok_bad = 1;
         if (tok_bad) atomicOr(&sh.flag, TV_STATUS_BAD_TOKEN);
         __syncthreads();
         bad = sh.flag;
     }
+    if (kDraft && !bad && *a.chain_fail) bad = TV_STATUS_INTERNAL;
     int32_t* path = a.path + (int64_t)b * T;
-    if (bad) {
-        for (int i = tid; i < T; i += blockDim.x) path[i] = -1;
-        if (tid == 0) {
-            a.status[b] = bad;
-            a.n_accepted[b] = -1;
-            a.final_token[b] = -1;
-            a.final_kind[b] = -1;
-            a.last_node[b] = -1;
-            if (a.selected_con) a.selected_con[b] = -1;
+    if (bad) {                     // every workgroup of the sequence sees the same verdict; one reports it
+        if (sl == 0) {
+            for (int i = tid; i < T; i += kDrawThreads) path[i] = -1;
+            if (tid == 0) {
+                a.status[b] = bad;
+                a.n_accepted[b] = -1;
+                a.final_token[b] = -1;
+                a.final_kind[b] = -1;
+                a.last_node[b] = -1;
+                if (a.selected_con) a.selected_con[b] = -1;
+            }
         }
         return;
     }
 
     // per-row statistics and each node's token logit in its parent's row
-    for (int i = tid; i < T; i += blockDim.x) {
-        const Red sp = merged_row_stat(a, b, 0, i, it);
-        sh.m_p[i] = sp.m;
-        sh.argmax[i] = sp.am;
-        sh.inv_s_p[i] = kGreedy ? 0.0 : 1.0 / sp.s;
-        if (kDraft) {
-            const Red sq = merged_row_stat(a, b, 1, i, it);
-            sh.m_q[i] = sq.m;
-            sh.inv_s_q[i] = 1.0 / sq.s;
+    {
+        const int n_rows = T * (kDraft ? 2 : 1);
+        int g = 1;                                   // lanes that share one row's ranges
+        while (2 * g * n_rows <= kDrawThreads && g < kWave) g *= 2;
+        const int per_pass = kDrawThreads / g;
+        for (int r0 = 0; r0 < n_rows; r0 += per_pass) {
+            const int r = r0 + tid / g;
+            const bool active = r < n_rows;
+            const int mat = (active && r >= T) ? 1 : 0, i = active ? r - mat * T : 0;
+            const Red st = group_row_stat(a, b, mat, i, active, tid % g, g, it, !kGreedy);
+            if (active && tid % g == 0) {
+                if (mat == 0) {
+                    sh.m_p[i] = st.m;
+                    sh.argmax[i] = st.am;
+                    sh.inv_s_p[i] = kGreedy ? 0.0 : 1.0 / st.s;
+                } else {
+                    sh.m_q[i] = st.m;
+                    sh.inv_s_q[i] = 1.0 / st.s;
+                }
+            }
         }
-        if (i > 0 && !kGreedy) {
-            const int64_t r = ((int64_t)b * T + sh.parent[i]) * a.row_stride + sh.token[i];
-            sh.z_tok_p[i] = a.target[r];
-        }
+        if (!kGreedy)
+            for (int i = 1 + tid; i < T; i += kDrawThreads) {
+                const int64_t r = ((int64_t)b * T + sh.parent[i]) * a.row_stride + sh.token[i];
+                sh.z_tok_p[i] = a.target[r];
+                if (kDraft) {                          // what the chain kernel left for this node
+                    sh.z_tok_q[i] = a.draft[r];
+                    sh.abit[i] = a.accept_bit[(int64_t)b * T + i];
+                    sh.chain_z[i] = a.chain_z[(int64_t)b * T + i];
+                }
+            }
     }
     __syncthreads();
 
-    // the walk: one thread, LDS only
-    if (tid == 0) {
+    // the walk: wave 0, LDS only.  Every lane follows the same path (the tests are wave-uniform); the
+    // lanes only share the search for a node's children, which a ballot over the parent array gives in
+    // index order (a child's index exceeds its parent's).
+    if (wave == 0) {
+        const int par_lo = (lane < T) ? sh.parent[lane] : -2;
+        const int par_hi = (lane + kWave < T) ? sh.parent[lane + kWave] : -2;
         int cur = 0, len = 0, nrej = 0;
-        path[0] = 0;
+        if (lane == 0) sh.path[0] = 0;
         for (;;) {
             nrej = 0;
             int next = -1;
-            for (int c = cur + 1; c < T; ++c) {
-                if (sh.parent[c] != cur) continue;
+            unsigned long long kids_lo = __ballot(par_lo == cur), kids_hi = __ballot(par_hi == cur);
+            while (kids_lo | kids_hi) {
+                int c;
+                if (kids_lo) { c = __ffsll((long long)kids_lo) - 1; kids_lo &= kids_lo - 1; }
+                else { c = kWave + __ffsll((long long)kids_hi) - 1; kids_hi &= kids_hi - 1; }
                 const int x = sh.token[c];
                 bool acc;
                 if (kGreedy) {
@@ -356,15 +611,14 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptArgs a)
                         sh.steps[nrej] = ChainStep{x, 0.0, 0.0, (ps > 0.0) ? 1.0 / ps : 0.0};
                     }
                 } else {
-                    acc = (a.accept_bit[(int64_t)b * T + c] != 0);
+                    acc = (sh.abit[c] != 0);
                     if (!acc) {
                         // rebuild the chain step exactly as the chain kernel formed it
                         double p, q;
-                        const int64_t r = ((int64_t)b * T + cur) * a.row_stride + x;
                         law_after<kRule>(x, unnorm_prob(sh.z_tok_p[c], sh.m_p[cur], it) * sh.inv_s_p[cur],
-                                         unnorm_prob(a.draft[r], sh.m_q[cur], it) * sh.inv_s_q[cur],
+                                         unnorm_prob(sh.z_tok_q[c], sh.m_q[cur], it) * sh.inv_s_q[cur],
                                          sh.steps, nrej, &p, &q);
-                        const double z = a.chain_z[(int64_t)b * T + c];
+                        const double z = sh.chain_z[c];
                         const double qs = 1.0 - q;
                         sh.steps[nrej] = ChainStep{x, (z > 0.0) ? 1.0 / z : 0.0,
                                                    (kRule == TV_RULE_DRAFT_WOR && qs > 0.0) ? 1.0 / qs : 0.0, 1.0};
@@ -375,107 +629,131 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptArgs a)
             }
             if (next < 0) break;
             cur = next;
-            path[++len] = cur;
+            sh.path[++len] = cur;
         }
-        for (int i = len + 1; i < T; ++i) path[i] = -1;
-        sh.cur = cur;
+        for (int i = len + 1 + lane; i < T; i += kWave) sh.path[i] = -1;
+        sh.cur = cur;                    // (every lane stores the same values)
         sh.len = len;
         sh.n_steps = nrej;
         sh.rejected_any = (nrej > 0);
         sh.tok_out = -1;
+        sh.slice_last = -1;
+        sh.seg_last = -1;
+        sh.hit = kDrawThreads;
+        sh.is_last = 1;
     }
     __syncthreads();
     const int cur = sh.cur;
 
     if (kGreedy) {
-        if (tid == 0) sh.tok_out = sh.argmax[cur];
+        if (tid == 0) sh.tok_out = sh.argmax[cur];       // launched with one workgroup per sequence
     } else {
         // ---- inverse CDF at the stop node: first v whose running sum of the law exceeds u --------
         const float* prow = a.target + ((int64_t)b * T + cur) * a.row_stride;
-        const float* qrow = kDraft ? a.draft + ((int64_t)b * T + cur) * a.row_stride : nullptr;
+        const float* qrow = kDraft ? a.draft + ((int64_t)b * T + cur) * a.row_stride : prow;
+        const bool vec_ok = aligned16(prow) && aligned16(qrow);
         const double u = (double)sh.unif[T + cur];
-        // level 1: each wave owns a contiguous range (a multiple of 256 entries)
-        const int per_wave = ((V + kWalkWaves - 1) / kWalkWaves + 255) / 256 * 256;
-        {
-            const int lo = wave * per_wave, hi = min(V, lo + per_wave);
-            double acc = 0.0;
-            int last = -1;
-#pragma unroll 4
-            for (int v = lo + lane; v < hi; v += kWave) {
-                const double pv = final_law<kRule>(a, sh, prow, qrow, cur, v, it);
-                acc += pv;
-                if (pv > 0.0) last = v;
-            }
-            acc = wave_sum(acc);
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) last = max(last, __shfl_xor(last, o, kWave));
-            if (lane == 0) { sh.wave_tot[wave] = acc; sh.last_pos[wave] = last; }
+        const int quads = a.slice_len / (4 * kDrawThreads);     // quads of entries per lane, contiguous
+        double* ssum = a.slice_sum + (int64_t)b * kMaxSlices;
+        int32_t* slast = a.slice_last + (int64_t)b * kMaxSlices;
+
+        // (a) mass of the law inside this workgroup's slice
+        double mass;
+        int last;
+        segment_scan<kRule, false>(sh, prow, qrow, vec_ok, cur, sl * a.slice_len + tid * 4 * quads, quads, V, it, u,
+                                   &mass, &last, nullptr);
+        if (last >= 0) atomicMax(&sh.slice_last, last);
+        const double tot = block_sum<kDrawWaves>(mass, sh.red);
+        if (tid == 0) {
+            agent_store(ssum + sl, tot);
+            __hip_atomic_store(slast + sl, sh.slice_last, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            stores_done();                                      // publish the slice, then count it
+            const unsigned prev = atomicAdd(a.arrivals + b, 1u);
+            sh.is_last = (prev == (unsigned)a.n_slices - 1u);
         }
         __syncthreads();
-        int w_star = -1;
-        double base = 0.0;
-        for (int w = 0; w < kWalkWaves; ++w) {
-            if (base + sh.wave_tot[w] > u) { w_star = w; break; }
-            base += sh.wave_tot[w];
-        }
-        if (w_star < 0) {
-            // rounding left the total at or below u: the last entry that carries mass
-            if (tid == 0) {
-                int last = -1;
-                for (int w = 0; w < kWalkWaves; ++w) last = max(last, sh.last_pos[w]);
-                sh.tok_out = last;
-            }
-        } else {
-            // level 2: the chosen range is cut into at most 2*kWalkWaves chunks, two per wave
-            const int lo = w_star * per_wave, hi = min(V, lo + per_wave);
-            const int chunk_len = ((per_wave + 2 * kWalkWaves - 1) / (2 * kWalkWaves) + kWave - 1) / kWave * kWave;
-            const int n_chunks = (hi - lo + chunk_len - 1) / chunk_len;      // <= 2*kWalkWaves
-            for (int ch = wave; ch < n_chunks; ch += kWalkWaves) {
-                double acc = 0.0;
-                const int c_lo = lo + ch * chunk_len, c_hi = min(hi, c_lo + chunk_len);
-                for (int v = c_lo + lane; v < c_hi; v += kWave) acc += final_law<kRule>(a, sh, prow, qrow, cur, v, it);
-                acc = wave_sum(acc);
-                if (lane == 0) sh.chunk_tot[ch] = acc;
-            }
-            __syncthreads();
-            int c_star = -1;
-            for (int ch = 0; ch < n_chunks; ++ch) {
-                if (base + sh.chunk_tot[ch] > u) { c_star = ch; break; }
-                base += sh.chunk_tot[ch];
-            }
-            // level 3: one wave scans the chosen chunk in vocabulary order
-            if (wave == 0) {
-                // (if rounding hid the crossing from the chunk sums, the whole range is scanned)
-                const int s_lo = (c_star >= 0) ? lo + c_star * chunk_len : lo;
-                const int s_hi = (c_star >= 0) ? min(hi, s_lo + chunk_len) : hi;
-                double run = base;
-                int found = -1;
-                for (int v0 = s_lo; v0 < s_hi && found < 0; v0 += kWave) {
-                    const int v = v0 + lane;
-                    const double pv = (v < s_hi) ? final_law<kRule>(a, sh, prow, qrow, cur, v, it) : 0.0;
-                    double inc = pv;           // inclusive scan over the wave, in vocabulary order
+        if (!sh.is_last) return;
+
+        // (b) the slice in which the running sum crosses u: wave 0, consecutive slices per lane
+        if (wave == 0) {
+            constexpr int kPer = kMaxSlices / kWave;
+            double sm[kPer], mine = 0.0;
+            int lst = -1;
 #pragma unroll
-                    for (int o = 1; o < kWave; o <<= 1) {
-                        const double t = __shfl_up(inc, o, kWave);
-                        if (lane >= o) inc += t;
-                    }
-                    const unsigned long long hit = __ballot((run + inc > u) && v < s_hi);
-                    if (hit) found = v0 + __ffsll((long long)hit) - 1;
-                    run += __shfl(inc, kWave - 1, kWave);
+            for (int k = 0; k < kPer; ++k) {
+                const int s = lane * kPer + k;
+                sm[k] = 0.0;
+                if (s < a.n_slices) {
+                    sm[k] = agent_load(ssum + s);
+                    lst = max(lst, __hip_atomic_load(slast + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
                 }
-                if (lane == 0) {
-                    if (found < 0) {
-                        // the chunk sums said the crossing is here, the in-order sums round just below:
-                        // take the last entry of the scanned span that carries mass
-                        for (int v = s_hi - 1; v >= s_lo && found < 0; --v)
-                            if (final_law<kRule>(a, sh, prow, qrow, cur, v, it) > 0.0) found = v;
-                    }
-                    sh.tok_out = found;
-                }
+                mine += sm[k];
+            }
+            double inc = mine;
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const double t = __shfl_up(inc, o, kWave);
+                if (lane >= o) inc += t;
+            }
+            double run = inc - mine, base_c = 0.0;
+            int cand = -1;
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) {
+                if (cand < 0 && lane * kPer + k < a.n_slices && run + sm[k] > u) { cand = lane * kPer + k; base_c = run; }
+                run += sm[k];
+            }
+            const unsigned long long hit = __ballot(cand >= 0);
+            int s_star = -1;
+            double base = 0.0;
+            if (hit) {
+                const int first = __ffsll((long long)hit) - 1;
+                s_star = __shfl(cand, first, kWave);
+                base = __shfl(base_c, first, kWave);
+            } else {
+                // rounding left the total at or below u: the last entry that carries mass
+#pragma unroll
+                for (int o = 32; o > 0; o >>= 1) lst = max(lst, __shfl_xor(lst, o, kWave));
+            }
+            if (lane == 0) {
+                if (s_star < 0) sh.tok_out = lst;
+                sh.s_star = s_star;
+                sh.base = base;
+            }
+        }
+        __syncthreads();
+        const int s_star = sh.s_star;
+        if (s_star >= 0) {
+            // (c) rescan that slice: per-lane masses, a prefix sum over the lanes in vocabulary order,
+            //     then the lane that holds the crossing walks its own entries one by one
+            const int v0 = s_star * a.slice_len + tid * 4 * quads;
+            segment_scan<kRule, false>(sh, prow, qrow, vec_ok, cur, v0, quads, V, it, u, &mass, &last, nullptr);
+            if (last >= 0) atomicMax(&sh.seg_last, last);
+            double inc = mass;
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const double t = __shfl_up(inc, o, kWave);
+                if (lane >= o) inc += t;
+            }
+            if (lane == kWave - 1) sh.wave_tot[wave] = inc;
+            __syncthreads();
+            double before = sh.base;
+            for (int w = 0; w < wave; ++w) before += sh.wave_tot[w];
+            const double excl = before + (inc - mass);
+            if (before + inc > u) atomicMin(&sh.hit, tid);
+            __syncthreads();
+            if (sh.hit == kDrawThreads) {
+                // the slice sums put the crossing here, the in-order sums round just below it
+                if (tid == 0) sh.tok_out = sh.seg_last;
+            } else if (tid == sh.hit) {
+                double run = excl;
+                int found = -1, seg_last = -1;
+                segment_scan<kRule, true>(sh, prow, qrow, vec_ok, cur, v0, quads, V, it, u, &run, &seg_last, &found);
+                sh.tok_out = (found >= 0) ? found : seg_last;
             }
         }
     }
     __syncthreads();
+    for (int i = tid; i < T; i += kDrawThreads) path[i] = sh.path[i];
     if (tid == 0) {
         a.status[b] = TV_STATUS_OK;
         a.n_accepted[b] = sh.len;
@@ -497,9 +775,9 @@ __global__ __launch_bounds__(kWalkThreads) void accept_walk_kernel(AcceptArgs a)
 int plan_accept(const tv_accept_desc& d, AcceptPlan* plan) {
     AcceptPlan p{};
     p.n_mat = (d.rule == TV_RULE_DRAFT_WOR || d.rule == TV_RULE_DRAFT_WR) ? 2 : 1;
-    // enough workgroups to fill 256 CUs a few times over, ranges no shorter than 4096 entries
+    // about a thousand workgroups (four per CU), ranges no shorter than 4096 entries
     const int rows = d.B * d.T * p.n_mat;
-    int splits = (2048 + rows - 1) / rows;
+    int splits = (1024 + rows - 1) / rows;
     const int max_splits = (d.V + 4095) / 4096;
     if (splits > max_splits) splits = max_splits;
     if (splits < 1) splits = 1;
@@ -508,26 +786,69 @@ int plan_accept(const tv_accept_desc& d, AcceptPlan* plan) {
     len = (len + 3) / 4 * 4;
     p.splits = (d.V + len - 1) / len;
     p.split_len = len;
+    // the final draw: at most kMaxSlices slices, each a whole number of quads per lane
+    constexpr int kGrain = 4 * kDrawThreads;
+    int ns = (d.V + kGrain - 1) / kGrain;
+    if (ns > kMaxSlices) ns = kMaxSlices;
+    int slen = (d.V + ns - 1) / ns;
+    slen = (slen + kGrain - 1) / kGrain * kGrain;
+    p.slice_len = slen;
+    p.n_slices = (d.rule == TV_RULE_GREEDY) ? 1 : (d.V + slen - 1) / slen;
     auto up = [](size_t x) { return (x + 255) / 256 * 256; };
     p.stats_bytes = up((size_t)rows * p.splits * sizeof(RowStat));
     p.chain_bytes = up((size_t)d.B * d.T * sizeof(double));
     p.bits_bytes = up((size_t)d.B * d.T * sizeof(int32_t));
-    p.total_bytes = p.stats_bytes + p.chain_bytes + p.bits_bytes;
+    p.slice_sum_bytes = up((size_t)d.B * kMaxSlices * sizeof(double));
+    p.slice_last_bytes = up((size_t)d.B * kMaxSlices * sizeof(int32_t));
+    p.arrivals_bytes = up((size_t)d.B * sizeof(unsigned));
+    // the sibling chains: one group of workgroups per node, one slice of kChainThreads * kChainPer entries each
+    constexpr int kChainSlice = kChainThreads * kChainPer;
+    p.chain_slices = (d.V + kChainSlice - 1) / kChainSlice;
+    p.chain_parts_bytes = (p.n_mat == 2) ? up((size_t)d.B * d.T * 2 * p.chain_slices * sizeof(double)) : 0;
+    p.chain_ctl_bytes = (p.n_mat == 2) ? up(((size_t)d.B * d.T + 2) * sizeof(unsigned)) : 0;
+    p.total_bytes = p.stats_bytes + p.chain_bytes + p.bits_bytes + p.slice_sum_bytes + p.slice_last_bytes +
+                    p.arrivals_bytes + p.chain_parts_bytes + p.chain_ctl_bytes;
     *plan = p;
     return TV_OK;
+}
+
+// Workgroups of the chain kernel that are resident together on the current device (0 if unknown).
+static int chain_resident_workgroups(int rule) {
+    static int cache[2][64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    int& c = cache[rule == TV_RULE_DRAFT_WOR ? 0 : 1][dev];
+    if (c == 0) {
+        int per_cu = 0, cus = 0;
+        const hipError_t e1 = (rule == TV_RULE_DRAFT_WOR)
+            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_chain_kernel<TV_RULE_DRAFT_WOR>, kChainThreads, 0)
+            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_chain_kernel<TV_RULE_DRAFT_WR>, kChainThreads, 0);
+        const hipError_t e2 = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e1 == hipSuccess && e2 == hipSuccess && per_cu > 0 && cus > 0) c = per_cu * cus;
+    }
+    return c;
 }
 
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t s) {
     const dim3 gs(a.splits, a.T * a.n_mat, a.B);
     if (a.rule == TV_RULE_GREEDY) accept_stats_kernel<true><<<gs, kStatThreads, 0, s>>>(a);
     else accept_stats_kernel<false><<<gs, kStatThreads, 0, s>>>(a);
-    if (a.rule == TV_RULE_DRAFT_WOR) accept_chain_kernel<TV_RULE_DRAFT_WOR><<<dim3(a.T, a.B), kWalkThreads, 0, s>>>(a);
-    else if (a.rule == TV_RULE_DRAFT_WR) accept_chain_kernel<TV_RULE_DRAFT_WR><<<dim3(a.T, a.B), kWalkThreads, 0, s>>>(a);
+    if (a.rule == TV_RULE_DRAFT_WOR || a.rule == TV_RULE_DRAFT_WR) {
+        // whole groups only, and no more workgroups than the device holds at once (they wait for each other)
+        const int cap = chain_resident_workgroups(a.rule);
+        int groups = cap / a.chain_slices;
+        if (groups < 1) return hipErrorLaunchOutOfResources;
+        if (groups > a.B * a.T) groups = a.B * a.T;
+        const unsigned gc = (unsigned)groups * (unsigned)a.chain_slices;
+        if (a.rule == TV_RULE_DRAFT_WOR) accept_chain_kernel<TV_RULE_DRAFT_WOR><<<gc, kChainThreads, 0, s>>>(a);
+        else accept_chain_kernel<TV_RULE_DRAFT_WR><<<gc, kChainThreads, 0, s>>>(a);
+    }
+    const dim3 gw(a.n_slices, a.B);
     switch (a.rule) {
-        case TV_RULE_GREEDY: accept_walk_kernel<TV_RULE_GREEDY><<<a.B, kWalkThreads, 0, s>>>(a); break;
-        case TV_RULE_DETERMINISTIC: accept_walk_kernel<TV_RULE_DETERMINISTIC><<<a.B, kWalkThreads, 0, s>>>(a); break;
-        case TV_RULE_DRAFT_WOR: accept_walk_kernel<TV_RULE_DRAFT_WOR><<<a.B, kWalkThreads, 0, s>>>(a); break;
-        default: accept_walk_kernel<TV_RULE_DRAFT_WR><<<a.B, kWalkThreads, 0, s>>>(a); break;
+        case TV_RULE_GREEDY: accept_walk_kernel<TV_RULE_GREEDY><<<gw, kDrawThreads, 0, s>>>(a); break;
+        case TV_RULE_DETERMINISTIC: accept_walk_kernel<TV_RULE_DETERMINISTIC><<<gw, kDrawThreads, 0, s>>>(a); break;
+        case TV_RULE_DRAFT_WOR: accept_walk_kernel<TV_RULE_DRAFT_WOR><<<gw, kDrawThreads, 0, s>>>(a); break;
+        default: accept_walk_kernel<TV_RULE_DRAFT_WR><<<gw, kDrawThreads, 0, s>>>(a); break;
     }
     return hipGetLastError();
 }

@@ -232,10 +232,20 @@ int tree_accept(const tv_accept_desc* desc, const float* target_logits, const fl
     a.stats = reinterpret_cast<RowStat*>(w);
     a.chain_z = reinterpret_cast<double*>(w + p.stats_bytes);
     a.accept_bit = reinterpret_cast<int32_t*>(w + p.stats_bytes + p.chain_bytes);
+    unsigned char* w2 = w + p.stats_bytes + p.chain_bytes + p.bits_bytes;
+    a.slice_sum = reinterpret_cast<double*>(w2);
+    a.slice_last = reinterpret_cast<int32_t*>(w2 + p.slice_sum_bytes);
+    a.arrivals = reinterpret_cast<unsigned*>(w2 + p.slice_sum_bytes + p.slice_last_bytes);
+    unsigned char* w3 = w2 + p.slice_sum_bytes + p.slice_last_bytes + p.arrivals_bytes;
+    a.chain_parts = reinterpret_cast<double*>(w3);
+    a.chain_arrivals = reinterpret_cast<unsigned*>(w3 + p.chain_parts_bytes);
+    a.chain_ticket = a.chain_arrivals + (size_t)desc->B * desc->T;
+    a.chain_fail = reinterpret_cast<int32_t*>(a.chain_ticket + 1);
     a.B = desc->B; a.T = desc->T; a.V = desc->V; a.C = con_anchor ? desc->C : 0; a.rule = desc->rule;
     a.temperature = desc->temperature;
     a.row_stride = desc->logits_row_stride ? desc->logits_row_stride : desc->V;
     a.splits = p.splits; a.split_len = p.split_len; a.n_mat = p.n_mat;
+    a.n_slices = p.n_slices; a.slice_len = p.slice_len; a.chain_slices = p.chain_slices;
     const hipError_t e = launch_accept(a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;
 }

@@ -64,8 +64,14 @@ struct AcceptPlan {
     int splits;           // ranges a logits row is cut into for the statistics pass
     int split_len;        // elements per range (multiple of 4)
     int n_mat;            // 1 (target only) or 2 (target and draft)
-    size_t stats_bytes, chain_bytes, bits_bytes, total_bytes;
+    int n_slices;         // workgroups per sequence that share the final draw (<= kMaxSlices)
+    int slice_len;        // vocabulary entries per slice (multiple of 4 * 256)
+    int chain_slices;     // draft rules: workgroups per node in the sibling-chain kernel
+    size_t stats_bytes, chain_bytes, bits_bytes, slice_sum_bytes, slice_last_bytes, arrivals_bytes,
+           chain_parts_bytes, chain_ctl_bytes, total_bytes;
 };
+
+constexpr int kMaxSlices = 128;      // a multiple of the wave size
 
 int plan_accept(const tv_accept_desc& d, AcceptPlan* plan);
 
@@ -86,10 +92,19 @@ struct AcceptArgs {
     RowStat* stats;       // [B][n_mat][T][splits]
     double*  chain_z;     // [B][T]: normaliser of the corrected law after rejecting child c
     int32_t* accept_bit;  // [B][T]
+    double*  slice_sum;   // [B][kMaxSlices]: mass of the final law inside one vocabulary slice
+    int32_t* slice_last;  // [B][kMaxSlices]: last entry of the slice that carries mass, or -1
+    unsigned* arrivals;   // [B]: workgroups of the draw kernel that have published their slice
+    double*  chain_parts;    // [B][T][2][chain_slices]: shares of a chain normaliser, two buffers per node
+    unsigned* chain_arrivals;// [B][T]: shares published so far by a node's group (never reset within a call)
+    unsigned* chain_ticket;  // [1]: next (group, slice) to hand out
+    int32_t* chain_fail;     // [1]: set when a bounded wait ran out
     int B, T, V, C, rule;
     float temperature;
     int64_t row_stride;
     int splits, split_len, n_mat;
+    int n_slices, slice_len;
+    int chain_slices;
 };
 
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t s);
