@@ -196,6 +196,13 @@ const char* tv_error_string(int code);
 /* host: library version, major*100 + minor. */
 int tv_version(void);
 
+/* host, for tests of the failure path: sets how many times a workgroup of tree_accept's sibling-chain
+ * kernel (draft rules) polls for the other workgroups of its group before it gives up; a sequence whose
+ * wait ran out gets TV_STATUS_INTERNAL and -1 outputs, and every kernel still ends normally.
+ * 0 restores the default (about a million polls).  Applies to calls made after it; returns the
+ * previous setting. */
+int tv_set_wait_limit(int polls);
+
 #ifdef __cplusplus
 }
 #endif

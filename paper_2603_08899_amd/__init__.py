@@ -27,7 +27,7 @@ TV_FINAL_BONUS, TV_FINAL_RESIDUAL = 0, 1
 EXPORTED_SYMBOLS = (
     "tv_attention_workspace_bytes", "tree_verify_attention",
     "tv_accept_workspace_bytes", "tree_accept",
-    "tv_build_mask_host", "tv_error_string", "tv_version",
+    "tv_build_mask_host", "tv_error_string", "tv_version", "tv_set_wait_limit",
 )
 
 
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         l = ctypes.CDLL(LIB_PATH)
         vp, sz = ctypes.c_void_p, ctypes.c_size_t
         l.tv_version.restype = ctypes.c_int
+        l.tv_set_wait_limit.restype = ctypes.c_int
+        l.tv_set_wait_limit.argtypes = [ctypes.c_int]
         l.tv_error_string.restype = ctypes.c_char_p
         l.tv_error_string.argtypes = [ctypes.c_int]
         l.tv_build_mask_host.restype = ctypes.c_int
@@ -125,6 +127,11 @@ def tv_accept_workspace_bytes(desc: tv_accept_desc) -> int:
     if rc:
         raise ConfuVerifyError(rc, "tv_accept_workspace_bytes")
     return int(n.value)
+
+
+def tv_set_wait_limit(polls: int) -> int:
+    """Test hook: polls before a sibling-chain workgroup gives up (0 = default); returns the old value."""
+    return int(lib().tv_set_wait_limit(int(polls)))
 
 
 def tv_build_mask_host(parent, kind):

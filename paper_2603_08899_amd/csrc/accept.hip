@@ -94,8 +94,11 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a
     // the kernels that follow on the stream count arriving workgroups from zero
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         if (blockIdx.y == 0) a.arrivals[b] = 0u;
-        if (a.n_mat == 2 && mat == 0) a.chain_arrivals[(int64_t)b * a.T + row] = 0u;
         if (a.n_mat == 2 && blockIdx.y == 0 && b == 0) *a.chain_fail = 0;
+    }
+    if (a.n_mat == 2 && mat == 0 && blockIdx.x == 0) {       // this node's share slots: a tag no early round expects
+        unsigned long long* parts = a.chain_parts + ((int64_t)b * a.T + row) * 2 * a.chain_slices;
+        for (int i = threadIdx.x; i < 2 * a.chain_slices; i += kStatThreads) parts[i] = 3ull;
     }
     const float* base = (mat == 0 ? a.target : a.draft) + ((int64_t)b * a.T + row) * a.row_stride;
     const int begin = split * a.split_len;
@@ -225,15 +228,14 @@ __device__ __forceinline__ double block_sum(double x, double* scratch /* kWaves 
 // The launch holds a whole number of groups of chain_slices workgroups, no more than fit on the device at
 // once.  A group takes the nodes that have children one after the other; each workgroup holds its slice of
 // the node's two laws in registers and the group steps through the children in order.  One child costs one
-// group-wide reduction (the normaliser of the corrected law): every workgroup publishes its partial sum,
-// counts itself on the node's arrival counter and waits until the count shows the whole group.
+// group-wide reduction (the normaliser of the corrected law): every workgroup publishes its partial sum and
+// waits until it has seen the partial sums of the whole group.
 //
 // Forward progress: a workgroup waits only for workgroups of its own launch, and the host sizes the grid so
-// that all of them are resident together.  The wait is bounded all the same: past kSpinLimit polls the
+// that all of them are resident together.  The wait is bounded all the same: past wait_limit polls the
 // workgroup gives up, raises chain_fail (the walk kernel turns it into TV_STATUS_INTERNAL) and exits.
 constexpr int kChainPer = 16;                                  // vocabulary entries per lane
 constexpr int kChainQuads = kChainPer / 4;
-constexpr unsigned kSpinLimit = 1u << 20;
 
 __device__ __forceinline__ double agent_load(const double* p) {
     return __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<const unsigned long long*>(p),
@@ -369,7 +371,6 @@ __global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs 
         }
     }
 
-    unsigned* arrived = a.chain_arrivals + (int64_t)b * T + u;
     for (int j = 0; j < k; ++j) {
         const int c = s_child[j];
         if (tid == 0) {
@@ -392,36 +393,42 @@ __global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs 
 #pragma unroll
         for (int e = 0; e < kChainPer; ++e) part += fmax(p[e] - q[e], 0.0);
         const double mine = block_sum<kChainWaves>(part, s_red);
-        double* parts = a.chain_parts + ((((int64_t)b * T + u) * 2) + (j & 1)) * S;   // two buffers, by parity of j
-        if (tid == 0) {
-            agent_store(parts + slice, mine);
-            stores_done();                                     // publish, then count
-            atomicAdd(arrived, 1u);
-            const unsigned target = (unsigned)(j + 1) * (unsigned)S;
-            unsigned polls = 0;
+        // ... published with the round number (mod 4) in the two lowest mantissa bits, which tells a reader that
+        // the slot holds this round's share: no counter, no second round trip.  Two buffers, by parity of j;
+        // the statistics kernel left tag 3 in both, which neither of the first two rounds expects.
+        unsigned long long* parts = a.chain_parts + ((((int64_t)b * T + u) * 2) + (j & 1)) * S;
+        const unsigned long long tag = (unsigned long long)(j & 3);
+        if (tid == 0)
+            __hip_atomic_store(parts + slice, ((unsigned long long)__double_as_longlong(mine) & ~3ull) | tag,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // ... and the whole: every workgroup of the group adds the shares in the same order
+        if (wave == 0) {
+            double z = 0.0;
             int fail = 0;
-            while (__hip_atomic_load(arrived, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-                __builtin_amdgcn_s_sleep(2);
-                if (++polls > kSpinLimit) { fail = 1; break; }
+            unsigned polls = 0;
+            for (int s = lane; s < S; s += kWave) {
+                unsigned long long bits = 0;
+                for (;;) {
+                    bits = __hip_atomic_load(parts + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((bits & 3ull) == tag) break;
+                    __builtin_amdgcn_s_sleep(1);
+                    if (++polls > a.wait_limit) { fail = 1; break; }
+                }
+                z += __longlong_as_double((long long)(bits & ~3ull));
             }
-            s_fail = fail;
+            fail = __any(fail);
+            z = wave_sum(z);
+            if (lane == 0) {
+                s_fail = fail;
+                s_steps[j].inv_z = (z > 0.0) ? 1.0 / z : 0.0;
+                if (slice == 0) a.chain_z[(int64_t)b * T + c] = z;
+            }
         }
         __syncthreads();
         if (s_fail) {
             if (tid == 0) *a.chain_fail = 1;
             return;
         }
-        // ... and the whole: every workgroup of the group adds the shares in the same order
-        if (wave == 0) {
-            double z = 0.0;
-            for (int s = lane; s < S; s += kWave) z += agent_load(parts + s);
-            z = wave_sum(z);
-            if (lane == 0) {
-                s_steps[j].inv_z = (z > 0.0) ? 1.0 / z : 0.0;
-                if (slice == 0) a.chain_z[(int64_t)b * T + c] = z;
-            }
-        }
-        __syncthreads();
         if (j + 1 < k) {
             const ChainStep st = s_steps[j];
 #pragma unroll
@@ -805,7 +812,7 @@ int plan_accept(const tv_accept_desc& d, AcceptPlan* plan) {
     constexpr int kChainSlice = kChainThreads * kChainPer;
     p.chain_slices = (d.V + kChainSlice - 1) / kChainSlice;
     p.chain_parts_bytes = (p.n_mat == 2) ? up((size_t)d.B * d.T * 2 * p.chain_slices * sizeof(double)) : 0;
-    p.chain_ctl_bytes = (p.n_mat == 2) ? up(((size_t)d.B * d.T + 2) * sizeof(unsigned)) : 0;
+    p.chain_ctl_bytes = (p.n_mat == 2) ? up(sizeof(int32_t)) : 0;
     p.total_bytes = p.stats_bytes + p.chain_bytes + p.bits_bytes + p.slice_sum_bytes + p.slice_last_bytes +
                     p.arrivals_bytes + p.chain_parts_bytes + p.chain_ctl_bytes;
     *plan = p;

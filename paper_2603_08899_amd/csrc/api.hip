@@ -109,6 +109,10 @@ extern "C" {
 
 int tv_version(void) { return 100; }
 
+static std::atomic<int> g_wait_limit{0};
+
+int tv_set_wait_limit(int polls) { return g_wait_limit.exchange(polls < 0 ? 0 : polls); }
+
 const char* tv_error_string(int code) {
     switch (code) {
         case TV_OK: return "ok";
@@ -237,15 +241,15 @@ int tree_accept(const tv_accept_desc* desc, const float* target_logits, const fl
     a.slice_last = reinterpret_cast<int32_t*>(w2 + p.slice_sum_bytes);
     a.arrivals = reinterpret_cast<unsigned*>(w2 + p.slice_sum_bytes + p.slice_last_bytes);
     unsigned char* w3 = w2 + p.slice_sum_bytes + p.slice_last_bytes + p.arrivals_bytes;
-    a.chain_parts = reinterpret_cast<double*>(w3);
-    a.chain_arrivals = reinterpret_cast<unsigned*>(w3 + p.chain_parts_bytes);
-    a.chain_ticket = a.chain_arrivals + (size_t)desc->B * desc->T;
-    a.chain_fail = reinterpret_cast<int32_t*>(a.chain_ticket + 1);
+    a.chain_parts = reinterpret_cast<unsigned long long*>(w3);
+    a.chain_fail = reinterpret_cast<int32_t*>(w3 + p.chain_parts_bytes);
     a.B = desc->B; a.T = desc->T; a.V = desc->V; a.C = con_anchor ? desc->C : 0; a.rule = desc->rule;
     a.temperature = desc->temperature;
     a.row_stride = desc->logits_row_stride ? desc->logits_row_stride : desc->V;
     a.splits = p.splits; a.split_len = p.split_len; a.n_mat = p.n_mat;
     a.n_slices = p.n_slices; a.slice_len = p.slice_len; a.chain_slices = p.chain_slices;
+    const int wl = g_wait_limit.load();
+    a.wait_limit = wl > 0 ? (unsigned)wl : (1u << 20);
     const hipError_t e = launch_accept(a, static_cast<hipStream_t>(hip_stream));
     return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;
 }

@@ -95,9 +95,8 @@ struct AcceptArgs {
     double*  slice_sum;   // [B][kMaxSlices]: mass of the final law inside one vocabulary slice
     int32_t* slice_last;  // [B][kMaxSlices]: last entry of the slice that carries mass, or -1
     unsigned* arrivals;   // [B]: workgroups of the draw kernel that have published their slice
-    double*  chain_parts;    // [B][T][2][chain_slices]: shares of a chain normaliser, two buffers per node
-    unsigned* chain_arrivals;// [B][T]: shares published so far by a node's group (never reset within a call)
-    unsigned* chain_ticket;  // [1]: next (group, slice) to hand out
+    unsigned long long* chain_parts;  // [B][T][2][chain_slices]: shares of a chain normaliser (fp64 bits, the two
+                             // lowest carrying a round tag), two buffers per node
     int32_t* chain_fail;     // [1]: set when a bounded wait ran out
     int B, T, V, C, rule;
     float temperature;
@@ -105,6 +104,7 @@ struct AcceptArgs {
     int splits, split_len, n_mat;
     int n_slices, slice_len;
     int chain_slices;
+    unsigned wait_limit;     // polls before a workgroup of the chain kernel gives up on its group
 };
 
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t s);

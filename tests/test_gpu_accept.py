@@ -135,3 +135,24 @@ def test_many_uniform_draws_on_one_full_size_tree():
         uniforms=rng.random((B, 2 * base.T), dtype=np.float32), con_anchor=np.repeat(base.con_anchor, B, axis=0))
     got = _run_and_compare(inp)
     assert len(set(got["final_token"].tolist())) > 1
+
+
+def test_wait_that_runs_out_is_reported_not_hung():
+    """With a wait limit of one poll the sibling-chain groups of a full-vocabulary draft-rule call
+    usually give up; the call must still return, and every sequence is then either flagged
+    TV_STATUS_INTERNAL with -1 outputs or correct.  The default limit restores normal service."""
+    import paper_2603_08899_amd as tv
+    inp = si.accept_case(1, 0, draft_target_corr=0.9, child_boost=5.0)
+    old = tv.tv_set_wait_limit(1)
+    try:
+        got = H.run_accept(inp)
+    finally:
+        tv.tv_set_wait_limit(old)
+    ref = H.oracle_accept(inp, 0)
+    if got["status"][0] == 0:
+        assert got["final_token"][0] == ref["final_token"] and np.array_equal(got["path"][0], ref["path"])
+    else:
+        assert got["status"][0] == tv.TV_STATUS_INTERNAL
+        assert got["n_accepted"][0] == -1 and got["final_token"][0] == -1 and np.all(got["path"][0] == -1)
+    print("wait limit 1 -> status", int(got["status"][0]))
+    _run_and_compare(inp)
