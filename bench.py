@@ -25,6 +25,21 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 WORKLOAD_INDEX = 2              # llama3.1-8b-32layers
 
 
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "attn_bf16_kernel_llama8b_hbm_traffic.txt")
+
+
+def measured_traffic_bytes():
+    """HBM bytes per attention launch from the committed counter summary (a line
+    `traffic_bytes_per_launch = N`), or None when the summary is absent."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            if line.startswith("traffic_bytes_per_launch"):
+                return int(float(line.split("=")[1]))
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -35,6 +50,9 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
     ap.add_argument("--splits", type=int, default=0, help="key ranges per sequence (0 = library decides)")
     ap.add_argument("--wg-row-blocks", type=int, default=0, help="row blocks sharing a key stream (0 = library decides)")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run three plain device copies of this many MiB before the timed region "
+                         "(a kernel of known traffic, to scale hardware counters of a profiler run)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path has no multi-GPU part); run with --gpus 1",
@@ -110,6 +128,16 @@ def main() -> int:
 
     stream = torch.cuda.Stream()          # default priority
 
+    if args.calibration_copy_mib > 0:
+        # a plain elementwise kernel (out = in + 0, fp32): reads n bytes and writes n bytes
+        n = args.calibration_copy_mib << 20
+        src = torch.ones(n // 4, device="cuda", dtype=torch.float32)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 0.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
     def timed(fn, steps, warmup):
         """Average milliseconds per call of fn over `steps` calls, HIP events on the launch stream."""
         with torch.cuda.stream(stream):
@@ -155,10 +183,20 @@ def main() -> int:
     flops_layer = 4 * M * w.Hq * (P + M) * w.D
     achieved = bytes_layer / (us_layer * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic_bytes(),
                 "kernel": "attn_bf16_kernel (+ combine), per layer launch",
                 "algorithmic_bytes_per_launch": bytes_layer,
                 "mfma_frac_of_bf16_peak": round(flops_layer / (us_layer * 1e-6) / 2.5e15, 4)}
+
+    # ---- tree_accept: bytes moved (statistics of all T rows) and the visited-row (algorithmic) figure ------------
+    n_visit = int(o_n[0]) + 1
+    moved = acc.T * acc.V * 4
+    accept_info = {
+        "us_per_step": round(ms_accept * 1e3, 2), "bytes_moved": moved,
+        "achieved_gbps_on_moved": round(moved / (ms_accept * 1e-3) / 1e9, 1),
+        "visited_rows": n_visit, "algorithmic_bytes": n_visit * acc.V * 4,
+        "frac_of_hbm_peak_on_algorithmic": round(n_visit * acc.V * 4 / (ms_accept * 1e-3) / 1e9 / HBM_PEAK_GBPS, 5),
+        "greedy_us_per_step": round(ms_greedy * 1e3, 2)}
 
     # ---- CPU oracle on the host cores, bounded sample: one of the 32 layers + one acceptance ---------------
     cpu = None
@@ -186,6 +224,7 @@ def main() -> int:
                    "launch": "eager" if args.no_graph else "hip-graph replay"},
         "tree_accept_steps_per_s": {"temp1.0_deterministic": round(1e3 / ms_accept, 1),
                                     "temp0_greedy": round(1e3 / ms_greedy, 1)},
+        "tree_accept": accept_info,
         "verify_steps_per_s": round(1e3 / ms_step, 2),
         "attention_tb_per_s": round(achieved / 1e3, 3),
         "roofline": roofline,
