@@ -54,6 +54,7 @@ struct Bf16Smem {
     float ml[kWgRows][2];                  // (max, sum) of every wave's rows
     int parent[kMaxRows];
     unsigned char kind[kMaxRows];
+    unsigned long long bits[kMaxRows][2];  // ancestor mask of every row (only filled where masked tiles occur)
     int flag;
 };
 
@@ -80,8 +81,14 @@ __device__ __forceinline__ void wait_vmcnt() {
 // the tiles that were just requested.  Completion is tracked by hand with wait_vmcnt (these loads
 // retire in order on the vector-memory counter).
 __device__ __forceinline__ void dma16(unsigned lds_addr, unsigned long long sbase, unsigned voff) {
+    // (the scalar operands are pinned to SGPRs: an "s" constraint alone does not stop the compiler from
+    //  handing over a vector register when it has lost track of a value's uniformity)
+    const unsigned m = __builtin_amdgcn_readfirstlane(lds_addr);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)sbase);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(sbase >> 32));
+    const unsigned long long sb = ((unsigned long long)hi << 32) | lo;
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory", "m0");
+                 :: "s"(m), "v"(voff), "s"(sb) : "memory", "m0");
 }
 // A wave-uniform pointer as a scalar value the assembler operand above accepts (pins it to SGPRs even when
 // the compiler cannot prove uniformity).
@@ -135,7 +142,7 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
     constexpr int S = kRingBytes / (NS * kStageBytes); // stages per stream: 2, 4 or 8 (= 2*RB)
     constexpr int PER = 16 / WPS;                      // direct-to-LDS loads per tile per wave
     static_assert(S == 2 * RB && PER >= 2, "stage ring layout");
-    extern __shared__ __align__(16) unsigned char smem_raw[];
+    extern __shared__ __align__(1024) unsigned char smem_raw[];   // stage bases are multiples of 256 (see k_it)
     Bf16Smem& sm = *reinterpret_cast<Bf16Smem*>(smem_raw);
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -204,14 +211,15 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
     // block and fetches the logical segment that the swizzle stores there.  This wave issues the
     // instructions j = jj*WPS + wsub: the first PER/2 of them are K rows, the rest V rows.  The per-lane part
     // of the address is constant; the tile only moves the (scalar) base.
-    unsigned lane_off[PER];
+    // Row 4*jb + l_row of a tile: the 4-row block jb goes into the scalar base, the lane keeps l_row rows plus its
+    // swizzled segment.  The V swizzle does not depend on the block; the K swizzle depends on jb & 3, of which a
+    // wave meets NP values (jb = jj*WPS + wsub).
+    constexpr int NP = (WPS >= 4) ? 1 : 4 / WPS;
+    unsigned k_lane[NP];
 #pragma unroll
-    for (int jj = 0; jj < PER; ++jj) {
-        const int j = jj * WPS + wsub;
-        const int row = 4 * (j & 7) + l_row;
-        const int seg = (j < 8) ? (l_seg ^ (row & 15)) : (l_seg ^ (l_row << 2));
-        lane_off[jj] = (unsigned)row * tok_bytes + (unsigned)(seg * 16);
-    }
+    for (int pi = 0; pi < NP; ++pi)
+        k_lane[pi] = (unsigned)l_row * tok_bytes + (unsigned)((l_seg ^ l_row ^ (4 * ((pi * WPS + wsub) & 3))) << 4);
+    const unsigned v_lane = (unsigned)l_row * tok_bytes + (unsigned)((l_seg ^ (l_row << 2)) << 4);
     auto issue_half = [&](int t, int stage, int half) {      // half 0: K rows, half 1: V rows
         const int k0 = t * kTK;
         const unsigned dst = __builtin_amdgcn_readfirstlane(ring_addr + stage * kStageBytes + half * kTileBytes);
@@ -220,8 +228,9 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
             const unsigned long long tile_base = scalar_base(base + (size_t)k0 * tok_bytes);
 #pragma unroll
             for (int jj = 0; jj < PER / 2; ++jj) {
-                const int j = (half * (PER / 2) + jj) * WPS + wsub;
-                dma16(dst + (j & 7) * 1024, tile_base, lane_off[half * (PER / 2) + jj]);
+                const int jb = (jj * WPS + wsub) & 7;        // 4-row block of this instruction
+                dma16(dst + jb * 1024, tile_base + (unsigned long long)(4 * jb) * tok_bytes,
+                      half ? v_lane : k_lane[jj % NP]);
             }
         } else {                                             // last tile: never read past the sequence's rows
 #pragma unroll
@@ -241,13 +250,43 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
 
     // ---- tree, validation (ordinary loads: the wait the compiler puts before the LDS writes also covers
     //      everything requested above, which is needed next anyway) ---------------------------------------
-    for (int i = tid; i < M; i += kThreads) {
-        sm.parent[i] = a.parent[(int64_t)b * M + i];
-        sm.kind[i] = a.kind[(int64_t)b * M + i];
+    int my_parent = -1, my_kind = TV_KIND_NODE;          // row tid (M <= 128 < kThreads)
+    if (tid < M) {
+        my_parent = a.parent[(int64_t)b * M + tid];
+        my_kind = a.kind[(int64_t)b * M + tid];
+        sm.parent[tid] = my_parent;
+        sm.kind[tid] = (unsigned char)my_kind;
     }
+    if (tid == 0) sm.flag = 0;
     wait_vmcnt<0>();
     __syncthreads();
-    int bad = validate_tree(sm.parent, sm.kind, M, &sm.flag);
+    // Row tid checks itself; a workgroup whose key range meets masked tiles (soft-prompt slots, new rows, the
+    // tail) also walks the row's ancestors once and leaves the two mask words in LDS.  The walk only follows
+    // parents that are smaller than the row they belong to, so it ends whatever the other rows hold.
+    int bad = 0;
+    if (tid < M) {
+        if (my_parent < -1 || my_parent >= tid) bad |= TV_STATUS_BAD_PARENT;
+        if (my_kind != TV_KIND_NODE && my_kind != TV_KIND_CONTEMPLATE) bad |= TV_STATUS_BAD_KIND;
+        else if (my_parent >= 0 && my_parent < tid && my_kind == TV_KIND_NODE &&
+                 sm.kind[my_parent] == TV_KIND_CONTEMPLATE)
+            bad |= TV_STATUS_BAD_KIND;
+        const int wg_t_begin = slot0 * tiles_per_slot + min(slot0, extra);
+        const int wg_t_end = (slot0 + NS) * tiles_per_slot + min(slot0 + NS, extra);
+        if (wg_t_begin * kTK < a.soft_len || wg_t_end * kTK > P) {
+            unsigned long long w0 = 0, w1 = 0;
+            int j = tid;
+            while (j >= 0) {
+                if (j < 64) w0 |= 1ull << j; else w1 |= 1ull << (j - 64);
+                const int pj = sm.parent[j];
+                j = (pj < j) ? pj : -1;
+            }
+            sm.bits[tid][0] = w0;
+            sm.bits[tid][1] = w1;
+        }
+    }
+    if (bad) atomicOr(&sm.flag, bad);
+    __syncthreads();
+    bad = sm.flag;
     if (bad_prefix) bad |= TV_STATUS_BAD_PREFIX;
     if (blockIdx.x == 0 && tid == 0) a.status[b] = bad;
     unsigned short* out16 = static_cast<unsigned short*>(a.out);
@@ -267,32 +306,36 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
     }
 
     // per-lane LDS offsets of the MFMA operands inside a tile
-    unsigned k_off[8];       // K (A operand of S^T): row ln, logical segment 2*ks + hf
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) k_off[ks] = (unsigned)(ln * kRowBytes + (((2 * ks + hf) ^ (ln & 15)) << 4));
-    unsigned v_off[4];       // V^T (A operand of O^T): transposed 8-byte reads, 4 keys x 16 d per 16 lanes
+    // K (A operand of S^T): row ln, logical segment 2*ks + hf, stored at segment (2*ks + hf) ^ (ln & 15): the
+    // offset for step ks is k_base ^ (ks << 5).  V^T (A operand of O^T): transposed 8-byte reads, 4 keys x 16 d
+    // per 16 lanes; the offset for column block dt is v_base ^ (dt << 6).  Both XORs only touch bits 5..7, so
+    // they commute with adding a stage base that is a multiple of 256.
+    const unsigned k_base = (unsigned)(ln * kRowBytes + ((hf ^ (ln & 15)) << 4));
+    unsigned v_base;
     {
         const int g16 = lane >> 4, i16 = lane & 15;
         const int row = 4 * (g16 >> 1) + (i16 >> 2);
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-            const int seg = (4 * (dt ^ (i16 >> 2))) + (g16 & 1) * 2 + ((i16 & 3) >> 1);
-            v_off[dt] = (unsigned)(kTileBytes + row * kRowBytes + seg * 16 + (i16 & 1) * 8);
-        }
+        const int seg0 = 4 * (i16 >> 2) + (g16 & 1) * 2 + ((i16 & 3) >> 1);
+        v_base = (unsigned)(kTileBytes + row * kRowBytes + seg0 * 16 + (i16 & 1) * 8);
     }
+    typedef const bf16x8 __attribute__((address_space(3))) * lds_b128_ptr;
+    typedef bf16x4 __attribute__((address_space(3))) * lds_b64_ptr;
 
     // ---- this lane's queries (column ln of each query block): B operands of S^T, kept in registers ------
     bf16x8 qreg[NQB][8];
     int tree_row[NQB];       // tree row of the queries (the mask of a tile is derived from it on demand)
+    {
+        const unsigned q_it = ring_addr + q_off + k_base;
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
+        for (int qb = 0; qb < NQB; ++qb) {
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            qreg[qb][ks] = *reinterpret_cast<const bf16x8*>(ring + q_off + qb * kTileBytes + k_off[ks]);
-            park(qreg[qb][ks]);
+            for (int ks = 0; ks < 8; ++ks) {
+                qreg[qb][ks] = *(lds_b128_ptr)((q_it + qb * kTileBytes) ^ (ks << 5));
+                park(qreg[qb][ks]);
+            }
+            const int r = min(row0 + qb * 32 + ln, n_rows - 1);
+            tree_row[qb] = r - (int)(((float)r + 0.5f) * a.inv_M) * M;      // r % M
         }
-        const int r = min(row0 + qb * 32 + ln, n_rows - 1);
-        tree_row[qb] = r - (int)(((float)r + 0.5f) * a.inv_M) * M;      // r % M
     }
     __syncthreads();         // the Q staging area goes back to the ring
 #pragma unroll
@@ -312,23 +355,24 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
             for (int j = 0; j < 16; ++j) o[dt][qb][j] = 0.f;
     }
 
-    // The product O^T += V^T P^T of a tile is issued one tile late, next to the exponentials of the
-    // following tile, so that the matrix pipe and the vector ALU work at the same time.  Carried over:
-    // the V^T operands (va) and the probabilities (pb) of the previous tile.
-    bf16x8 va[8], pb[NQB][2];
+    // One tile per round.  The product O^T += V^T P^T of a tile is issued one round late, next to the
+    // exponentials of the following tile, so that the matrix pipe and the vector ALU work at the same time
+    // inside one wave (the waves of a workgroup move in step: they meet at a barrier every round).  Carried
+    // from round to round: the V^T operands and the probabilities of the previous tile.  Two sets of those
+    // registers alternate (the loop body is written out twice), so nothing has to be copied at the loop edge.
+    bf16x8 va_a[8], va_b[8], pb_a[NQB][2], pb_b[NQB][2];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
+    for (int e = 0; e < 8; ++e)
 #pragma unroll
-        for (int x = 0; x < 8; ++x) va[e][x] = (__bf16)0.f;
-    }
+        for (int x = 0; x < 8; ++x) { va_a[e][x] = (__bf16)0.f; va_b[e][x] = (__bf16)0.f; }
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-            for (int x = 0; x < 8; ++x) pb[qb][ks][x] = (__bf16)0.f;
+            for (int x = 0; x < 8; ++x) { pb_a[qb][ks][x] = (__bf16)0.f; pb_b[qb][ks][x] = (__bf16)0.f; }
 
-    auto pv_mfma = [&]() {
+    auto pv_mfma = [&](bf16x8 (&va)[8], bf16x8 (&pb)[NQB][2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -338,7 +382,9 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
                     o[dt][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks * 4 + dt], pb[qb][ks], o[dt][qb], 0, 0, 0);
     };
 
-    for (int it = 0; it < n_iter; ++it) {
+    // Round `it`: consumes the previous tile's (va_in, pb_in), leaves this tile's in (va_out, pb_out).
+    auto tile_round = [&](int it, bf16x8 (&va_in)[8], bf16x8 (&pb_in)[NQB][2], bf16x8 (&va_out)[8],
+                          bf16x8 (&pb_out)[NQB][2]) __attribute__((always_inline)) {
         const bool live = it < n_my;
         if (live) {                                                     // this wave's part of tile `it` has landed
             if (n_my - 1 - it >= S - 2) wait_vmcnt<(S - 2) * PER>();    // steady state: S-2 younger tiles in flight
@@ -350,44 +396,38 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
             __builtin_amdgcn_wave_barrier();
         }
         const bool more = it + S - 1 < n_my;          // another tile to request, into the stage freed last round
-        if (more) issue_half(t_begin + it + S - 1, (it + S - 1) % S, 0);
-        if (!live) continue;
-        const unsigned char* stg = ring + (it % S) * kStageBytes;
+        if (more) issue_tile(t_begin + it + S - 1, (it + S - 1) % S);
+        if (!live) return;
+        const unsigned stage_addr = __builtin_amdgcn_readfirstlane(ring_addr + (it % S) * kStageBytes);
+        const unsigned k_it = stage_addr + k_base, v_it = stage_addr + v_base;
         const int k0 = (t_begin + it) * kTK;
 
         // S^T = K Q^T
-        bf16x8 ka[8];
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            ka[ks] = *reinterpret_cast<const bf16x8*>(stg + k_off[ks]);
-            park(ka[ks]);
-        }
-        // (two accumulation chains per query block, summed afterwards: consecutive matrix instructions
-        //  then never wait for each other's result)
-        f32x16 s[NQB], s_odd[NQB];
+        f32x16 s[NQB];
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) { s[qb][j] = 0.f; s_odd[qb][j] = 0.f; }
+            for (int j = 0; j < 16; ++j) s[qb][j] = 0.f;
+        bf16x8 ka[8];            // all eight reads are requested before the first product (no read waits on a product)
 #pragma unroll
-        for (int ks = 0; ks < 8; ks += 2)
+        for (int ks = 0; ks < 8; ++ks) {
+            ka[ks] = *(lds_b128_ptr)(k_it ^ (ks << 5));
+            park(ka[ks]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int qb = 0; qb < NQB; ++qb) {
+        for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb)
                 s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[qb][ks], s[qb], 0, 0, 0);
-                s_odd[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks + 1], qreg[qb][ks + 1], s_odd[qb], 0, 0, 0);
-            }
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) s[qb] += s_odd[qb];
 
-        if (more) issue_half(t_begin + it + S - 1, (it + S - 1) % S, 1);      // spread the requests: they queue in the texture path
 
         // mask (only tiles touching the soft-prompt slots, the new rows or the tail)
         if ((k0 < a.soft_len) || (k0 + kTK > P)) {
 #pragma unroll
             for (int qb = 0; qb < NQB; ++qb) {
-                // rare (a few tiles per sequence): rebuild the row's ancestor mask from the parent array
-                unsigned long long bits0, bits1;
-                ancestor_bits(sm.parent, tree_row[qb], &bits0, &bits1);
+                // rare (a few tiles per sequence): the row's ancestor mask, left in LDS by the prologue
+                const unsigned long long bits0 = sm.bits[tree_row[qb]][0], bits1 = sm.bits[tree_row[qb]][1];
                 const bool is_con = (sm.kind[tree_row[qb]] == TV_KIND_CONTEMPLATE);
                 const unsigned vis = tile_visibility(k0, P, a.soft_len, is_con, bits0, bits1) >> (4 * hf);
 #pragma unroll
@@ -418,13 +458,13 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
             }
             if (__any(any)) {
                 // rare: bring O up to date with the pending product, then rescale it to the new reference
-                pv_mfma();
+                pv_mfma(va_in, pb_in);
 #pragma unroll
                 for (int qb = 0; qb < NQB; ++qb) {
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                        for (int x = 0; x < 8; ++x) pb[qb][ks][x] = (__bf16)0.f;
+                        for (int x = 0; x < 8; ++x) pb_in[qb][ks][x] = (__bf16)0.f;
                     const float m_new = raise[qb] ? tmax[qb] : m_run[qb];
                     const float alpha = raise[qb] ? __builtin_amdgcn_exp2f(m_run[qb] - m_new) : 1.f;   // exp2(-inf) = 0
                     m_run[qb] = m_new;
@@ -438,7 +478,7 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
         }
 
         // previous tile's O^T += V^T P^T (matrix pipe) next to this tile's exponentials (vector ALU)
-        pv_mfma();
+        pv_mfma(va_in, pb_in);
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) {
             const float mc = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
@@ -447,7 +487,7 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
             for (int j = 0; j < 16; ++j) {
                 const float p = __builtin_amdgcn_exp2f(fmaf(s[qb][j], c, -mc));
                 sum += p;
-                pb[qb][j >> 3][j & 7] = (__bf16)p;
+                pb_out[qb][j >> 3][j & 7] = (__bf16)p;
             }
             l_run[qb] += sum;
         }
@@ -457,15 +497,20 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
-                const unsigned char* p0 = stg + v_off[dt] + ks * (16 * kRowBytes);
-                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((bf16x4 __attribute__((address_space(3)))*)(p0));
-                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-                    (bf16x4 __attribute__((address_space(3)))*)(p0 + 8 * kRowBytes));
-                va[ks * 4 + dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                park(va[ks * 4 + dt]);
+                const unsigned p0 = (v_it ^ (dt << 6)) + ks * (16 * kRowBytes);
+                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(p0));
+                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(p0 + 8 * kRowBytes));
+                va_out[ks * 4 + dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                park(va_out[ks * 4 + dt]);
             }
+    };
+    for (int it = 0; it < n_iter; it += 2) {
+        tile_round(it, va_a, pb_a, va_b, pb_b);
+        if (it + 1 < n_iter) tile_round(it + 1, va_b, pb_b, va_a, pb_a);
     }
-    pv_mfma();               // the last tile's product
+    // the last tile's product: its operands are in set b after an odd number of tiles, else in set a
+    if (n_my & 1) pv_mfma(va_b, pb_b);
+    else pv_mfma(va_a, pb_a);
 
     // ---- merge the streams through LDS -------------------------------------------------------------------
     // Merge buffer: [wave][its rows][32 float4]; float4 column c of a wave's row r is stored at column c ^ (r & 31).
