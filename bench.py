@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 WORKLOAD_INDEX = 2              # llama3.1-8b-32layers
+PAPER_LAYOUT_INDEX = 5          # the same model shape with one contemplate row per draft node
 
 
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "attn_bf16_kernel_llama8b_hbm_traffic.txt")
@@ -50,6 +51,8 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
     ap.add_argument("--splits", type=int, default=0, help="key ranges per sequence (0 = library decides)")
     ap.add_argument("--wg-row-blocks", type=int, default=0, help="row blocks sharing a key stream (0 = library decides)")
+    ap.add_argument("--no-paper-layout", action="store_true",
+                    help="skip the extra measurement of the paper's 120-row layout")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run three plain device copies of this many MiB before the timed region "
                          "(a kernel of known traffic, to scale hardware counters of a profiler run)")
@@ -72,27 +75,42 @@ def main() -> int:
 
     # ---- inputs, resident in HBM -------------------------------------------------------------------
     t0 = time.time()
-    layer0 = si.attention_case(WORKLOAD_INDEX, layer=0)
-    M, P = layer0.M, int(layer0.prefix_len[0])
-    rows = P + M
-    kpool = torch.empty((L, rows, w.Hkv, w.D), device="cuda", dtype=torch.bfloat16)
-    vpool = torch.empty_like(kpool)
-    qs = torch.empty((L, 1, M, w.Hq, w.D), device="cuda", dtype=torch.bfloat16)
-    for l in range(L):
-        x = layer0 if l == 0 else si.attention_case(WORKLOAD_INDEX, layer=l)
-        kpool[l].copy_(H.to_device_storage(x.k_pool, "bf16"))
-        vpool[l].copy_(H.to_device_storage(x.v_pool, "bf16"))
-        qs[l].copy_(H.to_device_storage(x.q, "bf16"))
-    outs = torch.empty_like(qs)
-    kv_off = torch.zeros(1, dtype=torch.int64, device="cuda")
-    plen = torch.from_numpy(layer0.prefix_len).cuda()
-    parent = torch.from_numpy(layer0.parent).cuda()
-    kind = torch.from_numpy(layer0.kind).cuda()
-    status = torch.zeros(1, dtype=torch.int32, device="cuda")
-    adesc = tv.make_attn_desc(dtype=tv.TV_DTYPE_BF16, B=1, M=M, Hq=w.Hq, Hkv=w.Hkv, D=w.D, soft_len=0,
-                              max_prefix_len=P, softmax_scale=layer0.scale, num_splits=args.splits,
-                              wg_row_blocks=args.wg_row_blocks)
-    aws = torch.empty(max(tv.tv_attention_workspace_bytes(adesc), 256), device="cuda", dtype=torch.uint8)
+    def attention_setup(index, soft_len=0):
+        """All layers of workload `index` in one KV pool on the device, and a function that launches them."""
+        wk = si.WORKLOADS[index]
+        first = si.attention_case(index, layer=0, soft_len=soft_len)
+        m, p = first.M, int(first.prefix_len[0])
+        kp = torch.empty((L, p + m, wk.Hkv, wk.D), device="cuda", dtype=torch.bfloat16)
+        vp = torch.empty_like(kp)
+        q = torch.empty((L, 1, m, wk.Hq, wk.D), device="cuda", dtype=torch.bfloat16)
+        for l in range(L):
+            x = first if l == 0 else si.attention_case(index, layer=l, soft_len=soft_len)
+            kp[l].copy_(H.to_device_storage(x.k_pool, "bf16"))
+            vp[l].copy_(H.to_device_storage(x.v_pool, "bf16"))
+            q[l].copy_(H.to_device_storage(x.q, "bf16"))
+        o = torch.empty_like(q)
+        off = torch.zeros(1, dtype=torch.int64, device="cuda")
+        pl = torch.from_numpy(first.prefix_len).cuda()
+        par = torch.from_numpy(first.parent).cuda()
+        kin = torch.from_numpy(first.kind).cuda()
+        st = torch.zeros(1, dtype=torch.int32, device="cuda")
+        desc = tv.make_attn_desc(dtype=tv.TV_DTYPE_BF16, B=1, M=m, Hq=wk.Hq, Hkv=wk.Hkv, D=wk.D, soft_len=soft_len,
+                                 max_prefix_len=p, softmax_scale=first.scale, num_splits=args.splits,
+                                 wg_row_blocks=args.wg_row_blocks)
+        ws = torch.empty(max(tv.tv_attention_workspace_bytes(desc), 256), device="cuda", dtype=torch.uint8)
+
+        def run():
+            for l in range(L):
+                tv.tree_verify_attention(desc, q[l], kp[l], vp[l], off, pl, par, kin, o[l], None, st, ws)
+
+        bytes_layer = 2 * (p + m) * wk.Hkv * wk.D * 2 + 2 * m * wk.Hq * wk.D * 2
+        flops_layer = 4 * m * wk.Hq * (p + m) * wk.D
+        return {"run": run, "first": first, "out": o, "M": m, "P": p, "bytes": bytes_layer, "flops": flops_layer,
+                "keep": (kp, vp, q, off, pl, par, kin, st, ws)}
+
+    main_attn = attention_setup(WORKLOAD_INDEX)
+    layer0, outs, M, P = main_attn["first"], main_attn["out"], main_attn["M"], main_attn["P"]
+    attention_layers = main_attn["run"]
 
     acc = si.accept_case(WORKLOAD_INDEX, 1, child_boost=5.0)      # temperature 1.0, no draft logits
     cdesc = tv.make_accept_desc(B=1, T=acc.T, V=acc.V, C=acc.C, rule=acc.rule, temperature=acc.temperature)
@@ -110,11 +128,6 @@ def main() -> int:
     gtl = torch.from_numpy(gacc.target_logits).cuda()
     gtoken = torch.from_numpy(gacc.token).cuda()
     setup_s = time.time() - t0
-
-    def attention_layers():
-        for l in range(L):
-            tv.tree_verify_attention(adesc, qs[l], kpool[l], vpool[l], kv_off, plen, parent, kind, outs[l], None,
-                                     status, aws)
 
     def accept():
         tv.tree_accept(cdesc, tl, None, token, aparent, un, ca, path, o_n, o_tok, o_kind, o_last, o_con, o_st, cws)
@@ -166,6 +179,23 @@ def main() -> int:
     ms_greedy = timed(accept_greedy, args.steps * 4, args.warmup)
     us_layer = ms_attn * 1e3 / L
 
+    # ---- the paper's own layout (one contemplate row per node, 120 rows, 16 soft-prompt slots): MFMA-bound --------
+    paper = None
+    if not args.no_paper_layout:
+        pa = attention_setup(PAPER_LAYOUT_INDEX, soft_len=16)
+        us_paper = timed(pa["run"], max(args.steps // 2, 2), 2) * 1e3 / L
+        got = pa["out"][0].float().cpu().numpy()[0].astype(np.float64)
+        pref = H.oracle_attention_rows(pa["first"], 0, range(pa["M"]), heads=[3])
+        perr = max(float(np.abs(got[i, h] - r).max()) for (i, h), r in pref.items())
+        paper = {"workload": si.WORKLOADS[PAPER_LAYOUT_INDEX].name, "rows": pa["M"], "soft_len": 16, "prefix": pa["P"],
+                 "us_per_layer": round(us_paper, 3),
+                 "roofline": {"bound": "mfma", "achieved": round(pa["flops"] / (us_paper * 1e-6) / 1e12, 1),
+                              "peak": 2500.0, "unit": "TFLOP/s",
+                              "frac": round(pa["flops"] / (us_paper * 1e-6) / 2.5e15, 4), "traffic": None},
+                 "hbm_gbps_on_algorithmic_bytes": round(pa["bytes"] / (us_paper * 1e-6) / 1e9, 1),
+                 "max_abs_err_layer0_head3": perr}
+        del pa
+
     # ---- sampled parity on what was just computed (layer 0, two heads; the acceptance result) -----------
     torch.cuda.synchronize()
     got0 = outs[0].float().cpu().numpy()[0].astype(np.float64)
@@ -179,8 +209,7 @@ def main() -> int:
                  and np.array_equal(path.cpu().numpy()[0], aref["path"]))
 
     # ---- roofline of the dominant kernel (attention) ------------------------------------------------------
-    bytes_layer = 2 * (P + M) * w.Hkv * w.D * 2 + 2 * M * w.Hq * w.D * 2
-    flops_layer = 4 * M * w.Hq * (P + M) * w.D
+    bytes_layer, flops_layer = main_attn["bytes"], main_attn["flops"]
     achieved = bytes_layer / (us_layer * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic_bytes(),
@@ -225,6 +254,7 @@ def main() -> int:
         "tree_accept_steps_per_s": {"temp1.0_deterministic": round(1e3 / ms_accept, 1),
                                     "temp0_greedy": round(1e3 / ms_greedy, 1)},
         "tree_accept": accept_info,
+        "contemplate_row_per_node": paper,
         "verify_steps_per_s": round(1e3 / ms_step, 2),
         "attention_tb_per_s": round(achieved / 1e3, 3),
         "roofline": roofline,

@@ -1,4 +1,4 @@
-"""The five synthetic workloads (shapes of the paper's evaluation: Llama-3.2-3B,
+"""The synthetic workloads (shapes of the paper's evaluation: Llama-3.2-3B,
 Llama-3.1-8B and Qwen3-4B targets, 60-node draft trees; Section 4) plus helpers that
 build one attention case / one acceptance case for a workload.
 
@@ -51,7 +51,13 @@ WORKLOADS = [
              ((1.0, tensors.RULE_DETERMINISTIC),), 1003),
     Workload("qwen3-4b-long", "bf16", 1, 32, 8, 128, 16384, 60, 4, 10, 8, 1, 151936, 3.0, _SQ,
              ((1.0, tensors.RULE_DRAFT_WOR),), 1004),
+    # the paper's own verification layout (Section 3.1): one contemplate row per draft node (C = T, 2T = 120 rows,
+    # interleaved) and 16 soft-prompt slots at the head of the cache; Llama-3.1-8B head geometry
+    Workload("llama3.1-8b-contemplate-per-node", "bf16", 1, 32, 8, 128, 4096 + 16, 60, 60, 8, 8, 32, 128256, 3.0, _SQ,
+             ((1.0, tensors.RULE_DETERMINISTIC),), 1005),
 ]
+
+PAPER_SOFT_LEN = 16      # soft-prompt slots named in Section 3.1
 
 
 def _trees_for(w: Workload, B: int):
@@ -81,7 +87,10 @@ def attention_case(index: int, *, layer: int = 0, soft_len: int = 0, peaked: boo
     node_parent = _trees_for(w, w.B)
     par, kin = [], []
     for b in range(w.B):
-        p, k, _ = trees.append_contemplates_chained(node_parent[b], w.C, anchor=0)
+        if w.C == w.T:
+            p, k, _, _ = trees.interleave_contemplates_per_node(node_parent[b])
+        else:
+            p, k, _ = trees.append_contemplates_chained(node_parent[b], w.C, anchor=0)
         par.append(p)
         kin.append(k)
     rng = np.random.default_rng([w.seed, layer, int(peaked), soft_len])
@@ -105,7 +114,10 @@ def accept_case(index: int, mode: int = 0, *, draft_target_corr: float = 0.0, ch
     temperature, rule = w.accept_modes[mode]
     node_parent = _trees_for(w, w.B)
     rng = np.random.default_rng([w.seed, 77, mode])
-    con_anchor = np.zeros((w.B, w.C), dtype=np.int32)
+    if w.C == w.T:      # one contemplate row per node: row c predicts the future of node c
+        con_anchor = np.tile(np.arange(w.C, dtype=np.int32), (w.B, 1))
+    else:               # a few contemplate rows, all anchored at the root
+        con_anchor = np.zeros((w.B, w.C), dtype=np.int32)
     return tensors.make_accept_inputs(
         rng, parent=node_parent, V=int(V_override or w.V), temperature=temperature, rule=rule,
         logit_std=w.logit_std, con_anchor=con_anchor, draft_target_corr=draft_target_corr,

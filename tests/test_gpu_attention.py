@@ -216,6 +216,16 @@ def test_full_size_long_context_sampled_heads():
         assert np.abs(out[0, i, h] - r).max() <= REL_TOL_BF16 * np.abs(r).max() + 1e-4
 
 
+@pytest.mark.parametrize("peaked", [False, True])
+def test_full_size_contemplate_row_per_node(peaked):
+    """The paper's verification layout at Llama-3.1-8B size (Section 3.1): 60 nodes each followed by its
+    contemplate row (120 rows, two mask words), 16 soft-prompt slots, prefix 4096: all outputs."""
+    inp = si.attention_case(5, soft_len=16, peaked=peaked)
+    assert inp.M == 120 and inp.soft_len == 16
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st)
+
+
 def test_full_size_ragged_batch_sampled_heads():
     """Eight sequences, prefix lengths 512..8192, one pool: two heads of every sequence."""
     inp = si.attention_case(3, peaked=True)
