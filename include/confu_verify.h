@@ -52,6 +52,7 @@ extern "C" {
 #define TV_STATUS_BAD_PREFIX    4   /* prefix_len < soft_len, < 0 or > max_prefix_len */
 #define TV_STATUS_BAD_TOKEN     8   /* token id outside [0, V) */
 #define TV_STATUS_INTERNAL     16   /* a bounded wait between workgroups ran out (tree_accept, draft rules) */
+#define TV_STATUS_BAD_PATH     32   /* tree_commit: path not a strictly increasing list of nodes starting at the root */
 
 /* ---- limits -------------------------------------------------------------------- */
 #define TV_MAX_ROWS   128          /* M (attention) and T (acceptance) */
@@ -182,6 +183,99 @@ int tree_accept(
 /* =================================================================================
  * Host helpers
  * ================================================================================= */
+
+/* =================================================================================
+ * tree_commit
+ *
+ * Operation (paper: Section 2, step 3 - a rejected draft token and everything after it
+ * are discarded; tree form: the longest accepted path is kept; Section 3.1 - after
+ * verification the future prediction that belongs to the last accepted token is the one
+ * handed to the draft model for the next iteration).
+ *
+ * After tree_accept: for every layer l < n_layers, sequence b and j = 0 .. n_accepted[b],
+ * the K and V rows of tree node path[b][j] (new row node_row[b][path[b][j]] of this step)
+ * are moved to new row j, so that the cache holds the accepted tokens contiguously, in
+ * order, right behind the old prefix; rows of rejected nodes and of contemplate rows are
+ * dropped (left as they are behind the new end).  new_prefix_len[b] = prefix_len[b] +
+ * n_accepted[b] + 1.  If hidden is given, f_out[b,:] = hidden[b, con_row[b][selected_con[b]], :]
+ * (zeros when selected_con[b] < 0).
+ *
+ * A sequence with n_accepted[b] < 0 (tree_accept flagged it) is left untouched:
+ * new_prefix_len[b] = prefix_len[b], status[b] = 0.  A malformed path (not starting at
+ * node 0, not strictly increasing, outside [0,T), or a mapped row outside [0,M)) sets
+ * TV_STATUS_BAD_PATH and leaves the sequence untouched.
+ * ================================================================================= */
+typedef struct tv_commit_desc {
+    uint32_t struct_size;      /* sizeof(tv_commit_desc), checked */
+    int32_t  dtype;            /* element type of the pools, hidden and f_out: TV_DTYPE_F32 or TV_DTYPE_BF16 */
+    int32_t  B;                /* sequences, >= 1 */
+    int32_t  T;                /* tree nodes per sequence (row length of path and node_row), 1..TV_MAX_ROWS */
+    int32_t  M;                /* new rows per sequence in the pools (nodes + contemplate rows), T..TV_MAX_ROWS */
+    int32_t  Hkv;              /* KV heads */
+    int32_t  D;                /* head dimension; D * element size is a multiple of 16 bytes */
+    int32_t  n_layers;         /* layers compacted by this call, >= 1 */
+    int64_t  kv_layer_stride;  /* elements between the pools of consecutive layers (ignored when n_layers = 1) */
+    int64_t  kv_token_stride;  /* as in tv_attn_desc; 0 = Hkv*D */
+    int64_t  kv_head_stride;   /* as in tv_attn_desc; 0 = D */
+    int32_t  C;                /* contemplate rows per sequence (row length of con_row), >= 0 */
+    int32_t  d_model;          /* elements of a hidden row; d_model * element size is a multiple of 16 bytes; 0 = no gather */
+} tv_commit_desc;
+
+/* Enqueues the work on hip_stream and returns without synchronising; no workspace.
+ * Returns TV_OK, TV_ERR_INVALID_ARG, TV_ERR_LAUNCH. */
+int tree_commit(
+    const tv_commit_desc* desc,
+    void*          k_pool,          /* device, updated in place: layer l starts at element l*kv_layer_stride */
+    void*          v_pool,          /* device, same layout */
+    const int64_t* kv_offset,       /* device [B] */
+    const int32_t* prefix_len,      /* device [B]: P_b before this step */
+    const int32_t* path,            /* device [B,T]: from tree_accept */
+    const int32_t* n_accepted,      /* device [B]: from tree_accept */
+    const int32_t* node_row,        /* device [B,T]: new-row index of tree node i (i if the nodes come first, 2i if a
+                                       contemplate row follows each node), or NULL for the identity */
+    const void*    hidden,          /* device [B,M,d_model] or NULL: final hidden states of this step's rows */
+    const int32_t* con_row,         /* device [B,C]: new-row index of contemplate row c; NULL iff hidden is NULL */
+    const int32_t* selected_con,    /* device [B]: from tree_accept; NULL iff hidden is NULL */
+    void*          f_out,           /* device [B,d_model]; NULL iff hidden is NULL */
+    int32_t*       new_prefix_len,  /* device [B] */
+    int32_t*       status,          /* device [B]: TV_STATUS_* bits */
+    void*          hip_stream);
+
+/* =================================================================================
+ * contemplate_embed
+ *
+ * Operation (paper: Section 3.2, dynamic contemplate tokens): the embedding of a
+ * contemplate (or future) token is a mixture of n_expert learnable embeddings, gated by
+ * the hidden state h of the most recently accepted token:
+ *
+ *   g = softmax(W h)  over the n_expert experts,  S = the k_expert experts with the largest
+ *   g (ties: lowest index),  out = sum_{e in S} g_e * E[e,:]
+ *
+ * (the gates are the softmax scores themselves: they are not renormalised over S).
+ * h, W, E and out share one element type; sums are fp32.
+ * ================================================================================= */
+typedef struct tv_embed_desc {
+    uint32_t struct_size;      /* sizeof(tv_embed_desc), checked */
+    int32_t  dtype;            /* TV_DTYPE_F32 or TV_DTYPE_BF16 */
+    int32_t  B;                /* tokens embedded by this call, >= 1 */
+    int32_t  d_in;             /* width of h (the target's concatenated hidden state, or the draft's), multiple of 8 */
+    int32_t  d_out;            /* width of an expert embedding, multiple of 8 */
+    int32_t  n_expert;         /* 1..64 */
+    int32_t  k_expert;         /* 1..n_expert */
+    int32_t  reserved;         /* 0 */
+} tv_embed_desc;
+
+/* Enqueues the work on hip_stream and returns without synchronising; no workspace.
+ * Returns TV_OK, TV_ERR_INVALID_ARG, TV_ERR_LAUNCH. */
+int contemplate_embed(
+    const tv_embed_desc* desc,
+    const void*    h,               /* device [B, d_in] */
+    const void*    router_w,        /* device [n_expert, d_in], row major */
+    const void*    expert_emb,      /* device [n_expert, d_out] */
+    void*          out,             /* device [B, d_out] */
+    float*         gates,           /* device [B, n_expert] or NULL: the softmax scores g */
+    int32_t*       chosen,          /* device [B, k_expert] or NULL: the selected experts, best first */
+    void*          hip_stream);
 
 /* host: checks a parent/kind pair and writes the ancestor-closure bit mask the attention
  * kernels build on the device: bit j of bits[2*i + j/64] is set iff row i may attend to new
