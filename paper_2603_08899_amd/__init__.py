@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libconfu_verify.so")
 TV_OK, TV_ERR_INVALID_ARG, TV_ERR_WORKSPACE, TV_ERR_LAUNCH, TV_ERR_UNSUPPORTED = 0, 1, 2, 3, 4
 TV_STATUS_BAD_PARENT, TV_STATUS_BAD_KIND, TV_STATUS_BAD_PREFIX, TV_STATUS_BAD_TOKEN = 1, 2, 4, 8
 TV_STATUS_INTERNAL = 16
+TV_STATUS_BAD_PATH = 32
 TV_MAX_ROWS = 128
 TV_DTYPE_F32, TV_DTYPE_BF16 = 0, 1
 TV_KIND_NODE, TV_KIND_CONTEMPLATE = 0, 1
@@ -27,6 +28,7 @@ TV_FINAL_BONUS, TV_FINAL_RESIDUAL = 0, 1
 EXPORTED_SYMBOLS = (
     "tv_attention_workspace_bytes", "tree_verify_attention",
     "tv_accept_workspace_bytes", "tree_accept",
+    "tree_commit", "contemplate_embed",
     "tv_build_mask_host", "tv_error_string", "tv_version", "tv_set_wait_limit",
 )
 
@@ -48,6 +50,23 @@ class tv_accept_desc(ctypes.Structure):
         ("V", ctypes.c_int32), ("C", ctypes.c_int32), ("rule", ctypes.c_int32),
         ("temperature", ctypes.c_float), ("logits_row_stride", ctypes.c_int64),
         ("reserved", ctypes.c_int32 * 2),
+    ]
+
+
+class tv_commit_desc(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32), ("dtype", ctypes.c_int32), ("B", ctypes.c_int32), ("T", ctypes.c_int32),
+        ("M", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("D", ctypes.c_int32), ("n_layers", ctypes.c_int32),
+        ("kv_layer_stride", ctypes.c_int64), ("kv_token_stride", ctypes.c_int64), ("kv_head_stride", ctypes.c_int64),
+        ("C", ctypes.c_int32), ("d_model", ctypes.c_int32),
+    ]
+
+
+class tv_embed_desc(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32), ("dtype", ctypes.c_int32), ("B", ctypes.c_int32), ("d_in", ctypes.c_int32),
+        ("d_out", ctypes.c_int32), ("n_expert", ctypes.c_int32), ("k_expert", ctypes.c_int32),
+        ("reserved", ctypes.c_int32),
     ]
 
 
@@ -86,6 +105,10 @@ def lib() -> ctypes.CDLL:
         l.tv_accept_workspace_bytes.argtypes = [ctypes.POINTER(tv_accept_desc), ctypes.POINTER(sz)]
         l.tree_accept.restype = ctypes.c_int
         l.tree_accept.argtypes = [ctypes.POINTER(tv_accept_desc)] + [vp] * 14 + [sz, vp]
+        l.tree_commit.restype = ctypes.c_int
+        l.tree_commit.argtypes = [ctypes.POINTER(tv_commit_desc)] + [vp] * 14
+        l.contemplate_embed.restype = ctypes.c_int
+        l.contemplate_embed.argtypes = [ctypes.POINTER(tv_embed_desc)] + [vp] * 7
         _lib = l
     return _lib
 
@@ -168,3 +191,33 @@ def tree_accept(desc: tv_accept_desc, target_logits, draft_logits, token, parent
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc:
         raise ConfuVerifyError(rc, "tree_accept")
+
+
+def make_commit_desc(*, dtype: int, B: int, T: int, M: int, Hkv: int, D: int, n_layers: int, kv_layer_stride: int = 0,
+                     kv_token_stride: int = 0, kv_head_stride: int = 0, C: int = 0, d_model: int = 0) -> tv_commit_desc:
+    return tv_commit_desc(ctypes.sizeof(tv_commit_desc), dtype, B, T, M, Hkv, D, n_layers, kv_layer_stride,
+                          kv_token_stride, kv_head_stride, C, d_model)
+
+
+def tree_commit(desc: tv_commit_desc, k_pool, v_pool, kv_offset, prefix_len, path, n_accepted, node_row, hidden,
+                con_row, selected_con, f_out, new_prefix_len, status, stream=None) -> None:
+    """Moves the accepted path's K/V rows to the front of this step's rows in every layer (in place) and, when
+    `hidden` is given, gathers the future prediction of the last accepted token; see include/confu_verify.h."""
+    rc = lib().tree_commit(
+        ctypes.byref(desc), _ptr(k_pool), _ptr(v_pool), _ptr(kv_offset), _ptr(prefix_len), _ptr(path),
+        _ptr(n_accepted), _ptr(node_row), _ptr(hidden), _ptr(con_row), _ptr(selected_con), _ptr(f_out),
+        _ptr(new_prefix_len), _ptr(status), _stream_handle(stream))
+    if rc:
+        raise ConfuVerifyError(rc, "tree_commit")
+
+
+def make_embed_desc(*, dtype: int, B: int, d_in: int, d_out: int, n_expert: int, k_expert: int) -> tv_embed_desc:
+    return tv_embed_desc(ctypes.sizeof(tv_embed_desc), dtype, B, d_in, d_out, n_expert, k_expert, 0)
+
+
+def contemplate_embed(desc: tv_embed_desc, h, router_w, expert_emb, out, gates, chosen, stream=None) -> None:
+    """Mixture-of-experts embedding of contemplate / future tokens; see include/confu_verify.h."""
+    rc = lib().contemplate_embed(ctypes.byref(desc), _ptr(h), _ptr(router_w), _ptr(expert_emb), _ptr(out),
+                                 _ptr(gates), _ptr(chosen), _stream_handle(stream))
+    if rc:
+        raise ConfuVerifyError(rc, "contemplate_embed")

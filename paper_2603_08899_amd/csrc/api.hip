@@ -254,4 +254,55 @@ int tree_accept(const tv_accept_desc* desc, const float* target_logits, const fl
     return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;
 }
 
+int tree_commit(const tv_commit_desc* d, void* k_pool, void* v_pool, const int64_t* kv_offset,
+                const int32_t* prefix_len, const int32_t* path, const int32_t* n_accepted, const int32_t* node_row,
+                const void* hidden, const int32_t* con_row, const int32_t* selected_con, void* f_out,
+                int32_t* new_prefix_len, int32_t* status, void* hip_stream) {
+    if (!d || d->struct_size != sizeof(tv_commit_desc)) return TV_ERR_INVALID_ARG;
+    if (d->dtype != TV_DTYPE_F32 && d->dtype != TV_DTYPE_BF16) return TV_ERR_INVALID_ARG;
+    const int elem = (d->dtype == TV_DTYPE_F32) ? 4 : 2;
+    if (d->B < 1 || d->B > 65535 || d->T < 1 || d->T > TV_MAX_ROWS || d->M < d->T || d->M > TV_MAX_ROWS) return TV_ERR_INVALID_ARG;
+    if (d->Hkv < 1 || d->D < 1 || (d->D * elem) % 16 != 0 || d->n_layers < 1 || d->n_layers > 65535) return TV_ERR_INVALID_ARG;
+    if (d->C < 0 || d->d_model < 0 || (d->d_model * elem) % 16 != 0) return TV_ERR_INVALID_ARG;
+    if (d->kv_token_stride < 0 || d->kv_head_stride < 0 || d->kv_layer_stride < 0) return TV_ERR_INVALID_ARG;
+    const int64_t hs = d->kv_head_stride ? d->kv_head_stride : d->D;
+    const int64_t ts = d->kv_token_stride ? d->kv_token_stride : (int64_t)d->Hkv * d->D;
+    if (hs < d->D || ts < d->D || (hs * elem) % 16 != 0 || (ts * elem) % 16 != 0) return TV_ERR_INVALID_ARG;
+    if (d->n_layers > 1 && (d->kv_layer_stride <= 0 || (d->kv_layer_stride * elem) % 16 != 0)) return TV_ERR_INVALID_ARG;
+    if (!k_pool || !v_pool || !kv_offset || !prefix_len || !path || !n_accepted || !new_prefix_len || !status)
+        return TV_ERR_INVALID_ARG;
+    if (((uintptr_t)k_pool | (uintptr_t)v_pool) & 15) return TV_ERR_INVALID_ARG;
+    const bool gather = hidden != nullptr;
+    if (gather && (!con_row || !selected_con || !f_out || d->d_model < 1 || d->C < 1)) return TV_ERR_INVALID_ARG;
+    if (gather && (((uintptr_t)hidden | (uintptr_t)f_out) & 15)) return TV_ERR_INVALID_ARG;
+    CommitArgs a{};
+    a.k = k_pool; a.v = v_pool; a.kv_offset = kv_offset; a.prefix_len = prefix_len; a.path = path;
+    a.n_accepted = n_accepted; a.node_row = node_row;
+    a.hidden = hidden; a.con_row = gather ? con_row : nullptr; a.selected_con = gather ? selected_con : nullptr;
+    a.f_out = gather ? f_out : nullptr;
+    a.new_prefix_len = new_prefix_len; a.status = status;
+    a.B = d->B; a.T = d->T; a.M = d->M; a.Hkv = d->Hkv; a.D = d->D; a.n_layers = d->n_layers; a.C = d->C;
+    a.d_model = d->d_model; a.elem = elem;
+    a.layer_stride = d->n_layers > 1 ? d->kv_layer_stride : 0; a.tok_stride = ts; a.head_stride = hs;
+    const hipError_t e = launch_commit(a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;
+}
+
+int contemplate_embed(const tv_embed_desc* d, const void* h, const void* router_w, const void* expert_emb, void* out,
+                      float* gates, int32_t* chosen, void* hip_stream) {
+    if (!d || d->struct_size != sizeof(tv_embed_desc)) return TV_ERR_INVALID_ARG;
+    if (d->dtype != TV_DTYPE_F32 && d->dtype != TV_DTYPE_BF16) return TV_ERR_INVALID_ARG;
+    if (d->B < 1 || d->d_in < 8 || d->d_in % 8 != 0 || d->d_out < 8 || d->d_out % 8 != 0) return TV_ERR_INVALID_ARG;
+    if (d->n_expert < 1 || d->n_expert > 64 || d->k_expert < 1 || d->k_expert > d->n_expert || d->reserved != 0)
+        return TV_ERR_INVALID_ARG;
+    if (!h || !router_w || !expert_emb || !out) return TV_ERR_INVALID_ARG;
+    if (((uintptr_t)h | (uintptr_t)router_w | (uintptr_t)expert_emb | (uintptr_t)out) & 15) return TV_ERR_INVALID_ARG;
+    EmbedArgs a{};
+    a.h = h; a.router_w = router_w; a.expert_emb = expert_emb; a.out = out; a.gates = gates; a.chosen = chosen;
+    a.B = d->B; a.d_in = d->d_in; a.d_out = d->d_out; a.n_expert = d->n_expert; a.k_expert = d->k_expert;
+    a.bf16 = (d->dtype == TV_DTYPE_BF16);
+    const hipError_t e = launch_embed(a, static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;
+}
+
 }  // extern "C"

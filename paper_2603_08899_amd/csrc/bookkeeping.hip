@@ -1,0 +1,223 @@
+// The two small steps around the verification pass, for gfx950:
+//   tree_commit        moves the K/V rows of the accepted path to the front of this step's rows in every
+//                      layer's pool (rejected nodes and contemplate rows are dropped) and picks the future
+//                      prediction of the last accepted token   (paper: Section 2, step 3; Section 3.1)
+//   contemplate_embed  mixture-of-experts embedding of a contemplate / future token: router logits,
+//                      softmax, top-K, weighted sum of expert embeddings   (paper: Section 3.2)
+// Both are small and bound by memory latency; plain ALUs, 16-byte accesses.
+#include "tv_internal.hpp"
+
+namespace tv {
+
+namespace {
+
+constexpr int kCommitThreads = 256;
+constexpr int kCommitHeld = 8;                                  // 16-byte pieces a lane holds at once
+constexpr int kCommitChunk = kCommitThreads * kCommitHeld;      // pieces moved between two barriers
+
+// ---- tree_commit ------------------------------------------------------------------------------------------
+// Grid (n_layers, B, 2): one workgroup moves the accepted rows of one sequence in the K (z = 0) or V (z = 1)
+// pool of one layer.  Row j of the new cache comes from new row src[j] >= j; several moves of one sequence
+// overlap (a destination may be the source of an earlier entry of the path), so a chunk of rows is read
+// completely before any of it is written.  Later sources lie strictly behind every earlier destination, so
+// chunks can follow each other without further ordering.
+__global__ __launch_bounds__(kCommitThreads) void commit_kernel(CommitArgs a) {
+    const int l = blockIdx.x, b = blockIdx.y, which = blockIdx.z;
+    const int tid = threadIdx.x, T = a.T;
+    __shared__ int s_src[kMaxRows];
+    __shared__ int s_ok;
+    const int n = a.n_accepted[b];
+    if (tid == 0) s_ok = 1;
+    __syncthreads();
+    if (n >= 0 && n < T && tid <= n) {
+        const int node = a.path[(int64_t)b * T + tid];
+        const int prev = (tid > 0) ? a.path[(int64_t)b * T + tid - 1] : -1;
+        bool bad = node < 0 || node >= T || node <= prev || (tid == 0 && node != 0);
+        int row = -1;
+        if (!bad) {
+            row = a.node_row ? a.node_row[(int64_t)b * T + node] : node;
+            bad = row < 0 || row >= a.M;
+        }
+        s_src[tid] = row;
+        if (bad) s_ok = 0;
+    }
+    __syncthreads();
+    const bool ok = n >= 0 && n < T && s_ok != 0;
+    const int P = a.prefix_len[b];
+    if (l == 0 && which == 0 && tid == 0) {
+        a.status[b] = (n >= 0 && !ok) ? TV_STATUS_BAD_PATH : TV_STATUS_OK;
+        a.new_prefix_len[b] = P + (ok ? n + 1 : 0);
+    }
+    if (l == 0 && which == 1 && a.hidden) {
+        // the future prediction that belongs to the last accepted token
+        const int c = a.selected_con[b];
+        const int row = (c >= 0 && c < a.C) ? a.con_row[(int64_t)b * a.C + c] : -1;
+        const int pieces = a.d_model * a.elem / 16;
+        uint4* dst = reinterpret_cast<uint4*>(static_cast<unsigned char*>(a.f_out) + (int64_t)b * a.d_model * a.elem);
+        const uint4* src = (row >= 0 && row < a.M)
+            ? reinterpret_cast<const uint4*>(static_cast<const unsigned char*>(a.hidden) +
+                                             ((int64_t)b * a.M + row) * a.d_model * a.elem)
+            : nullptr;
+        for (int i = tid; i < pieces; i += kCommitThreads) dst[i] = src ? src[i] : make_uint4(0u, 0u, 0u, 0u);
+    }
+    if (!ok) return;
+
+    unsigned char* pool = static_cast<unsigned char*>(which ? a.v : a.k) +
+                          ((int64_t)l * a.layer_stride + (a.kv_offset[b] + P) * a.tok_stride) * a.elem;
+    const int segs = a.D * a.elem / 16;                 // 16-byte pieces of one head's row
+    const int per_row = a.Hkv * segs;
+    auto piece = [&](int row, int rem) -> uint4* {
+        const int g = rem / segs, sg = rem - g * segs;
+        return reinterpret_cast<uint4*>(pool + ((int64_t)row * a.tok_stride + (int64_t)g * a.head_stride) * a.elem) + sg;
+    };
+    if (per_row <= kCommitChunk) {
+        const int rows_per_chunk = kCommitChunk / per_row;
+        for (int j0 = 0; j0 <= n; j0 += rows_per_chunk) {
+            const int rows = min(rows_per_chunk, n + 1 - j0);
+            const int units = rows * per_row;
+            uint4 held[kCommitHeld];
+#pragma unroll
+            for (int k = 0; k < kCommitHeld; ++k) {
+                const int u = tid + k * kCommitThreads;
+                if (u < units) {
+                    const int j = j0 + u / per_row;
+                    held[k] = *piece(s_src[j], u % per_row);
+                }
+            }
+            __syncthreads();                            // every read of the chunk is complete
+#pragma unroll
+            for (int k = 0; k < kCommitHeld; ++k) {
+                const int u = tid + k * kCommitThreads;
+                if (u < units) {
+                    const int j = j0 + u / per_row;
+                    if (s_src[j] != j) *piece(j, u % per_row) = held[k];
+                }
+            }
+        }
+    } else {
+        // very wide rows: one row at a time (its source is another row, or itself)
+        for (int j = 0; j <= n; ++j) {
+            if (s_src[j] == j) continue;
+            for (int u = tid; u < per_row; u += kCommitThreads) *piece(j, u) = *piece(s_src[j], u);
+            __syncthreads();
+        }
+    }
+}
+
+// ---- contemplate_embed --------------------------------------------------------------------------------------
+constexpr int kEmbedThreads = 1024;
+constexpr int kEmbedWaves = kEmbedThreads / kWave;
+constexpr int kMaxExperts = 64;
+
+template <bool kBf16>
+__device__ __forceinline__ void load8(const void* base, int64_t index, float* x) {
+    if (kBf16) {
+        const uint4 r = *reinterpret_cast<const uint4*>(static_cast<const unsigned short*>(base) + index);
+        const unsigned w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[2 * i] = __uint_as_float(w[i] << 16);
+            x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    } else {
+        const float4 r0 = *reinterpret_cast<const float4*>(static_cast<const float*>(base) + index);
+        const float4 r1 = *reinterpret_cast<const float4*>(static_cast<const float*>(base) + index + 4);
+        x[0] = r0.x; x[1] = r0.y; x[2] = r0.z; x[3] = r0.w;
+        x[4] = r1.x; x[5] = r1.y; x[6] = r1.z; x[7] = r1.w;
+    }
+}
+
+// One workgroup per token: the waves share the experts' router rows, wave 0 normalises and selects, all lanes
+// form the output.
+template <bool kBf16>
+__global__ __launch_bounds__(kEmbedThreads) void embed_kernel(EmbedArgs a) {
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    __shared__ float s_logit[kMaxExperts];
+    __shared__ float s_gate[kMaxExperts];
+    __shared__ int s_chosen[kMaxExperts];
+
+    // router logits: expert e = wave, wave + 16, ...; a lane covers 8 consecutive inputs per step
+    for (int e = wave; e < a.n_expert; e += kEmbedWaves) {
+        float acc = 0.f;
+        for (int i = lane * 8; i < a.d_in; i += kWave * 8) {
+            float hv[8], wv[8];
+            load8<kBf16>(a.h, (int64_t)b * a.d_in + i, hv);
+            load8<kBf16>(a.router_w, (int64_t)e * a.d_in + i, wv);
+#pragma unroll
+            for (int x = 0; x < 8; ++x) acc = fmaf(hv[x], wv[x], acc);
+        }
+        acc = wave_sum(acc);
+        if (lane == 0) s_logit[e] = acc;
+    }
+    __syncthreads();
+
+    // softmax over the experts and the K best of them (lowest index on ties), best first
+    if (wave == 0) {
+        const bool live = lane < a.n_expert;
+        const float z = live ? s_logit[lane] : -INFINITY;
+        const float m = wave_max(z);
+        const float ex = live ? expf(z - m) : 0.f;
+        const float g = ex / wave_sum(ex);
+        if (live) {
+            s_gate[lane] = g;
+            if (a.gates) a.gates[(int64_t)b * a.n_expert + lane] = g;
+        }
+        float cand = live ? g : -1.f;
+        for (int r = 0; r < a.k_expert; ++r) {
+            float bv = cand;
+            int bi = lane;
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const float ov = __shfl_xor(bv, o, kWave);
+                const int oi = __shfl_xor(bi, o, kWave);
+                if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+            }
+            if (lane == 0) {
+                s_chosen[r] = bi;
+                if (a.chosen) a.chosen[(int64_t)b * a.k_expert + r] = bi;
+            }
+            if (lane == bi) cand = -1.f;
+        }
+    }
+    __syncthreads();
+
+    // out = sum over the chosen experts of gate * embedding
+    for (int c = tid * 8; c < a.d_out; c += kEmbedThreads * 8) {
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int r = 0; r < a.k_expert; ++r) {
+            const int e = s_chosen[r];
+            const float g = s_gate[e];
+            float ev[8];
+            load8<kBf16>(a.expert_emb, (int64_t)e * a.d_out + c, ev);
+#pragma unroll
+            for (int x = 0; x < 8; ++x) acc[x] = fmaf(g, ev[x], acc[x]);
+        }
+        if (kBf16) {
+            typedef __bf16 bf16x8 __attribute__((ext_vector_type(8), may_alias));
+            bf16x8 o;
+#pragma unroll
+            for (int x = 0; x < 8; ++x) o[x] = (__bf16)acc[x];
+            *reinterpret_cast<bf16x8*>(static_cast<unsigned short*>(a.out) + (int64_t)b * a.d_out + c) = o;
+        } else {
+            float* o = static_cast<float*>(a.out) + (int64_t)b * a.d_out + c;
+            *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+            *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        }
+    }
+}
+
+}  // namespace
+
+hipError_t launch_commit(const CommitArgs& a, hipStream_t s) {
+    commit_kernel<<<dim3(a.n_layers, a.B, 2), kCommitThreads, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+hipError_t launch_embed(const EmbedArgs& a, hipStream_t s) {
+    if (a.bf16) embed_kernel<true><<<a.B, kEmbedThreads, 0, s>>>(a);
+    else embed_kernel<false><<<a.B, kEmbedThreads, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace tv

@@ -109,6 +109,40 @@ struct AcceptArgs {
 
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t s);
 
+// ---- commit of the accepted path, contemplate embedding ---------------------------------------------
+struct CommitArgs {
+    void* k;
+    void* v;
+    const int64_t* kv_offset;
+    const int32_t* prefix_len;
+    const int32_t* path;
+    const int32_t* n_accepted;
+    const int32_t* node_row;
+    const void* hidden;
+    const int32_t* con_row;
+    const int32_t* selected_con;
+    void* f_out;
+    int32_t* new_prefix_len;
+    int32_t* status;
+    int B, T, M, Hkv, D, n_layers, C, d_model;
+    int elem;                          // bytes per element
+    int64_t layer_stride, tok_stride, head_stride;   // elements
+};
+
+struct EmbedArgs {
+    const void* h;
+    const void* router_w;
+    const void* expert_emb;
+    void* out;
+    float* gates;
+    int32_t* chosen;
+    int B, d_in, d_out, n_expert, k_expert;
+    bool bf16;
+};
+
+hipError_t launch_commit(const CommitArgs& a, hipStream_t s);
+hipError_t launch_embed(const EmbedArgs& a, hipStream_t s);
+
 // ---- small device helpers -------------------------------------------------------------------------
 __device__ __forceinline__ float wave_max(float x) {
 #pragma unroll
