@@ -179,6 +179,43 @@ def main() -> int:
     ms_greedy = timed(accept_greedy, args.steps * 4, args.warmup)
     us_layer = ms_attn * 1e3 / L
 
+    # ---- the steps around the pass: commit of the accepted path (all layers, one call), contemplate embedding -----
+    kp_all, vp_all = main_attn["keep"][0], main_attn["keep"][1]
+    cm_desc = tv.make_commit_desc(dtype=tv.TV_DTYPE_BF16, B=1, T=acc.T, M=M, Hkv=w.Hkv, D=w.D, n_layers=L,
+                                  kv_layer_stride=kp_all.stride(0), C=acc.C, d_model=4096)
+    hidden = torch.randn((1, M, 4096), device="cuda").to(torch.bfloat16)
+    con_row = (acc.T + torch.arange(acc.C, device="cuda", dtype=torch.int32)).reshape(1, -1).contiguous()
+    f_out = torch.empty((1, 4096), device="cuda", dtype=torch.bfloat16)
+    new_len = torch.zeros(1, **i32)
+    cm_status = torch.zeros(1, **i32)
+    plen_d = main_attn["keep"][4]
+    kv_off_d = main_attn["keep"][3]
+
+    def commit():
+        tv.tree_commit(cm_desc, kp_all, vp_all, kv_off_d, plen_d, path, o_n, None, hidden, con_row, o_con, f_out,
+                       new_len, cm_status)
+
+    em_desc = tv.make_embed_desc(dtype=tv.TV_DTYPE_BF16, B=1, d_in=3 * 4096, d_out=4096, n_expert=64, k_expert=4)
+    em_h = torch.randn((1, 3 * 4096), device="cuda").to(torch.bfloat16)
+    em_w = (torch.randn((64, 3 * 4096), device="cuda") * 0.02).to(torch.bfloat16)
+    em_e = torch.randn((64, 4096), device="cuda").to(torch.bfloat16)
+    em_out = torch.empty((1, 4096), device="cuda", dtype=torch.bfloat16)
+
+    def embed():
+        tv.contemplate_embed(em_desc, em_h, em_w, em_e, em_out, None, None)
+
+    with torch.cuda.stream(stream):
+        accept()                          # path / n_accepted / selected_con for the commit
+    torch.cuda.synchronize()
+    ms_commit = timed(commit, args.steps * 4, args.warmup)      # (after the first call the moves are repeats)
+    ms_embed = timed(embed, args.steps * 4, args.warmup)
+    n_moved = int(o_n[0]) + 1
+    around = {"tree_commit_us": round(ms_commit * 1e3, 2), "tree_commit_layers": L,
+              "tree_commit_bytes_moved": 2 * 2 * L * n_moved * w.Hkv * w.D * 2,
+              "contemplate_embed_us": round(ms_embed * 1e3, 2),
+              "contemplate_embed_bytes_read": 2 * (64 * 3 * 4096 + 3 * 4096 + 4 * 4096),
+              "contemplate_embed_shape": "d_in 12288, d_out 4096, 64 experts, top 4, bf16"}
+
     # ---- the paper's own layout (one contemplate row per node, 120 rows, 16 soft-prompt slots): MFMA-bound --------
     paper = None
     if not args.no_paper_layout:
@@ -255,6 +292,7 @@ def main() -> int:
                                     "temp0_greedy": round(1e3 / ms_greedy, 1)},
         "tree_accept": accept_info,
         "contemplate_row_per_node": paper,
+        "around_the_pass": around,
         "verify_steps_per_s": round(1e3 / ms_step, 2),
         "attention_tb_per_s": round(achieved / 1e3, 3),
         "roofline": roofline,
