@@ -163,6 +163,11 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
     const unsigned ring_addr = lds_address(ring);
     const int l_row = lane >> 4, l_seg = lane & 15;    // a direct-to-LDS load lands lane l at row l/16, segment l%16
 
+    // the two per-sequence scalars everything below waits for: requested first, so that their latency runs
+    // under the Q requests (the assembly statements of those keep later loads from moving up past them)
+    const int P = a.prefix_len[b];
+    const int64_t kv_first_row = a.kv_offset[b];
+
     // ---- Q for this wave's rows: HBM -> LDS (the upper half of the stream's ring is free at this point) -
     // Each 32-row query block is laid out like a K tile, with the same segment swizzle.
     const int q_off = (S / 2) * kStageBytes + wsub * (NQB * kTileBytes);
@@ -170,24 +175,18 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
         const unsigned q_stage = __builtin_amdgcn_readfirstlane(ring_addr + q_off);
         const unsigned long long q_sbase =
             scalar_base(static_cast<const unsigned char*>(a.q) + (int64_t)b * M * a.Hq * (kD * 2));
-        int r = row0 + l_row;                         // packed row of instruction 0; +4 per instruction
-        int hl = (int)(((float)r + 0.5f) * a.inv_M);  // r / M (exact for these sizes)
-        int i = r - hl * M;                           // (head in group, tree row) of packed row r
 #pragma unroll
         for (int j = 0; j < 8 * NQB; ++j) {
             const int row = 4 * (j & 7) + l_row;      // row inside the query block: selects the swizzle
-            const bool over = r >= n_rows;            // padding rows re-read the last packed row
-            const int ii = over ? M - 1 : i, hh = over ? G - 1 : hl;
-            const unsigned off = (unsigned)((ii * a.Hq + g * G + hh) * (kD * 2) + ((l_seg ^ (row & 15)) * 16));
+            const int r = min(row0 + 4 * j + l_row, n_rows - 1);      // padding rows re-read the last packed row
+            const int hl = (int)(((float)r + 0.5f) * a.inv_M);         // r / M (exact for these sizes)
+            const int i = r - hl * M;                                  // (head in group, tree row) of packed row r
+            const unsigned off = (unsigned)((i * a.Hq + g * G + hl) * (kD * 2) + ((l_seg ^ (row & 15)) * 16));
             dma16(q_stage + j * 1024, q_sbase, off);
-            r += 4;
-            i += 4;
-            while (i >= M) { i -= M; ++hl; }
         }
     }
 
     // ---- key range, first K/V tiles (they depend on the prefix length only) ---------------------------
-    const int P = a.prefix_len[b];
     const bool bad_prefix = (P < a.soft_len || P < 0 || P > a.max_prefix_len);
     const int Lk = bad_prefix ? M : P + M;
     const int n_tiles = (Lk + kTK - 1) / kTK;
@@ -202,7 +201,7 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
     // the longest stream of the workgroup is its first one
     const int n_iter = bad_prefix ? 0 : tiles_per_slot + (slot0 < extra ? 1 : 0);
 
-    const int64_t seq_base = (a.kv_offset[b] * a.tok_stride + (int64_t)g * a.head_stride) * 2;
+    const int64_t seq_base = (kv_first_row * a.tok_stride + (int64_t)g * a.head_stride) * 2;
     const unsigned char* kbase = static_cast<const unsigned char*>(a.k) + seq_base;
     const unsigned char* vbase = static_cast<const unsigned char*>(a.v) + seq_base;
     const unsigned tok_bytes = (unsigned)(a.tok_stride * 2);
@@ -504,13 +503,19 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
                 park(va_out[ks * 4 + dt]);
             }
     };
-    for (int it = 0; it < n_iter; it += 2) {
-        tile_round(it, va_a, pb_a, va_b, pb_b);
-        if (it + 1 < n_iter) tile_round(it + 1, va_b, pb_b, va_a, pb_a);
+    if (NQB == 1) {
+        for (int it = 0; it < n_iter; it += 2) {
+            tile_round(it, va_a, pb_a, va_b, pb_b);
+            if (it + 1 < n_iter) tile_round(it + 1, va_b, pb_b, va_a, pb_a);
+        }
+        // the last tile's product: its operands are in set b after an odd number of tiles, else in set a
+        if (n_my & 1) pv_mfma(va_b, pb_b);
+        else pv_mfma(va_a, pb_a);
+    } else {
+        // 64-row waves have no registers to spare for a second set: one set, consumed before it is refilled
+        for (int it = 0; it < n_iter; ++it) tile_round(it, va_a, pb_a, va_a, pb_a);
+        pv_mfma(va_a, pb_a);
     }
-    // the last tile's product: its operands are in set b after an odd number of tiles, else in set a
-    if (n_my & 1) pv_mfma(va_b, pb_b);
-    else pv_mfma(va_a, pb_a);
 
     // ---- merge the streams through LDS -------------------------------------------------------------------
     // Merge buffer: [wave][its rows][32 float4]; float4 column c of a wave's row r is stored at column c ^ (r & 31).
