@@ -93,9 +93,10 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a
     const int b = blockIdx.z;
     // the kernels that follow on the stream count arriving workgroups from zero
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        if (blockIdx.y == 0) a.arrivals[b] = 0u;
         if (a.n_mat == 2 && blockIdx.y == 0 && b == 0) *a.chain_fail = 0;
     }
+    if (blockIdx.x == 0 && blockIdx.y == 0)                  // the draw kernel's slice slots: "not published yet"
+        for (int i = threadIdx.x; i < kMaxSlices; i += kStatThreads) a.slice_bits[(int64_t)b * kMaxSlices + i] = 3ull;
     if (a.n_mat == 2 && mat == 0 && blockIdx.x == 0) {       // this node's share slots: a tag no early round expects
         unsigned long long* parts = a.chain_parts + ((int64_t)b * a.T + row) * 2 * a.chain_slices;
         for (int i = threadIdx.x; i < 2 * a.chain_slices; i += kStatThreads) parts[i] = 3ull;
@@ -462,7 +463,7 @@ struct WalkShared {
     double wave_tot[kDrawWaves];
     double base;                  // mass of the final law in the slices before the chosen one
     int flag, cur, n_steps, rejected_any, len, tok_out;
-    int slice_last, is_last, s_star, hit, seg_last;
+    int slice_last, s_star, hit, fallback;
 };
 
 // One lane's contiguous run of vocabulary entries [v0, v0 + 4*quads).  kFind = false: the mass of the
@@ -507,15 +508,13 @@ __device__ __forceinline__ void segment_scan(const WalkShared& sh, const float* 
     if (kFind) *found = fnd;
 }
 
+// One sequence, one vocabulary slice.
 template <int kRule>
-__global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a) {
-    const int sl = blockIdx.x;
-    const int b = blockIdx.y;
+__device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared& sh, int b, int sl) {
     const int T = a.T, V = a.V;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     constexpr bool kGreedy = (kRule == TV_RULE_GREEDY);
     constexpr bool kDraft = (kRule == TV_RULE_DRAFT_WOR || kRule == TV_RULE_DRAFT_WR);
-    __shared__ WalkShared sh;
     const float it = kGreedy ? 0.f : kLog2e / a.temperature;
 
     for (int i = tid; i < T; i += kDrawThreads) {
@@ -645,9 +644,7 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a)
         sh.rejected_any = (nrej > 0);
         sh.tok_out = -1;
         sh.slice_last = -1;
-        sh.seg_last = -1;
         sh.hit = kDrawThreads;
-        sh.is_last = 1;
     }
     __syncthreads();
     const int cur = sh.cur;
@@ -661,41 +658,45 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a)
         const bool vec_ok = aligned16(prow) && aligned16(qrow);
         const double u = (double)sh.unif[T + cur];
         const int quads = a.slice_len / (4 * kDrawThreads);     // quads of entries per lane, contiguous
-        double* ssum = a.slice_sum + (int64_t)b * kMaxSlices;
-        int32_t* slast = a.slice_last + (int64_t)b * kMaxSlices;
+        unsigned long long* slots = a.slice_bits + (int64_t)b * kMaxSlices;
 
-        // (a) mass of the law inside this workgroup's slice
+        // (a) mass of the law inside this workgroup's slice, published with tag 0 in the two lowest mantissa bits
+        //     (the statistics kernel left tag 3 in every slot)
         double mass;
         int last;
-        segment_scan<kRule, false>(sh, prow, qrow, vec_ok, cur, sl * a.slice_len + tid * 4 * quads, quads, V, it, u,
-                                   &mass, &last, nullptr);
+        const int v0 = sl * a.slice_len + tid * 4 * quads;
+        segment_scan<kRule, false>(sh, prow, qrow, vec_ok, cur, v0, quads, V, it, u, &mass, &last, nullptr);
         if (last >= 0) atomicMax(&sh.slice_last, last);
         const double tot = block_sum<kDrawWaves>(mass, sh.red);
-        if (tid == 0) {
-            agent_store(ssum + sl, tot);
-            __hip_atomic_store(slast + sl, sh.slice_last, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            stores_done();                                      // publish the slice, then count it
-            const unsigned prev = atomicAdd(a.arrivals + b, 1u);
-            sh.is_last = (prev == (unsigned)a.n_slices - 1u);
-        }
-        __syncthreads();
-        if (!sh.is_last) return;
+        if (tid == 0)
+            __hip_atomic_store(slots + sl, (unsigned long long)__double_as_longlong(tot) & ~3ull, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
 
-        // (b) the slice in which the running sum crosses u: wave 0, consecutive slices per lane
+        // (b) every workgroup of the sequence reads every slice's mass (they are all resident: the host sizes
+        //     the launch for that) and finds the slice in which the running sum crosses u; if rounding leaves the
+        //     total at or below u, the last slice that carries mass takes over
         if (wave == 0) {
             constexpr int kPer = kMaxSlices / kWave;
             double sm[kPer], mine = 0.0;
-            int lst = -1;
+            int fail = 0;
+            unsigned polls = 0;
 #pragma unroll
             for (int k = 0; k < kPer; ++k) {
                 const int s = lane * kPer + k;
                 sm[k] = 0.0;
                 if (s < a.n_slices) {
-                    sm[k] = agent_load(ssum + s);
-                    lst = max(lst, __hip_atomic_load(slast + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+                    unsigned long long bits;
+                    for (;;) {
+                        bits = __hip_atomic_load(slots + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if ((bits & 3ull) == 0ull) break;
+                        __builtin_amdgcn_s_sleep(1);
+                        if (++polls > a.wait_limit) { fail = 1; break; }
+                    }
+                    sm[k] = __longlong_as_double((long long)(bits & ~3ull));
                 }
                 mine += sm[k];
             }
+            fail = __any(fail);
             double inc = mine;
 #pragma unroll
             for (int o = 1; o < kWave; o <<= 1) {
@@ -703,38 +704,51 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a)
                 if (lane >= o) inc += t;
             }
             double run = inc - mine, base_c = 0.0;
-            int cand = -1;
+            int cand = -1, has_mass = -1;
 #pragma unroll
             for (int k = 0; k < kPer; ++k) {
                 if (cand < 0 && lane * kPer + k < a.n_slices && run + sm[k] > u) { cand = lane * kPer + k; base_c = run; }
+                if (sm[k] > 0.0) has_mass = lane * kPer + k;
                 run += sm[k];
             }
             const unsigned long long hit = __ballot(cand >= 0);
-            int s_star = -1;
+            int s_star;
             double base = 0.0;
             if (hit) {
                 const int first = __ffsll((long long)hit) - 1;
                 s_star = __shfl(cand, first, kWave);
                 base = __shfl(base_c, first, kWave);
             } else {
-                // rounding left the total at or below u: the last entry that carries mass
 #pragma unroll
-                for (int o = 32; o > 0; o >>= 1) lst = max(lst, __shfl_xor(lst, o, kWave));
+                for (int o = 32; o > 0; o >>= 1) has_mass = max(has_mass, __shfl_xor(has_mass, o, kWave));
+                s_star = has_mass;
             }
             if (lane == 0) {
-                if (s_star < 0) sh.tok_out = lst;
-                sh.s_star = s_star;
+                sh.s_star = fail ? -2 : s_star;
+                sh.fallback = hit ? 0 : 1;
                 sh.base = base;
             }
         }
         __syncthreads();
         const int s_star = sh.s_star;
-        if (s_star >= 0) {
-            // (c) rescan that slice: per-lane masses, a prefix sum over the lanes in vocabulary order,
-            //     then the lane that holds the crossing walks its own entries one by one
-            const int v0 = s_star * a.slice_len + tid * 4 * quads;
-            segment_scan<kRule, false>(sh, prow, qrow, vec_ok, cur, v0, quads, V, it, u, &mass, &last, nullptr);
-            if (last >= 0) atomicMax(&sh.seg_last, last);
+        if (s_star == -2) {                       // the bounded wait ran out: report instead of hanging
+            if (sl == 0) {
+                for (int i = tid; i < T; i += kDrawThreads) path[i] = -1;
+                if (tid == 0) {
+                    a.status[b] = TV_STATUS_INTERNAL;
+                    a.n_accepted[b] = -1;
+                    a.final_token[b] = -1;
+                    a.final_kind[b] = -1;
+                    a.last_node[b] = -1;
+                    if (a.selected_con) a.selected_con[b] = -1;
+                }
+            }
+            return;
+        }
+        if (s_star != sl && !(s_star < 0 && sl == 0)) return;        // another slice finishes (slice 0 if no mass at all)
+        if (s_star >= 0 && !sh.fallback) {
+            // (c) the crossing is in this slice: a prefix sum over the lanes' masses in vocabulary order, then the
+            //     lane that holds the crossing walks its own entries one by one
             double inc = mass;
 #pragma unroll
             for (int o = 1; o < kWave; o <<= 1) {
@@ -750,13 +764,15 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a)
             __syncthreads();
             if (sh.hit == kDrawThreads) {
                 // the slice sums put the crossing here, the in-order sums round just below it
-                if (tid == 0) sh.tok_out = sh.seg_last;
+                if (tid == 0) sh.tok_out = sh.slice_last;
             } else if (tid == sh.hit) {
                 double run = excl;
                 int found = -1, seg_last = -1;
                 segment_scan<kRule, true>(sh, prow, qrow, vec_ok, cur, v0, quads, V, it, u, &run, &seg_last, &found);
                 sh.tok_out = (found >= 0) ? found : seg_last;
             }
+        } else if (tid == 0) {
+            sh.tok_out = sh.slice_last;           // the last entry that carries mass (-1 if there is none)
         }
     }
     __syncthreads();
@@ -774,6 +790,19 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a)
                     if (a.con_anchor[(int64_t)b * a.C + c] == cur) sel = c;
             a.selected_con[b] = sel;
         }
+    }
+}
+
+// The launch holds a whole number of groups of n_slices workgroups, all resident together (the workgroups of a
+// group wait for each other's slice masses); a group takes sequences one after the other.
+template <int kRule>
+__global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a) {
+    __shared__ WalkShared sh;
+    const int n_groups = gridDim.x / a.n_slices;
+    const int group = blockIdx.x / a.n_slices, sl = blockIdx.x % a.n_slices;
+    for (int b = group; b < a.B; b += n_groups) {
+        __syncthreads();
+        accept_walk_one<kRule>(a, sh, b, sl);
     }
 }
 
@@ -805,16 +834,14 @@ int plan_accept(const tv_accept_desc& d, AcceptPlan* plan) {
     p.stats_bytes = up((size_t)rows * p.splits * sizeof(RowStat));
     p.chain_bytes = up((size_t)d.B * d.T * sizeof(double));
     p.bits_bytes = up((size_t)d.B * d.T * sizeof(int32_t));
-    p.slice_sum_bytes = up((size_t)d.B * kMaxSlices * sizeof(double));
-    p.slice_last_bytes = up((size_t)d.B * kMaxSlices * sizeof(int32_t));
-    p.arrivals_bytes = up((size_t)d.B * sizeof(unsigned));
+    p.slice_bytes = up((size_t)d.B * kMaxSlices * sizeof(unsigned long long));
     // the sibling chains: one group of workgroups per node, one slice of kChainThreads * kChainPer entries each
     constexpr int kChainSlice = kChainThreads * kChainPer;
     p.chain_slices = (d.V + kChainSlice - 1) / kChainSlice;
     p.chain_parts_bytes = (p.n_mat == 2) ? up((size_t)d.B * d.T * 2 * p.chain_slices * sizeof(double)) : 0;
     p.chain_ctl_bytes = (p.n_mat == 2) ? up(sizeof(int32_t)) : 0;
-    p.total_bytes = p.stats_bytes + p.chain_bytes + p.bits_bytes + p.slice_sum_bytes + p.slice_last_bytes +
-                    p.arrivals_bytes + p.chain_parts_bytes + p.chain_ctl_bytes;
+    p.total_bytes = p.stats_bytes + p.chain_bytes + p.bits_bytes + p.slice_bytes + p.chain_parts_bytes +
+                    p.chain_ctl_bytes;
     *plan = p;
     return TV_OK;
 }
@@ -836,6 +863,27 @@ static int chain_resident_workgroups(int rule) {
     return c;
 }
 
+// Workgroups of the walk kernel that are resident together on the current device (0 if unknown).
+static int walk_resident_workgroups(int rule) {
+    static int cache[4][64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64 || rule < 0 || rule > 3) return 0;
+    int& c = cache[rule][dev];
+    if (c == 0) {
+        int per_cu = 0, cus = 0;
+        hipError_t e1;
+        switch (rule) {
+            case TV_RULE_GREEDY: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_GREEDY>, kDrawThreads, 0); break;
+            case TV_RULE_DETERMINISTIC: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_DETERMINISTIC>, kDrawThreads, 0); break;
+            case TV_RULE_DRAFT_WOR: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_DRAFT_WOR>, kDrawThreads, 0); break;
+            default: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_DRAFT_WR>, kDrawThreads, 0); break;
+        }
+        const hipError_t e2 = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e1 == hipSuccess && e2 == hipSuccess && per_cu > 0 && cus > 0) c = per_cu * cus;
+    }
+    return c;
+}
+
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t s) {
     const dim3 gs(a.splits, a.T * a.n_mat, a.B);
     if (a.rule == TV_RULE_GREEDY) accept_stats_kernel<true><<<gs, kStatThreads, 0, s>>>(a);
@@ -850,7 +898,11 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t s) {
         if (a.rule == TV_RULE_DRAFT_WOR) accept_chain_kernel<TV_RULE_DRAFT_WOR><<<gc, kChainThreads, 0, s>>>(a);
         else accept_chain_kernel<TV_RULE_DRAFT_WR><<<gc, kChainThreads, 0, s>>>(a);
     }
-    const dim3 gw(a.n_slices, a.B);
+    // whole groups of n_slices workgroups, no more than are resident at once
+    int walk_groups = walk_resident_workgroups(a.rule) / a.n_slices;
+    if (walk_groups < 1) return hipErrorLaunchOutOfResources;
+    if (walk_groups > a.B) walk_groups = a.B;
+    const dim3 gw((unsigned)walk_groups * (unsigned)a.n_slices);
     switch (a.rule) {
         case TV_RULE_GREEDY: accept_walk_kernel<TV_RULE_GREEDY><<<gw, kDrawThreads, 0, s>>>(a); break;
         case TV_RULE_DETERMINISTIC: accept_walk_kernel<TV_RULE_DETERMINISTIC><<<gw, kDrawThreads, 0, s>>>(a); break;

@@ -237,10 +237,8 @@ int tree_accept(const tv_accept_desc* desc, const float* target_logits, const fl
     a.chain_z = reinterpret_cast<double*>(w + p.stats_bytes);
     a.accept_bit = reinterpret_cast<int32_t*>(w + p.stats_bytes + p.chain_bytes);
     unsigned char* w2 = w + p.stats_bytes + p.chain_bytes + p.bits_bytes;
-    a.slice_sum = reinterpret_cast<double*>(w2);
-    a.slice_last = reinterpret_cast<int32_t*>(w2 + p.slice_sum_bytes);
-    a.arrivals = reinterpret_cast<unsigned*>(w2 + p.slice_sum_bytes + p.slice_last_bytes);
-    unsigned char* w3 = w2 + p.slice_sum_bytes + p.slice_last_bytes + p.arrivals_bytes;
+    a.slice_bits = reinterpret_cast<unsigned long long*>(w2);
+    unsigned char* w3 = w2 + p.slice_bytes;
     a.chain_parts = reinterpret_cast<unsigned long long*>(w3);
     a.chain_fail = reinterpret_cast<int32_t*>(w3 + p.chain_parts_bytes);
     a.B = desc->B; a.T = desc->T; a.V = desc->V; a.C = con_anchor ? desc->C : 0; a.rule = desc->rule;

@@ -67,8 +67,7 @@ struct AcceptPlan {
     int n_slices;         // workgroups per sequence that share the final draw (<= kMaxSlices)
     int slice_len;        // vocabulary entries per slice (multiple of 4 * 256)
     int chain_slices;     // draft rules: workgroups per node in the sibling-chain kernel
-    size_t stats_bytes, chain_bytes, bits_bytes, slice_sum_bytes, slice_last_bytes, arrivals_bytes,
-           chain_parts_bytes, chain_ctl_bytes, total_bytes;
+    size_t stats_bytes, chain_bytes, bits_bytes, slice_bytes, chain_parts_bytes, chain_ctl_bytes, total_bytes;
 };
 
 constexpr int kMaxSlices = 128;      // a multiple of the wave size
@@ -92,9 +91,8 @@ struct AcceptArgs {
     RowStat* stats;       // [B][n_mat][T][splits]
     double*  chain_z;     // [B][T]: normaliser of the corrected law after rejecting child c
     int32_t* accept_bit;  // [B][T]
-    double*  slice_sum;   // [B][kMaxSlices]: mass of the final law inside one vocabulary slice
-    int32_t* slice_last;  // [B][kMaxSlices]: last entry of the slice that carries mass, or -1
-    unsigned* arrivals;   // [B]: workgroups of the draw kernel that have published their slice
+    unsigned long long* slice_bits;   // [B][kMaxSlices]: mass of the final law inside one vocabulary slice (fp64
+                             // bits; the two lowest are a tag: 0 = published, 3 = not yet)
     unsigned long long* chain_parts;  // [B][T][2][chain_slices]: shares of a chain normaliser (fp64 bits, the two
                              // lowest carrying a round tag), two buffers per node
     int32_t* chain_fail;     // [1]: set when a bounded wait ran out
@@ -104,7 +102,7 @@ struct AcceptArgs {
     int splits, split_len, n_mat;
     int n_slices, slice_len;
     int chain_slices;
-    unsigned wait_limit;     // polls before a workgroup of the chain kernel gives up on its group
+    unsigned wait_limit;     // polls before a workgroup gives up waiting for the others of its group
 };
 
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t s);
