@@ -14,11 +14,11 @@
 //                            rejected), so every parent is processed independently: one workgroup per
 //                            parent walks its children in order and needs one vocabulary-wide
 //                            reduction (the corrected law's normaliser) per child.
-//   3. accept_walk_kernel    a few workgroups per sequence.  Each one repeats the (cheap, LDS-only)
+//   3. accept_walk_kernel    a group of workgroups per sequence.  Each one repeats the (cheap, LDS-only)
 //                            walk from the root, then sums the final law over its own slice of the
-//                            vocabulary; the workgroup that publishes its slice last finds the slice
-//                            in which the running sum crosses the uniform, rescans that slice in
-//                            vocabulary order and writes the results.
+//                            vocabulary and publishes that mass; every workgroup reads all the masses,
+//                            and the one whose slice holds the crossing of the uniform finishes the
+//                            inverse-CDF search inside its slice and writes the results.
 #include "tv_internal.hpp"
 
 namespace tv {
