@@ -200,9 +200,10 @@ def main() -> int:
     em_w = (torch.randn((64, 3 * 4096), device="cuda") * 0.02).to(torch.bfloat16)
     em_e = torch.randn((64, 4096), device="cuda").to(torch.bfloat16)
     em_out = torch.empty((1, 4096), device="cuda", dtype=torch.bfloat16)
+    em_ws = torch.empty(tv.tv_embed_workspace_bytes(em_desc), device="cuda", dtype=torch.uint8)
 
     def embed():
-        tv.contemplate_embed(em_desc, em_h, em_w, em_e, em_out, None, None)
+        tv.contemplate_embed(em_desc, em_h, em_w, em_e, em_out, None, None, em_ws)
 
     with torch.cuda.stream(stream):
         accept()                          # path / n_accepted / selected_con for the commit

@@ -265,8 +265,11 @@ typedef struct tv_embed_desc {
     int32_t  reserved;         /* 0 */
 } tv_embed_desc;
 
-/* Enqueues the work on hip_stream and returns without synchronising; no workspace.
- * Returns TV_OK, TV_ERR_INVALID_ARG, TV_ERR_LAUNCH. */
+/* host: writes the workspace size (bytes) contemplate_embed needs for *desc. */
+int tv_embed_workspace_bytes(const tv_embed_desc* desc, size_t* out_bytes);
+
+/* Enqueues the work on hip_stream and returns without synchronising.
+ * Returns TV_OK, TV_ERR_INVALID_ARG, TV_ERR_WORKSPACE, TV_ERR_LAUNCH. */
 int contemplate_embed(
     const tv_embed_desc* desc,
     const void*    h,               /* device [B, d_in] */
@@ -275,6 +278,8 @@ int contemplate_embed(
     void*          out,             /* device [B, d_out] */
     float*         gates,           /* device [B, n_expert] or NULL: the softmax scores g */
     int32_t*       chosen,          /* device [B, k_expert] or NULL: the selected experts, best first */
+    void*          workspace,       /* device, 16-byte aligned, >= tv_embed_workspace_bytes() */
+    size_t         workspace_bytes,
     void*          hip_stream);
 
 /* host: checks a parent/kind pair and writes the ancestor-closure bit mask the attention

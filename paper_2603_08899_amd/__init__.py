@@ -28,7 +28,7 @@ TV_FINAL_BONUS, TV_FINAL_RESIDUAL = 0, 1
 EXPORTED_SYMBOLS = (
     "tv_attention_workspace_bytes", "tree_verify_attention",
     "tv_accept_workspace_bytes", "tree_accept",
-    "tree_commit", "contemplate_embed",
+    "tree_commit", "contemplate_embed", "tv_embed_workspace_bytes",
     "tv_build_mask_host", "tv_error_string", "tv_version", "tv_set_wait_limit",
 )
 
@@ -108,7 +108,9 @@ def lib() -> ctypes.CDLL:
         l.tree_commit.restype = ctypes.c_int
         l.tree_commit.argtypes = [ctypes.POINTER(tv_commit_desc)] + [vp] * 14
         l.contemplate_embed.restype = ctypes.c_int
-        l.contemplate_embed.argtypes = [ctypes.POINTER(tv_embed_desc)] + [vp] * 7
+        l.contemplate_embed.argtypes = [ctypes.POINTER(tv_embed_desc)] + [vp] * 7 + [sz, vp]
+        l.tv_embed_workspace_bytes.restype = ctypes.c_int
+        l.tv_embed_workspace_bytes.argtypes = [ctypes.POINTER(tv_embed_desc), ctypes.POINTER(sz)]
         _lib = l
     return _lib
 
@@ -215,9 +217,19 @@ def make_embed_desc(*, dtype: int, B: int, d_in: int, d_out: int, n_expert: int,
     return tv_embed_desc(ctypes.sizeof(tv_embed_desc), dtype, B, d_in, d_out, n_expert, k_expert, 0)
 
 
-def contemplate_embed(desc: tv_embed_desc, h, router_w, expert_emb, out, gates, chosen, stream=None) -> None:
+def tv_embed_workspace_bytes(desc: tv_embed_desc) -> int:
+    n = ctypes.c_size_t(0)
+    rc = lib().tv_embed_workspace_bytes(ctypes.byref(desc), ctypes.byref(n))
+    if rc:
+        raise ConfuVerifyError(rc, "tv_embed_workspace_bytes")
+    return int(n.value)
+
+
+def contemplate_embed(desc: tv_embed_desc, h, router_w, expert_emb, out, gates, chosen, workspace, stream=None) -> None:
     """Mixture-of-experts embedding of contemplate / future tokens; see include/confu_verify.h."""
     rc = lib().contemplate_embed(ctypes.byref(desc), _ptr(h), _ptr(router_w), _ptr(expert_emb), _ptr(out),
-                                 _ptr(gates), _ptr(chosen), _stream_handle(stream))
+                                 _ptr(gates), _ptr(chosen), _ptr(workspace),
+                                 0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                 _stream_handle(stream))
     if rc:
         raise ConfuVerifyError(rc, "contemplate_embed")

@@ -286,17 +286,35 @@ int tree_commit(const tv_commit_desc* d, void* k_pool, void* v_pool, const int64
     return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;
 }
 
-int contemplate_embed(const tv_embed_desc* d, const void* h, const void* router_w, const void* expert_emb, void* out,
-                      float* gates, int32_t* chosen, void* hip_stream) {
+static int check_embed_desc(const tv_embed_desc* d) {
     if (!d || d->struct_size != sizeof(tv_embed_desc)) return TV_ERR_INVALID_ARG;
     if (d->dtype != TV_DTYPE_F32 && d->dtype != TV_DTYPE_BF16) return TV_ERR_INVALID_ARG;
-    if (d->B < 1 || d->d_in < 8 || d->d_in % 8 != 0 || d->d_out < 8 || d->d_out % 8 != 0) return TV_ERR_INVALID_ARG;
+    if (d->B < 1 || d->B > 65535 || d->d_in < 8 || d->d_in % 8 != 0 || d->d_out < 8 || d->d_out % 8 != 0)
+        return TV_ERR_INVALID_ARG;
     if (d->n_expert < 1 || d->n_expert > 64 || d->k_expert < 1 || d->k_expert > d->n_expert || d->reserved != 0)
         return TV_ERR_INVALID_ARG;
+    return TV_OK;
+}
+
+int tv_embed_workspace_bytes(const tv_embed_desc* desc, size_t* out_bytes) {
+    if (!out_bytes) return TV_ERR_INVALID_ARG;
+    const int rc = check_embed_desc(desc);
+    if (rc != TV_OK) return rc;
+    *out_bytes = up256((size_t)desc->B * desc->n_expert * sizeof(float));
+    return TV_OK;
+}
+
+int contemplate_embed(const tv_embed_desc* d, const void* h, const void* router_w, const void* expert_emb, void* out,
+                      float* gates, int32_t* chosen, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    const int rc = check_embed_desc(d);
+    if (rc != TV_OK) return rc;
+    if (!workspace || workspace_bytes < up256((size_t)d->B * d->n_expert * sizeof(float)) || ((uintptr_t)workspace & 15))
+        return TV_ERR_WORKSPACE;
     if (!h || !router_w || !expert_emb || !out) return TV_ERR_INVALID_ARG;
     if (((uintptr_t)h | (uintptr_t)router_w | (uintptr_t)expert_emb | (uintptr_t)out) & 15) return TV_ERR_INVALID_ARG;
     EmbedArgs a{};
     a.h = h; a.router_w = router_w; a.expert_emb = expert_emb; a.out = out; a.gates = gates; a.chosen = chosen;
+    a.logits = static_cast<float*>(workspace);
     a.B = d->B; a.d_in = d->d_in; a.d_out = d->d_out; a.n_expert = d->n_expert; a.k_expert = d->k_expert;
     a.bf16 = (d->dtype == TV_DTYPE_BF16);
     const hipError_t e = launch_embed(a, static_cast<hipStream_t>(hip_stream));

@@ -4,7 +4,8 @@
 //                      prediction of the last accepted token   (paper: Section 2, step 3; Section 3.1)
 //   contemplate_embed  mixture-of-experts embedding of a contemplate / future token: router logits,
 //                      softmax, top-K, weighted sum of expert embeddings   (paper: Section 3.2)
-// Both are small and bound by memory latency; plain ALUs, 16-byte accesses.
+// Both are small and bound by memory latency; plain ALUs, 16-byte accesses.  The embedding runs as two
+// kernels: one router logit per workgroup, then one block of output columns per workgroup.
 #include "tv_internal.hpp"
 
 namespace tv {
@@ -105,8 +106,9 @@ __global__ __launch_bounds__(kCommitThreads) void commit_kernel(CommitArgs a) {
 }
 
 // ---- contemplate_embed --------------------------------------------------------------------------------------
-constexpr int kEmbedThreads = 1024;
+constexpr int kEmbedThreads = 256;
 constexpr int kEmbedWaves = kEmbedThreads / kWave;
+constexpr int kEmbedCols = kEmbedThreads * 8;        // output columns per workgroup of the second kernel
 constexpr int kMaxExperts = 64;
 
 template <bool kBf16>
@@ -127,41 +129,49 @@ __device__ __forceinline__ void load8(const void* base, int64_t index, float* x)
     }
 }
 
-// One workgroup per token: the waves share the experts' router rows, wave 0 normalises and selects, all lanes
-// form the output.
+// Kernel 1, grid (n_expert, B): one router logit per workgroup (fp32 dot product, a lane covers 8 consecutive
+// inputs per step; lanes, then waves, are summed in a fixed order).
 template <bool kBf16>
-__global__ __launch_bounds__(kEmbedThreads) void embed_kernel(EmbedArgs a) {
-    const int b = blockIdx.x;
+__global__ __launch_bounds__(kEmbedThreads) void embed_logit_kernel(EmbedArgs a) {
+    const int e = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    __shared__ float s_logit[kMaxExperts];
+    __shared__ float s_part[kEmbedWaves];
+    float acc = 0.f;
+    for (int i = tid * 8; i < a.d_in; i += kEmbedThreads * 8) {
+        float hv[8], wv[8];
+        load8<kBf16>(a.h, (int64_t)b * a.d_in + i, hv);
+        load8<kBf16>(a.router_w, (int64_t)e * a.d_in + i, wv);
+#pragma unroll
+        for (int x = 0; x < 8; ++x) acc = fmaf(hv[x], wv[x], acc);
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) s_part[wave] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        float t = 0.f;
+        for (int w = 0; w < kEmbedWaves; ++w) t += s_part[w];
+        a.logits[(int64_t)b * a.n_expert + e] = t;
+    }
+}
+
+// Kernel 2, grid (column blocks, B): every workgroup normalises the (at most 64) logits and selects the K best
+// experts itself (lowest index on ties, best first), then forms its block of output columns.
+template <bool kBf16>
+__global__ __launch_bounds__(kEmbedThreads) void embed_mix_kernel(EmbedArgs a) {
+    const int b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     __shared__ float s_gate[kMaxExperts];
     __shared__ int s_chosen[kMaxExperts];
-
-    // router logits: expert e = wave, wave + 16, ...; a lane covers 8 consecutive inputs per step
-    for (int e = wave; e < a.n_expert; e += kEmbedWaves) {
-        float acc = 0.f;
-        for (int i = lane * 8; i < a.d_in; i += kWave * 8) {
-            float hv[8], wv[8];
-            load8<kBf16>(a.h, (int64_t)b * a.d_in + i, hv);
-            load8<kBf16>(a.router_w, (int64_t)e * a.d_in + i, wv);
-#pragma unroll
-            for (int x = 0; x < 8; ++x) acc = fmaf(hv[x], wv[x], acc);
-        }
-        acc = wave_sum(acc);
-        if (lane == 0) s_logit[e] = acc;
-    }
-    __syncthreads();
-
-    // softmax over the experts and the K best of them (lowest index on ties), best first
     if (wave == 0) {
         const bool live = lane < a.n_expert;
-        const float z = live ? s_logit[lane] : -INFINITY;
+        const float z = live ? a.logits[(int64_t)b * a.n_expert + lane] : -INFINITY;
         const float m = wave_max(z);
         const float ex = live ? expf(z - m) : 0.f;
         const float g = ex / wave_sum(ex);
+        const bool writer = (blockIdx.x == 0);
         if (live) {
             s_gate[lane] = g;
-            if (a.gates) a.gates[(int64_t)b * a.n_expert + lane] = g;
+            if (writer && a.gates) a.gates[(int64_t)b * a.n_expert + lane] = g;
         }
         float cand = live ? g : -1.f;
         for (int r = 0; r < a.k_expert; ++r) {
@@ -175,7 +185,7 @@ __global__ __launch_bounds__(kEmbedThreads) void embed_kernel(EmbedArgs a) {
             }
             if (lane == 0) {
                 s_chosen[r] = bi;
-                if (a.chosen) a.chosen[(int64_t)b * a.k_expert + r] = bi;
+                if (writer && a.chosen) a.chosen[(int64_t)b * a.k_expert + r] = bi;
             }
             if (lane == bi) cand = -1.f;
         }
@@ -183,27 +193,27 @@ __global__ __launch_bounds__(kEmbedThreads) void embed_kernel(EmbedArgs a) {
     __syncthreads();
 
     // out = sum over the chosen experts of gate * embedding
-    for (int c = tid * 8; c < a.d_out; c += kEmbedThreads * 8) {
-        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int r = 0; r < a.k_expert; ++r) {
-            const int e = s_chosen[r];
-            const float g = s_gate[e];
-            float ev[8];
-            load8<kBf16>(a.expert_emb, (int64_t)e * a.d_out + c, ev);
+    const int c = blockIdx.x * kEmbedCols + tid * 8;
+    if (c >= a.d_out) return;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int r = 0; r < a.k_expert; ++r) {
+        const int e = s_chosen[r];
+        const float g = s_gate[e];
+        float ev[8];
+        load8<kBf16>(a.expert_emb, (int64_t)e * a.d_out + c, ev);
 #pragma unroll
-            for (int x = 0; x < 8; ++x) acc[x] = fmaf(g, ev[x], acc[x]);
-        }
-        if (kBf16) {
-            typedef __bf16 bf16x8 __attribute__((ext_vector_type(8), may_alias));
-            bf16x8 o;
+        for (int x = 0; x < 8; ++x) acc[x] = fmaf(g, ev[x], acc[x]);
+    }
+    if (kBf16) {
+        typedef __bf16 bf16x8 __attribute__((ext_vector_type(8), may_alias));
+        bf16x8 o;
 #pragma unroll
-            for (int x = 0; x < 8; ++x) o[x] = (__bf16)acc[x];
-            *reinterpret_cast<bf16x8*>(static_cast<unsigned short*>(a.out) + (int64_t)b * a.d_out + c) = o;
-        } else {
-            float* o = static_cast<float*>(a.out) + (int64_t)b * a.d_out + c;
-            *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-            *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
-        }
+        for (int x = 0; x < 8; ++x) o[x] = (__bf16)acc[x];
+        *reinterpret_cast<bf16x8*>(static_cast<unsigned short*>(a.out) + (int64_t)b * a.d_out + c) = o;
+    } else {
+        float* o = static_cast<float*>(a.out) + (int64_t)b * a.d_out + c;
+        *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        *reinterpret_cast<float4*>(o + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
     }
 }
 
@@ -215,8 +225,14 @@ hipError_t launch_commit(const CommitArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_embed(const EmbedArgs& a, hipStream_t s) {
-    if (a.bf16) embed_kernel<true><<<a.B, kEmbedThreads, 0, s>>>(a);
-    else embed_kernel<false><<<a.B, kEmbedThreads, 0, s>>>(a);
+    const dim3 g1(a.n_expert, a.B), g2((a.d_out + kEmbedCols - 1) / kEmbedCols, a.B);
+    if (a.bf16) {
+        embed_logit_kernel<true><<<g1, kEmbedThreads, 0, s>>>(a);
+        embed_mix_kernel<true><<<g2, kEmbedThreads, 0, s>>>(a);
+    } else {
+        embed_logit_kernel<false><<<g1, kEmbedThreads, 0, s>>>(a);
+        embed_mix_kernel<false><<<g2, kEmbedThreads, 0, s>>>(a);
+    }
     return hipGetLastError();
 }
 

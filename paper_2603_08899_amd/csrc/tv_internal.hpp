@@ -134,6 +134,7 @@ struct EmbedArgs {
     void* out;
     float* gates;
     int32_t* chosen;
+    float* logits;                     // workspace [B][n_expert]
     int B, d_in, d_out, n_expert, k_expert;
     bool bf16;
 };

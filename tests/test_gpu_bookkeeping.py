@@ -164,7 +164,8 @@ def _run_embed(dtype, B, d_in, d_out, n_expert, k_expert, seed, tie=False):
     gates = torch.full((B, n_expert), -1.0, device="cuda", dtype=torch.float32)
     chosen = torch.full((B, k_expert), -1, device="cuda", dtype=torch.int32)
     desc = tv.make_embed_desc(dtype=dt, B=B, d_in=d_in, d_out=d_out, n_expert=n_expert, k_expert=k_expert)
-    tv.contemplate_embed(desc, hd, wd, ed, out, gates, chosen)
+    ws = torch.empty(tv.tv_embed_workspace_bytes(desc), device="cuda", dtype=torch.uint8)
+    tv.contemplate_embed(desc, hd, wd, ed, out, gates, chosen, ws)
     torch.cuda.synchronize()
     ref_out, ref_g, ref_ch = bk.contemplate_embed(h, w, e, k_expert)
     g = gates.cpu().numpy().astype(np.float64)
