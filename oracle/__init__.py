@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "confu_oracle.c")
 _LIB = os.path.join(_HERE, "libconfu_oracle.so")
 
-RULE_GREEDY, RULE_DETERMINISTIC, RULE_DRAFT_WOR, RULE_DRAFT_WR = 0, 1, 2, 3
+RULE_GREEDY, RULE_DETERMINISTIC, RULE_DRAFT_WOR, RULE_DRAFT_WR, RULE_SAMPLE_MATCH = 0, 1, 2, 3, 4
 FINAL_BONUS, FINAL_RESIDUAL = 0, 1
 KIND_NODE, KIND_CONTEMPLATE = 0, 1
 

@@ -18,7 +18,9 @@
  *    replaced by a token from the target's corrected distribution, and the output law
  *    equals the target model's (Section 2, steps 3-4; Section 5).  The rule is the
  *    speculative-sampling rule of the literature the paper cites there, generalised
- *    to sibling lists; temperature 0 is greedy matching (Section 4).
+ *    to sibling lists; temperature 0 is greedy matching (Section 4).  RULE_SAMPLE_MATCH
+ *    is the literal reading of step 3 instead: the target's token is sampled at each node
+ *    and a draft child is accepted iff it proposed exactly that token.
  *
  * Every pin of these functions lives in tests/ (closed forms, textbook special
  * cases, brute force, exact enumeration of the output law).  No function here is
@@ -45,6 +47,7 @@
 #define RULE_DETERMINISTIC 1
 #define RULE_DRAFT_WOR 2
 #define RULE_DRAFT_WR 3
+#define RULE_SAMPLE_MATCH 4
 
 #define FINAL_BONUS 0
 #define FINAL_RESIDUAL 1
@@ -230,7 +233,7 @@ int oracle_tree_accept(int T, int V, int C, double temp, int rule,
     if (T < 1 || V < 1 || !target_logits || !token || !parent || !path || !n_accepted ||
         !final_token || !final_kind || !last_node)
         return ORACLE_BAD_ARG;
-    if (rule < RULE_GREEDY || rule > RULE_DRAFT_WR) return ORACLE_BAD_ARG;
+    if (rule < RULE_GREEDY || rule > RULE_SAMPLE_MATCH) return ORACLE_BAD_ARG;
     if (rule != RULE_GREEDY && (!(temp > 0.0) || !uniforms)) return ORACLE_BAD_ARG;
     const int use_draft = (rule == RULE_DRAFT_WOR || rule == RULE_DRAFT_WR);
     if (use_draft && !draft_logits) return ORACLE_BAD_ARG;
@@ -248,10 +251,20 @@ int oracle_tree_accept(int T, int V, int C, double temp, int rule,
     int cur = 0, len = 0;
     path[0] = 0;
     int rejected_any = 0;
+    int sampled = -1;
     for (;;) {
         rejected_any = 0;
         int next = -1;
-        if (rule == RULE_GREEDY) {
+        if (rule == RULE_SAMPLE_MATCH) {
+            /* the literal reading of Section 2, step 3: draw the target's own token at this node
+             * (inverse CDF with the node's uniform); a child is accepted iff it proposed that token */
+            softmax_row(target_logits + (size_t)cur * V, V, temp, p);
+            sampled = inverse_cdf(p, V, (double)uniforms[T + cur]);
+            for (int c = cur + 1; c < T && next < 0; ++c) {
+                if (parent[c] != cur) continue;
+                if (token[c] == sampled) next = c; else rejected_any = 1;
+            }
+        } else if (rule == RULE_GREEDY) {
             const int best = argmax_row(target_logits + (size_t)cur * V, V);
             for (int c = cur + 1; c < T && next < 0; ++c) {
                 if (parent[c] != cur) continue;
@@ -305,6 +318,8 @@ int oracle_tree_accept(int T, int V, int C, double temp, int rule,
 
     if (rule == RULE_GREEDY) {
         *final_token = argmax_row(target_logits + (size_t)cur * V, V);
+    } else if (rule == RULE_SAMPLE_MATCH) {
+        *final_token = sampled;          /* the target's token at the stop node, matched by no child */
     } else {
         /* p now holds the law to draw from at the stop node: the target's own law if
          * nothing was rejected there, the last corrected law otherwise */

@@ -455,3 +455,50 @@ def test_bad_inputs_are_rejected(kw):
     with pytest.raises(oracle.OracleError):
         oracle.tree_accept(tl, None, args["token"], args["parent"], np.zeros(4, np.float32),
                            temperature=1.0, rule=DET)
+
+
+# ---- the literal sample-and-match reading (Section 2, step 3) ---------------------------------------------
+def test_sample_and_match_is_autoregressive_sampling_along_the_tree():
+    """With node-indexed uniforms the emitted tokens must be exactly what plain sampling of the target would
+    emit: at each visited node the token searchsorted(cumsum(p_node), u[T+node]); the walk follows a child iff it
+    carries that token.  Checked with an independent numpy walk."""
+    rng = np.random.default_rng(77)
+    T, V = 14, 9
+    SM = oracle.RULE_SAMPLE_MATCH
+    for trial in range(200):
+        parent = trees.random_tree(rng, T, 4, 3)
+        tl = (rng.standard_normal((T, V)) * 1.5).astype(np.float32)
+        token = rng.integers(0, V, size=T).astype(np.int32)
+        un = rng.random(2 * T, dtype=np.float32)
+        temp = 1.0 if trial % 2 else 0.7
+        r = oracle.tree_accept(tl, None, token, parent, un, temperature=temp, rule=SM)
+        cur, path = 0, [0]
+        while True:
+            y = int(np.searchsorted(np.cumsum(_softmax64(tl[cur], temp)), float(un[T + cur]), side="right"))
+            kids = [c for c in range(cur + 1, T) if parent[c] == cur]
+            hit = [c for c in kids if token[c] == y]
+            if not hit:
+                break
+            cur = hit[0]
+            path.append(cur)
+        assert list(r["path"][:len(path)]) == path and r["n_accepted"] == len(path) - 1
+        assert r["final_token"] == y and r["last_node"] == cur
+        assert r["final_kind"] == (oracle.FINAL_RESIDUAL if kids else oracle.FINAL_BONUS)
+
+
+def test_sample_and_match_first_token_law_is_the_target_law():
+    """Over a stratified grid of the root's uniform the first emitted token (the accepted child's token, or the
+    final token when nothing is accepted) is distributed as softmax(target[root]) up to the grid resolution."""
+    rng = np.random.default_rng(78)
+    T, V, n = 5, 6, 4000
+    parent = np.array([-1, 0, 0, 0, 1], dtype=np.int32)
+    token = np.array([0, 2, 4, 5, 1], dtype=np.int32)
+    tl = rng.standard_normal((T, V)).astype(np.float32)
+    counts = np.zeros(V)
+    for k in range(n):
+        un = np.full(2 * T, 0.5, dtype=np.float32)
+        un[T + 0] = (k + 0.5) / n
+        r = oracle.tree_accept(tl, None, token, parent, un, temperature=1.0, rule=oracle.RULE_SAMPLE_MATCH)
+        first = token[r["path"][1]] if r["n_accepted"] >= 1 else r["final_token"]
+        counts[first] += 1
+    assert np.abs(counts / n - _softmax64(tl[0], 1.0)).max() <= 2.0 / n
