@@ -68,6 +68,9 @@ extern "C" {
 #define TV_RULE_DETERMINISTIC  1   /* temp > 0, no draft law: each child is a point-mass proposal */
 #define TV_RULE_DRAFT_WOR      2   /* temp > 0, siblings drawn from the draft law without replacement */
 #define TV_RULE_DRAFT_WR       3   /* temp > 0, siblings drawn independently (with replacement) */
+#define TV_RULE_SAMPLE_MATCH   4   /* temp > 0, target logits only: the target's token is sampled at each node
+                                      (inverse CDF at u[T + node]) and a child is accepted iff it proposed that token;
+                                      the final token is the sample at the stop node */
 
 #define TV_FINAL_BONUS     0       /* nothing was rejected at the stop node: token from the target law */
 #define TV_FINAL_RESIDUAL  1       /* at least one child was rejected there: token from the corrected law */

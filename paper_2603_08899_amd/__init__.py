@@ -22,7 +22,7 @@ TV_STATUS_BAD_PATH = 32
 TV_MAX_ROWS = 128
 TV_DTYPE_F32, TV_DTYPE_BF16 = 0, 1
 TV_KIND_NODE, TV_KIND_CONTEMPLATE = 0, 1
-TV_RULE_GREEDY, TV_RULE_DETERMINISTIC, TV_RULE_DRAFT_WOR, TV_RULE_DRAFT_WR = 0, 1, 2, 3
+TV_RULE_GREEDY, TV_RULE_DETERMINISTIC, TV_RULE_DRAFT_WOR, TV_RULE_DRAFT_WR, TV_RULE_SAMPLE_MATCH = 0, 1, 2, 3, 4
 TV_FINAL_BONUS, TV_FINAL_RESIDUAL = 0, 1
 
 EXPORTED_SYMBOLS = (

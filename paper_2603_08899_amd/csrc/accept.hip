@@ -443,6 +443,94 @@ __global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs 
     }   // next node of this group
 }
 
+// ---- 2b. the target's own token at every node (sample-and-match rule) ---------------------------------------
+// Grid (T, B): one workgroup draws, for one node, the token that plain sampling of the target would emit there:
+// inverse CDF of softmax(target row / temperature) at the node's uniform u[T + node].  The row's ranges (already
+// reduced by the statistics kernel) locate the range that holds the crossing; only that range is read again.
+__global__ __launch_bounds__(kDrawThreads) void accept_sample_kernel(AcceptArgs a) {
+    const int i = blockIdx.x, b = blockIdx.y;
+    const int T = a.T, V = a.V;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const float it = kLog2e / a.temperature;
+    __shared__ double s_wave_tot[kDrawWaves];
+    __shared__ double s_base, s_inv_total;
+    __shared__ float s_max;
+    __shared__ int s_split, s_hit, s_last, s_tok;
+    const double u = (double)a.uniforms[(int64_t)b * 2 * T + T + i];
+    const RowStat* st = a.stats + (((int64_t)b * a.n_mat) * T + i) * a.splits;
+
+    if (wave == 0) {
+        // mass of every range relative to the row's maximum (a lane owns the ranges lane, lane + 64, ... but there
+        // are at most 64), prefix sum in range order, first range whose running sum exceeds u
+        const bool live = lane < a.splits;
+        const float ms = live ? st[lane].max_logit : -INFINITY;
+        const float m = wave_max(ms);
+        const double mass = live ? ((ms == m) ? st[lane].sum_exp : st[lane].sum_exp * unnorm_prob(ms, m, it)) : 0.0;
+        double inc = mass;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const double t = __shfl_up(inc, o, kWave);
+            if (lane >= o) inc += t;
+        }
+        const double total = __shfl(inc, kWave - 1, kWave);
+        const double inv_total = 1.0 / total;
+        const unsigned long long cross = __ballot(live && inc * inv_total > u);
+        const unsigned long long has = __ballot(live && mass > 0.0);
+        // (if rounding leaves the total at or below u: the last range that carries mass)
+        const int split = cross ? __ffsll((long long)cross) - 1 : (has ? 63 - __builtin_clzll(has) : 0);
+        const double before = __shfl(inc - mass, split, kWave);
+        if (lane == 0) {
+            s_split = split;
+            s_base = before * inv_total;
+            s_inv_total = inv_total;
+            s_max = m;
+            s_hit = kDrawThreads;
+            s_last = -1;
+            s_tok = -1;
+        }
+    }
+    __syncthreads();
+
+    // the chosen range, contiguous runs per lane in vocabulary order
+    const float* row = a.target + ((int64_t)b * T + i) * a.row_stride;
+    const int begin = s_split * a.split_len, end = min(V, begin + a.split_len);
+    const int per = (end - begin + kDrawThreads - 1) / kDrawThreads;
+    const int v0 = begin + tid * per, v1 = min(end, v0 + per);
+    const float m = s_max;
+    const double inv_total = s_inv_total;
+    double mine = 0.0;
+    int last = -1;
+    for (int v = v0; v < v1; ++v) {
+        const double pv = unnorm_prob(row[v], m, it) * inv_total;
+        mine += pv;
+        if (pv > 0.0) last = v;
+    }
+    if (last >= 0) atomicMax(&s_last, last);
+    double inc = mine;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const double t = __shfl_up(inc, o, kWave);
+        if (lane >= o) inc += t;
+    }
+    if (lane == kWave - 1) s_wave_tot[wave] = inc;
+    __syncthreads();
+    double before = s_base;
+    for (int w = 0; w < wave; ++w) before += s_wave_tot[w];
+    if (before + inc > u) atomicMin(&s_hit, tid);
+    __syncthreads();
+    if (tid == s_hit) {
+        double run = before + (inc - mine);
+        int found = -1;
+        for (int v = v0; v < v1 && found < 0; ++v) {
+            run += unnorm_prob(row[v], m, it) * inv_total;
+            if (run > u) found = v;
+        }
+        s_tok = (found >= 0) ? found : last;
+    }
+    __syncthreads();
+    if (tid == 0) a.sampled[(int64_t)b * T + i] = (s_hit == kDrawThreads) ? s_last : s_tok;
+}
+
 // ---- 3. walk + final draw ---------------------------------------------------------------------------------
 struct WalkShared {
     int parent[kMaxRows];
@@ -513,7 +601,9 @@ template <int kRule>
 __device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared& sh, int b, int sl) {
     const int T = a.T, V = a.V;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    constexpr bool kGreedy = (kRule == TV_RULE_GREEDY);
+    // sample-and-match walks like greedy, with the node's sampled token in the place of the row's argmax
+    constexpr bool kMatch = (kRule == TV_RULE_SAMPLE_MATCH);
+    constexpr bool kGreedy = (kRule == TV_RULE_GREEDY) || kMatch;
     constexpr bool kDraft = (kRule == TV_RULE_DRAFT_WOR || kRule == TV_RULE_DRAFT_WR);
     const float it = kGreedy ? 0.f : kLog2e / a.temperature;
 
@@ -553,7 +643,9 @@ __device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared&
     }
 
     // per-row statistics and each node's token logit in its parent's row
-    {
+    if (kMatch) {
+        for (int i = tid; i < T; i += kDrawThreads) sh.argmax[i] = a.sampled[(int64_t)b * T + i];
+    } else {
         const int n_rows = T * (kDraft ? 2 : 1);
         int g = 1;                                   // lanes that share one row's ranges
         while (2 * g * n_rows <= kDrawThreads && g < kWave) g *= 2;
@@ -829,7 +921,7 @@ int plan_accept(const tv_accept_desc& d, AcceptPlan* plan) {
     int slen = (d.V + ns - 1) / ns;
     slen = (slen + kGrain - 1) / kGrain * kGrain;
     p.slice_len = slen;
-    p.n_slices = (d.rule == TV_RULE_GREEDY) ? 1 : (d.V + slen - 1) / slen;
+    p.n_slices = (d.rule == TV_RULE_GREEDY || d.rule == TV_RULE_SAMPLE_MATCH) ? 1 : (d.V + slen - 1) / slen;
     auto up = [](size_t x) { return (x + 255) / 256 * 256; };
     p.stats_bytes = up((size_t)rows * p.splits * sizeof(RowStat));
     p.chain_bytes = up((size_t)d.B * d.T * sizeof(double));
@@ -865,9 +957,9 @@ static int chain_resident_workgroups(int rule) {
 
 // Workgroups of the walk kernel that are resident together on the current device (0 if unknown).
 static int walk_resident_workgroups(int rule) {
-    static int cache[4][64];
+    static int cache[5][64];
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64 || rule < 0 || rule > 3) return 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64 || rule < 0 || rule > 4) return 0;
     int& c = cache[rule][dev];
     if (c == 0) {
         int per_cu = 0, cus = 0;
@@ -876,6 +968,7 @@ static int walk_resident_workgroups(int rule) {
             case TV_RULE_GREEDY: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_GREEDY>, kDrawThreads, 0); break;
             case TV_RULE_DETERMINISTIC: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_DETERMINISTIC>, kDrawThreads, 0); break;
             case TV_RULE_DRAFT_WOR: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_DRAFT_WOR>, kDrawThreads, 0); break;
+            case TV_RULE_SAMPLE_MATCH: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_SAMPLE_MATCH>, kDrawThreads, 0); break;
             default: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_DRAFT_WR>, kDrawThreads, 0); break;
         }
         const hipError_t e2 = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
@@ -898,6 +991,7 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t s) {
         if (a.rule == TV_RULE_DRAFT_WOR) accept_chain_kernel<TV_RULE_DRAFT_WOR><<<gc, kChainThreads, 0, s>>>(a);
         else accept_chain_kernel<TV_RULE_DRAFT_WR><<<gc, kChainThreads, 0, s>>>(a);
     }
+    if (a.rule == TV_RULE_SAMPLE_MATCH) accept_sample_kernel<<<dim3(a.T, a.B), kDrawThreads, 0, s>>>(a);
     // whole groups of n_slices workgroups, no more than are resident at once
     int walk_groups = walk_resident_workgroups(a.rule) / a.n_slices;
     if (walk_groups < 1) return hipErrorLaunchOutOfResources;
@@ -905,6 +999,7 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t s) {
     const dim3 gw((unsigned)walk_groups * (unsigned)a.n_slices);
     switch (a.rule) {
         case TV_RULE_GREEDY: accept_walk_kernel<TV_RULE_GREEDY><<<gw, kDrawThreads, 0, s>>>(a); break;
+        case TV_RULE_SAMPLE_MATCH: accept_walk_kernel<TV_RULE_SAMPLE_MATCH><<<gw, kDrawThreads, 0, s>>>(a); break;
         case TV_RULE_DETERMINISTIC: accept_walk_kernel<TV_RULE_DETERMINISTIC><<<gw, kDrawThreads, 0, s>>>(a); break;
         case TV_RULE_DRAFT_WOR: accept_walk_kernel<TV_RULE_DRAFT_WOR><<<gw, kDrawThreads, 0, s>>>(a); break;
         default: accept_walk_kernel<TV_RULE_DRAFT_WR><<<gw, kDrawThreads, 0, s>>>(a); break;

@@ -192,7 +192,7 @@ int tree_verify_attention(const tv_attn_desc* desc, const void* q, const void* k
 static int check_accept_desc(const tv_accept_desc* d) {
     if (!d || d->struct_size != sizeof(tv_accept_desc)) return TV_ERR_INVALID_ARG;
     if (d->B < 1 || d->T < 1 || d->T > TV_MAX_ROWS || d->V < 1 || d->C < 0) return TV_ERR_INVALID_ARG;
-    if (d->rule < TV_RULE_GREEDY || d->rule > TV_RULE_DRAFT_WR) return TV_ERR_INVALID_ARG;
+    if (d->rule < TV_RULE_GREEDY || d->rule > TV_RULE_SAMPLE_MATCH) return TV_ERR_INVALID_ARG;
     if (d->rule != TV_RULE_GREEDY && !(d->temperature > 0.f)) return TV_ERR_INVALID_ARG;
     if (d->logits_row_stride != 0 && d->logits_row_stride < d->V) return TV_ERR_INVALID_ARG;
     if (d->reserved[0] != 0 || d->reserved[1] != 0) return TV_ERR_INVALID_ARG;
@@ -236,6 +236,7 @@ int tree_accept(const tv_accept_desc* desc, const float* target_logits, const fl
     a.stats = reinterpret_cast<RowStat*>(w);
     a.chain_z = reinterpret_cast<double*>(w + p.stats_bytes);
     a.accept_bit = reinterpret_cast<int32_t*>(w + p.stats_bytes + p.chain_bytes);
+    a.sampled = a.accept_bit;
     unsigned char* w2 = w + p.stats_bytes + p.chain_bytes + p.bits_bytes;
     a.slice_bits = reinterpret_cast<unsigned long long*>(w2);
     unsigned char* w3 = w2 + p.slice_bytes;

@@ -90,7 +90,8 @@ struct AcceptArgs {
     int32_t* status;
     RowStat* stats;       // [B][n_mat][T][splits]
     double*  chain_z;     // [B][T]: normaliser of the corrected law after rejecting child c
-    int32_t* accept_bit;  // [B][T]
+    int32_t* accept_bit;  // [B][T] (draft rules)
+    int32_t* sampled;     // [B][T] (sample-and-match rule; same storage as accept_bit): the target's token at each node
     unsigned long long* slice_bits;   // [B][kMaxSlices]: mass of the final law inside one vocabulary slice (fp64
                              // bits; the two lowest are a tag: 0 = published, 3 = not yet)
     unsigned long long* chain_parts;  // [B][T][2][chain_slices]: shares of a chain normaliser (fp64 bits, the two

@@ -15,6 +15,7 @@ RULE_GREEDY = 0
 RULE_DETERMINISTIC = 1
 RULE_DRAFT_WOR = 2
 RULE_DRAFT_WR = 3
+RULE_SAMPLE_MATCH = 4
 
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:

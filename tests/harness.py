@@ -134,6 +134,12 @@ def decision_margins(inp: AcceptInputs, b: int, ref: dict) -> float:
     margin = np.inf
     path = ref["path"][:ref["n_accepted"] + 1]
     p = None
+    if inp.rule == oracle.RULE_SAMPLE_MATCH:
+        # one inverse-CDF draw at every visited node
+        for cur in path:
+            cdf = np.cumsum(_softmax64(inp.target_logits[b, cur], inp.temperature))
+            margin = min(margin, float(np.abs(cdf - float(un[T + cur])).min()))
+        return margin
     for step, cur in enumerate(path):
         p = _softmax64(inp.target_logits[b, cur], inp.temperature)
         q = None if inp.draft_logits is None else _softmax64(inp.draft_logits[b, cur], inp.temperature)

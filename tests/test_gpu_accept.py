@@ -13,7 +13,7 @@ from tests import harness as H
 pytestmark = pytest.mark.gpu
 
 RULES = {"greedy": oracle.RULE_GREEDY, "det": oracle.RULE_DETERMINISTIC, "wor": oracle.RULE_DRAFT_WOR,
-         "wr": oracle.RULE_DRAFT_WR}
+         "wr": oracle.RULE_DRAFT_WR, "match": oracle.RULE_SAMPLE_MATCH}
 
 
 def _batch(seed, *, B, T, V, rule, temp, corr=0.9, max_depth=6, max_children=4, std=2.0, C=0, tree=None, boost=0.0):
@@ -156,3 +156,26 @@ def test_wait_that_runs_out_is_reported_not_hung():
         assert got["n_accepted"][0] == -1 and got["final_token"][0] == -1 and np.all(got["path"][0] == -1)
     print("wait limit 1 -> status", int(got["status"][0]))
     _run_and_compare(inp)
+
+
+# ---- the literal sample-and-match reading -----------------------------------------------------------------------
+@pytest.mark.parametrize("temp", [1.0, 0.7])
+def test_sample_and_match_many_small_sequences(temp):
+    inp = _batch(41, B=256, T=24, V=5003, rule=RULES["match"], temp=temp, C=3, boost=7.0)
+    inp.draft_logits = None
+    got = _run_and_compare(inp)
+    assert got["n_accepted"].max() >= 2 and got["n_accepted"].min() <= 2       # walks of different lengths
+
+
+def test_sample_and_match_full_vocabulary_and_padded_rows():
+    import dataclasses
+    base = si.accept_case(2, 1, child_boost=5.0)
+    inp = dataclasses.replace(base, rule=RULES["match"])
+    got = _run_and_compare(inp)
+    print("accepted", int(got["n_accepted"][0]))
+    small = _batch(42, B=4, T=20, V=3001, rule=RULES["match"], temp=1.0, boost=6.0)
+    small.draft_logits = None
+    _run_and_compare(small, row_stride=3003)
+    # batch of eight at full size
+    b8 = dataclasses.replace(si.accept_case(3, 0, child_boost=5.0), rule=RULES["match"])
+    _run_and_compare(b8)
