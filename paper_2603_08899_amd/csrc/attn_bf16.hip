@@ -503,7 +503,7 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
                 park(va_out[ks * 4 + dt]);
             }
     };
-    if (NQB == 1) {
+    if (NQB == 1 && RB == 1) {
         for (int it = 0; it < n_iter; it += 2) {
             tile_round(it, va_a, pb_a, va_b, pb_b);
             if (it + 1 < n_iter) tile_round(it + 1, va_b, pb_b, va_a, pb_a);
