@@ -238,18 +238,10 @@ __device__ __forceinline__ double block_sum(double x, double* scratch /* kWaves 
 constexpr int kChainPer = 16;                                  // vocabulary entries per lane
 constexpr int kChainQuads = kChainPer / 4;
 
-__device__ __forceinline__ double agent_load(const double* p) {
-    return __longlong_as_double((long long)__hip_atomic_load(reinterpret_cast<const unsigned long long*>(p),
-                                                             __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-}
-__device__ __forceinline__ void agent_store(double* p, double x) {
-    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), (unsigned long long)__double_as_longlong(x),
-                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 // What workgroups hand to each other inside a kernel goes through agent-scope atomic stores and loads, which
-// pass by the caches that are not coherent across the device; a lane then only has to wait until its stores
-// have completed before it counts itself in.  (A device-wide release fence would write back the whole L2.)
-__device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// pass by the caches that are not coherent across the device (a device-wide release fence would write back
+// the whole L2); every published value carries its own "ready" tag, so no second store has to be ordered
+// behind it.
 
 // Four consecutive logits of a row (entries past the end of the row read as -infinity, which the
 // laws map to zero mass).
@@ -281,165 +273,165 @@ __global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs 
     if (group >= n_groups) return;
     int loaded_b = -1;
     for (int item = group;; item += n_groups) {
-    const int b = item / T, r = item % T;
-    if (b >= a.B) break;
-    __syncthreads();
-    if (b != loaded_b) {
-        loaded_b = b;
-        for (int i = tid; i < T; i += kChainThreads) {
-            s_parent[i] = a.parent[(int64_t)b * T + i];
-            s_token[i] = a.token[(int64_t)b * T + i];
-            s_has[i] = 0;
-        }
+        const int b = item / T, r = item % T;
+        if (b >= a.B) break;
         __syncthreads();
-        int bad = validate_tree(s_parent, nullptr, T, &s_flag);
-        int tok_bad = 0;
-        for (int i = tid; i < T; i += kChainThreads)
-            if (s_token[i] < 0 || s_token[i] >= V) tok_bad = 1;
-        if (tok_bad) atomicOr(&s_flag, TV_STATUS_BAD_TOKEN);
-        __syncthreads();
-        bad = s_flag;
-        if (!bad)
-            for (int i = 1 + tid; i < T; i += kChainThreads) s_has[s_parent[i]] = 1;
-        __syncthreads();
-        if (wave == 0) {        // the nodes that have children, in index order
-            unsigned long long lo = __ballot(lane < T && s_has[lane]);
-            unsigned long long hi = __ballot(lane + kWave < T && s_has[lane + kWave]);
-            if (lane == 0) {
-                int n = 0;
-                while (lo) { s_internal[n++] = __ffsll((long long)lo) - 1; lo &= lo - 1; }
-                while (hi) { s_internal[n++] = kWave + __ffsll((long long)hi) - 1; hi &= hi - 1; }
-                s_nint = bad ? 0 : n;       // malformed input: nothing to do (the walk kernel reports it)
-                s_fail = 0;
+        if (b != loaded_b) {
+            loaded_b = b;
+            for (int i = tid; i < T; i += kChainThreads) {
+                s_parent[i] = a.parent[(int64_t)b * T + i];
+                s_token[i] = a.token[(int64_t)b * T + i];
+                s_has[i] = 0;
             }
-        }
-        __syncthreads();
-    }
-    if (r >= s_nint) continue;
-    const int u = s_internal[r];
-    if (wave == 0) {            // the children of u, in index order
-        const int par_lo = (lane < T) ? s_parent[lane] : -2;
-        const int par_hi = (lane + kWave < T) ? s_parent[lane + kWave] : -2;
-        unsigned long long kids_lo = __ballot(par_lo == u), kids_hi = __ballot(par_hi == u);
-        if (lane == 0) {
-            int k = 0;
-            while (kids_lo) { s_child[k++] = __ffsll((long long)kids_lo) - 1; kids_lo &= kids_lo - 1; }
-            while (kids_hi) { s_child[k++] = kWave + __ffsll((long long)kids_hi) - 1; kids_hi &= kids_hi - 1; }
-            s_k = k;
-        }
-    }
-    __syncthreads();
-    const int k = s_k;
-
-    const float it = kLog2e / a.temperature;
-    if (wave < 2) {         // wave 0: the target row's statistics, wave 1: the draft row's
-        const Red r = group_row_stat(a, b, wave, u, true, lane, kWave, it, true);
-        if (lane == 0) s_stat[wave] = r;
-    }
-    __syncthreads();
-    const Red sp = s_stat[0], sq = s_stat[1];
-    const double inv_sp = 1.0 / sp.s, inv_sq = 1.0 / sq.s;
-    const float* prow = a.target + ((int64_t)b * T + u) * a.row_stride;
-    const float* qrow = a.draft + ((int64_t)b * T + u) * a.row_stride;
-    const bool vec_ok = aligned16(prow) && aligned16(qrow);
-    __shared__ float s_zp[kMaxRows], s_zq[kMaxRows], s_u[kMaxRows];      // per child: its token's logits, its uniform
-    if (tid < k) {
-        const int c = s_child[tid];
-        s_zp[tid] = prow[s_token[c]];
-        s_zq[tid] = qrow[s_token[c]];
-        s_u[tid] = a.uniforms[(int64_t)b * 2 * T + c];
-    }
-    __syncthreads();
-
-    // this lane's entries of the two laws: quad qd covers v = slice_base + (qd * threads + tid) * 4 ...
-    const int slice_base = slice * (kChainThreads * kChainPer);
-    double p[kChainPer], q[kChainPer];
-#pragma unroll
-    for (int qd = 0; qd < kChainQuads; ++qd) {
-        const int v = slice_base + (qd * kChainThreads + tid) * 4;
-        float zp[4], zq[4];
-        if (v < V) {
-            load_quad(prow, vec_ok, v, V, zp);
-            load_quad(qrow, vec_ok, v, V, zq);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { zp[e] = -INFINITY; zq[e] = -INFINITY; }
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            p[4 * qd + e] = unnorm_prob(zp[e], sp.m, it) * inv_sp;
-            q[4 * qd + e] = unnorm_prob(zq[e], sq.m, it) * inv_sq;
-        }
-    }
-
-    for (int j = 0; j < k; ++j) {
-        const int c = s_child[j];
-        if (tid == 0) {
-            // the accept test of child j, as if its earlier siblings were all rejected
-            const int x = s_token[c];
-            double px, qx;
-            law_after<kRule>(x, unnorm_prob(s_zp[j], sp.m, it) * inv_sp, unnorm_prob(s_zq[j], sq.m, it) * inv_sq,
-                             s_steps, j, &px, &qx);
-            if (slice == 0) a.accept_bit[(int64_t)b * T + c] = ((double)s_u[j] * qx < px) ? 1 : 0;
-            ChainStep st;
-            st.tok = x;
-            st.inv_z = 0.0;
-            st.inv_ps = 1.0;
-            const double qs = 1.0 - qx;      // mass of q left once x is removed
-            st.inv_qs = (kRule == TV_RULE_DRAFT_WOR && qs > 0.0) ? 1.0 / qs : 0.0;
-            s_steps[j] = st;
-        }
-        // normaliser of the corrected law after rejecting child j: this slice's share ...
-        double part = 0.0;
-#pragma unroll
-        for (int e = 0; e < kChainPer; ++e) part += fmax(p[e] - q[e], 0.0);
-        const double mine = block_sum<kChainWaves>(part, s_red);
-        // ... published with the round number (mod 4) in the two lowest mantissa bits, which tells a reader that
-        // the slot holds this round's share: no counter, no second round trip.  Two buffers, by parity of j;
-        // the statistics kernel left tag 3 in both, which neither of the first two rounds expects.
-        unsigned long long* parts = a.chain_parts + ((((int64_t)b * T + u) * 2) + (j & 1)) * S;
-        const unsigned long long tag = (unsigned long long)(j & 3);
-        if (tid == 0)
-            __hip_atomic_store(parts + slice, ((unsigned long long)__double_as_longlong(mine) & ~3ull) | tag,
-                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        // ... and the whole: every workgroup of the group adds the shares in the same order
-        if (wave == 0) {
-            double z = 0.0;
-            int fail = 0;
-            unsigned polls = 0;
-            for (int s = lane; s < S; s += kWave) {
-                unsigned long long bits = 0;
-                for (;;) {
-                    bits = __hip_atomic_load(parts + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if ((bits & 3ull) == tag) break;
-                    __builtin_amdgcn_s_sleep(1);
-                    if (++polls > a.wait_limit) { fail = 1; break; }
+            __syncthreads();
+            int bad = validate_tree(s_parent, nullptr, T, &s_flag);
+            int tok_bad = 0;
+            for (int i = tid; i < T; i += kChainThreads)
+                if (s_token[i] < 0 || s_token[i] >= V) tok_bad = 1;
+            if (tok_bad) atomicOr(&s_flag, TV_STATUS_BAD_TOKEN);
+            __syncthreads();
+            bad = s_flag;
+            if (!bad)
+                for (int i = 1 + tid; i < T; i += kChainThreads) s_has[s_parent[i]] = 1;
+            __syncthreads();
+            if (wave == 0) {        // the nodes that have children, in index order
+                unsigned long long lo = __ballot(lane < T && s_has[lane]);
+                unsigned long long hi = __ballot(lane + kWave < T && s_has[lane + kWave]);
+                if (lane == 0) {
+                    int n = 0;
+                    while (lo) { s_internal[n++] = __ffsll((long long)lo) - 1; lo &= lo - 1; }
+                    while (hi) { s_internal[n++] = kWave + __ffsll((long long)hi) - 1; hi &= hi - 1; }
+                    s_nint = bad ? 0 : n;       // malformed input: nothing to do (the walk kernel reports it)
+                    s_fail = 0;
                 }
-                z += __longlong_as_double((long long)(bits & ~3ull));
             }
-            fail = __any(fail);
-            z = wave_sum(z);
+            __syncthreads();
+        }
+        if (r >= s_nint) continue;
+        const int u = s_internal[r];
+        if (wave == 0) {            // the children of u, in index order
+            const int par_lo = (lane < T) ? s_parent[lane] : -2;
+            const int par_hi = (lane + kWave < T) ? s_parent[lane + kWave] : -2;
+            unsigned long long kids_lo = __ballot(par_lo == u), kids_hi = __ballot(par_hi == u);
             if (lane == 0) {
-                s_fail = fail;
-                s_steps[j].inv_z = (z > 0.0) ? 1.0 / z : 0.0;
-                if (slice == 0) a.chain_z[(int64_t)b * T + c] = z;
+                int k = 0;
+                while (kids_lo) { s_child[k++] = __ffsll((long long)kids_lo) - 1; kids_lo &= kids_lo - 1; }
+                while (kids_hi) { s_child[k++] = kWave + __ffsll((long long)kids_hi) - 1; kids_hi &= kids_hi - 1; }
+                s_k = k;
             }
         }
         __syncthreads();
-        if (s_fail) {
-            if (tid == 0) *a.chain_fail = 1;
-            return;
+        const int k = s_k;
+
+        const float it = kLog2e / a.temperature;
+        if (wave < 2) {         // wave 0: the target row's statistics, wave 1: the draft row's
+            const Red r = group_row_stat(a, b, wave, u, true, lane, kWave, it, true);
+            if (lane == 0) s_stat[wave] = r;
         }
-        if (j + 1 < k) {
-            const ChainStep st = s_steps[j];
+        __syncthreads();
+        const Red sp = s_stat[0], sq = s_stat[1];
+        const double inv_sp = 1.0 / sp.s, inv_sq = 1.0 / sq.s;
+        const float* prow = a.target + ((int64_t)b * T + u) * a.row_stride;
+        const float* qrow = a.draft + ((int64_t)b * T + u) * a.row_stride;
+        const bool vec_ok = aligned16(prow) && aligned16(qrow);
+        __shared__ float s_zp[kMaxRows], s_zq[kMaxRows], s_u[kMaxRows];      // per child: its token's logits, its uniform
+        if (tid < k) {
+            const int c = s_child[tid];
+            s_zp[tid] = prow[s_token[c]];
+            s_zq[tid] = qrow[s_token[c]];
+            s_u[tid] = a.uniforms[(int64_t)b * 2 * T + c];
+        }
+        __syncthreads();
+
+        // this lane's entries of the two laws: quad qd covers v = slice_base + (qd * threads + tid) * 4 ...
+        const int slice_base = slice * (kChainThreads * kChainPer);
+        double p[kChainPer], q[kChainPer];
 #pragma unroll
-            for (int qd = 0; qd < kChainQuads; ++qd) {
-                const int v = slice_base + (qd * kChainThreads + tid) * 4;
+        for (int qd = 0; qd < kChainQuads; ++qd) {
+            const int v = slice_base + (qd * kChainThreads + tid) * 4;
+            float zp[4], zq[4];
+            if (v < V) {
+                load_quad(prow, vec_ok, v, V, zp);
+                load_quad(qrow, vec_ok, v, V, zq);
+            } else {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) law_step<kRule>(v + e, st, p[4 * qd + e], q[4 * qd + e]);
+                for (int e = 0; e < 4; ++e) { zp[e] = -INFINITY; zq[e] = -INFINITY; }
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                p[4 * qd + e] = unnorm_prob(zp[e], sp.m, it) * inv_sp;
+                q[4 * qd + e] = unnorm_prob(zq[e], sq.m, it) * inv_sq;
             }
         }
-    }
+
+        for (int j = 0; j < k; ++j) {
+            const int c = s_child[j];
+            if (tid == 0) {
+                // the accept test of child j, as if its earlier siblings were all rejected
+                const int x = s_token[c];
+                double px, qx;
+                law_after<kRule>(x, unnorm_prob(s_zp[j], sp.m, it) * inv_sp, unnorm_prob(s_zq[j], sq.m, it) * inv_sq,
+                                 s_steps, j, &px, &qx);
+                if (slice == 0) a.accept_bit[(int64_t)b * T + c] = ((double)s_u[j] * qx < px) ? 1 : 0;
+                ChainStep st;
+                st.tok = x;
+                st.inv_z = 0.0;
+                st.inv_ps = 1.0;
+                const double qs = 1.0 - qx;      // mass of q left once x is removed
+                st.inv_qs = (kRule == TV_RULE_DRAFT_WOR && qs > 0.0) ? 1.0 / qs : 0.0;
+                s_steps[j] = st;
+            }
+            // normaliser of the corrected law after rejecting child j: this slice's share ...
+            double part = 0.0;
+#pragma unroll
+            for (int e = 0; e < kChainPer; ++e) part += fmax(p[e] - q[e], 0.0);
+            const double mine = block_sum<kChainWaves>(part, s_red);
+            // ... published with the round number (mod 4) in the two lowest mantissa bits, which tells a reader that
+            // the slot holds this round's share: no counter, no second round trip.  Two buffers, by parity of j;
+            // the statistics kernel left tag 3 in both, which neither of the first two rounds expects.
+            unsigned long long* parts = a.chain_parts + ((((int64_t)b * T + u) * 2) + (j & 1)) * S;
+            const unsigned long long tag = (unsigned long long)(j & 3);
+            if (tid == 0)
+                __hip_atomic_store(parts + slice, ((unsigned long long)__double_as_longlong(mine) & ~3ull) | tag,
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // ... and the whole: every workgroup of the group adds the shares in the same order
+            if (wave == 0) {
+                double z = 0.0;
+                int fail = 0;
+                unsigned polls = 0;
+                for (int s = lane; s < S; s += kWave) {
+                    unsigned long long bits = 0;
+                    for (;;) {
+                        bits = __hip_atomic_load(parts + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if ((bits & 3ull) == tag) break;
+                        __builtin_amdgcn_s_sleep(1);
+                        if (++polls > a.wait_limit) { fail = 1; break; }
+                    }
+                    z += __longlong_as_double((long long)(bits & ~3ull));
+                }
+                fail = __any(fail);
+                z = wave_sum(z);
+                if (lane == 0) {
+                    s_fail = fail;
+                    s_steps[j].inv_z = (z > 0.0) ? 1.0 / z : 0.0;
+                    if (slice == 0) a.chain_z[(int64_t)b * T + c] = z;
+                }
+            }
+            __syncthreads();
+            if (s_fail) {
+                if (tid == 0) *a.chain_fail = 1;
+                return;
+            }
+            if (j + 1 < k) {
+                const ChainStep st = s_steps[j];
+#pragma unroll
+                for (int qd = 0; qd < kChainQuads; ++qd) {
+                    const int v = slice_base + (qd * kChainThreads + tid) * 4;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) law_step<kRule>(v + e, st, p[4 * qd + e], q[4 * qd + e]);
+                }
+            }
+        }
     }   // next node of this group
 }
 
