@@ -107,8 +107,8 @@ typedef struct tv_attn_desc {
     int64_t  kv_token_stride;  /* elements between consecutive rows of the pool; 0 = Hkv*D */
     int64_t  kv_head_stride;   /* elements between KV heads of one row; 0 = D */
     int32_t  num_splits;       /* 0 = library decides how many ranges the keys are cut into */
-    int32_t  wg_row_blocks;    /* bf16 path tuning, 0 = library decides: low byte = 64-row blocks of the packed query rows
-                                  one workgroup covers (1, 2 or 4); +0x100 = four 64-row waves instead of eight 32-row waves */
+    int32_t  wg_row_blocks;    /* bf16 path tuning, 0 = library decides: 64-row blocks of the packed query rows that one
+                                  workgroup covers (1, 2 or 4) */
 } tv_attn_desc;
 
 /* host: writes the workspace size (bytes) tree_verify_attention needs for *desc.

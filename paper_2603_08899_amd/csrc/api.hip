@@ -31,10 +31,8 @@ int check_attn_desc(const tv_attn_desc* d) {
         return TV_ERR_INVALID_ARG;
     if (d->Hq / d->Hkv > 16) return TV_ERR_INVALID_ARG;
     if (d->soft_len < 0 || d->max_prefix_len < d->soft_len || d->num_splits < 0) return TV_ERR_INVALID_ARG;
-    {
-        const int rbw = d->wg_row_blocks & 0xff;
-        if ((d->wg_row_blocks & ~0x1ff) != 0 || (rbw != 0 && rbw != 1 && rbw != 2 && rbw != 4)) return TV_ERR_INVALID_ARG;
-    }
+    if (d->wg_row_blocks != 0 && d->wg_row_blocks != 1 && d->wg_row_blocks != 2 && d->wg_row_blocks != 4)
+        return TV_ERR_INVALID_ARG;
     if (!(d->softmax_scale > 0.f)) return TV_ERR_INVALID_ARG;
     if (d->kv_token_stride < 0 || d->kv_head_stride < 0) return TV_ERR_INVALID_ARG;
     if (d->dtype == TV_DTYPE_F32) {
@@ -69,26 +67,34 @@ int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
     }
     const int rows = p.G * d.M;
     const int rb_needed = (rows + 63) / 64;
-    // waves of a workgroup that share one key stream (the rest of the 4 waves split the keys)
-    p.rb_per_wg = (d.wg_row_blocks & 0xff) ? (d.wg_row_blocks & 0xff) : 1;
-    p.wave_rows = (d.wg_row_blocks & 0x100) ? 64 : 32;
-    p.row_blocks = (rb_needed + p.rb_per_wg - 1) / p.rb_per_wg * p.rb_per_wg;
-    const int64_t base = (int64_t)d.B * d.Hkv * (p.row_blocks / p.rb_per_wg);
     const int n_tiles = (d.max_prefix_len + d.M + 31) / 32;
-    int n;
-    if (d.num_splits > 0) {
-        n = d.num_splits;
-    } else {
-        // one workgroup per CU for a single sequence; ragged batches get a few more, smaller ones
-        // so the hardware dispatcher can even them out
-        const int cus = device_cu_count();
-        const int64_t want = (d.B == 1) ? cus : 4 * (int64_t)cus;
-        n = (int)((want + base / 2) / base);
-    }
-    const int max_n = n_tiles / 8 > 1 ? n_tiles / 8 : 1;     // at least two tiles per wave
-    if (n > max_n) n = max_n;
-    if (n > 64) n = 64;
-    if (n < 1) n = 1;
+    // key ranges for workgroups of rb 64-row blocks
+    auto chunks_for = [&](int rb) {
+        const int64_t base = (int64_t)d.B * d.Hkv * ((rb_needed + rb - 1) / rb);
+        int n;
+        if (d.num_splits > 0) {
+            n = d.num_splits;
+        } else {
+            // one workgroup per CU for a single sequence; ragged batches get a few more, smaller ones
+            // so the hardware dispatcher can even them out
+            const int cus = device_cu_count();
+            const int64_t want = (d.B == 1) ? cus : 4 * (int64_t)cus;
+            n = (int)((want + base / 2) / base);
+        }
+        const int max_n = n_tiles / 8 > 1 ? n_tiles / 8 : 1;     // at least two tiles per wave
+        if (n > max_n) n = max_n;
+        if (n > 64) n = 64;
+        if (n < 1) n = 1;
+        return n;
+    };
+    // 64-row workgroups (four key streams, the smallest partial results) unless the caller says otherwise or
+    // every workgroup would get a long run of tiles: then 128-row workgroups, whose deeper stage ring and
+    // two-phase rounds stream K/V faster, win over their larger prologue and partial results (measured
+    // crossover on MI355X: about 40 tiles per 64-row workgroup)
+    p.rb_per_wg = d.wg_row_blocks ? d.wg_row_blocks : 1;
+    if (d.wg_row_blocks == 0 && rb_needed % 2 == 0 && n_tiles / chunks_for(1) >= 40) p.rb_per_wg = 2;
+    p.row_blocks = (rb_needed + p.rb_per_wg - 1) / p.rb_per_wg * p.rb_per_wg;
+    const int n = chunks_for(p.rb_per_wg);
     p.n_chunks = n;
     p.chunk_len = 0;
     if (n > 1) {
@@ -183,7 +189,7 @@ int tree_verify_attention(const tv_attn_desc* desc, const void* q, const void* k
     a.inv_M = 1.0f / (float)desc->M;
     a.head_stride = desc->kv_head_stride ? desc->kv_head_stride : desc->D;
     a.tok_stride = desc->kv_token_stride ? desc->kv_token_stride : (int64_t)desc->Hkv * desc->D;
-    a.row_blocks = p.row_blocks; a.n_chunks = p.n_chunks; a.chunk_len = p.chunk_len; a.rb_per_wg = p.rb_per_wg; a.wave_rows = p.wave_rows;
+    a.row_blocks = p.row_blocks; a.n_chunks = p.n_chunks; a.chunk_len = p.chunk_len; a.rb_per_wg = p.rb_per_wg;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const hipError_t e = (desc->dtype == TV_DTYPE_F32) ? launch_attention_f32(a, s) : launch_attention_bf16(a, s);
     return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;

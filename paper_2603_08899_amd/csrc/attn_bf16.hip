@@ -6,14 +6,13 @@
 //
 // Mapping
 //   - The G = Hq/Hkv query heads of one KV head times the M rows are packed into G*M rows
-//     r = head_in_group*M + row.  A wave owns NQB blocks of 32 consecutive packed rows (32 or 64 rows):
-//     Q^T for its rows stays in registers as the MFMA B operand for the whole kernel.
-//   - A workgroup covers RB*64 packed rows and one of n_chunks ranges of the sequence's keys.  Its waves
-//     (8 waves of 32 rows, two per SIMD so that one wave's softmax arithmetic runs under the other's matrix
-//     instructions; or 4 waves of 64 rows) form NS key streams: the range is cut into NS contiguous runs of
-//     32-key tiles, and the waves of a stream - one per row slice - consume the same K/V tiles from LDS.
+//     r = head_in_group*M + row.  A wave owns 32 consecutive packed rows: Q^T for its rows stays in
+//     registers as the MFMA B operand for the whole kernel.
+//   - A workgroup (8 waves, two per SIMD) covers RB*64 packed rows and one of n_chunks ranges of the
+//     sequence's keys.  Its waves form NS = 4/RB key streams: the range is cut into NS contiguous runs of
+//     32-key tiles, and the 2*RB waves of a stream - one per 32-row slice - consume the same K/V tiles from LDS.
 //   - K/V tiles and the Q block go HBM -> LDS directly (global_load_lds, 16 bytes per lane, no registers),
-//     tiles several steps ahead into a ring of stages per stream.  Rows are 256 bytes; bank conflicts are
+//     tiles ahead of their use into a ring of 2*RB stages per stream.  Rows are 256 bytes; bank conflicts are
 //     avoided by an XOR swizzle of the 16-byte segments which is applied on the global-address side.
 //   - Scores are formed transposed, S^T = K Q^T (A = K tile from LDS).  In the 32x32 accumulator a
 //     lane then holds one query (column) and 16 keys (rows): exactly the B-operand layout of
@@ -21,6 +20,12 @@
 //     Softmax row reductions are in-lane plus one exchange between the wave's halves.
 //   - Only tiles overlapping the soft-prompt slots, the new rows or the tail are masked, with a
 //     32-bit visibility word per (lane, query) derived from the two-word ancestor mask.
+//   - RB = 1 (64-row workgroups, four streams of two stages: the smallest partial results, for short and
+//     medium contexts): one barrier per tile; the product O^T += V^T P^T of a tile is issued one tile late,
+//     next to the following tile's exponentials.
+//     RB = 2, 4 (128- and 256-row workgroups, stages enough to keep tiles several rounds ahead, for long
+//     contexts and batches): a tile takes two barrier slots, scores in one, softmax and O^T product in the
+//     next, and the two waves of a SIMD are one slot apart.
 //   - Streams are merged through LDS; with n_chunks > 1 partial results (O / L in bf16, max and L in fp32)
 //     go to the workspace and attn_bf16_combine_kernel finishes.
 #include <atomic>
@@ -102,11 +107,6 @@ __device__ __forceinline__ unsigned lds_address(const void* p) {
     return (unsigned)(uintptr_t)(const void __attribute__((address_space(3)))*)p;
 }
 
-// Parks an MFMA A/B operand in the accumulation registers (an empty asm with an 'a' constraint): the matrix
-// instructions read operands from there as well as from ordinary VGPRs, and the ordinary ones are needed for
-// the accumulators (kept there so that the softmax arithmetic works on them in place).
-__device__ __forceinline__ void park(bf16x8& x) { asm("" : "+a"(x)); }
-
 // Visibility of the 32 keys of the tile starting at k0 for one query row (bit kk = key k0+kk).
 __device__ __forceinline__ unsigned tile_visibility(int k0, int P, int soft_len, bool is_con,
                                                     unsigned long long b0, unsigned long long b1) {
@@ -130,19 +130,18 @@ __device__ __forceinline__ unsigned tile_visibility(int k0, int P, int soft_len,
     return pm | nm;
 }
 
-// RB:  64-row blocks covered by one workgroup (1, 2 or 4)
-// NQB: 32-row query blocks per wave: 1 (eight waves, two per SIMD) or 2 (four waves)
-template <int RB, int NQB>
-__global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
-    constexpr int NW = 8 / NQB;                        // waves per workgroup
+// RB: 64-row blocks covered by one workgroup (1, 2 or 4)
+template <int RB>
+__global__ __launch_bounds__(512, 1) void attn_bf16_kernel(AttnArgs a) {
+    constexpr int NW = 8;                              // waves per workgroup, two per SIMD (waves w and w+4)
     constexpr int kThreads = NW * kWave;
-    constexpr int WROWS = 32 * NQB;                    // packed rows per wave
+    constexpr int WROWS = 32;                          // packed rows per wave
     constexpr int WPS = (kQRows * RB) / WROWS;         // waves per key stream (one per row slice)
     constexpr int NS = NW / WPS;                       // key streams per workgroup
     constexpr int S = kRingBytes / (NS * kStageBytes); // stages per stream: 2, 4 or 8 (= 2*RB)
     constexpr int PER = 16 / WPS;                      // direct-to-LDS loads per tile per wave
     static_assert(S == 2 * RB && PER >= 2, "stage ring layout");
-    extern __shared__ __align__(1024) unsigned char smem_raw[];   // stage bases are multiples of 256 (see k_it)
+    extern __shared__ __align__(1024) unsigned char smem_raw[];   // stage bases are multiples of 256 (see k_base)
     Bf16Smem& sm = *reinterpret_cast<Bf16Smem*>(smem_raw);
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -169,16 +168,16 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
     const int64_t kv_first_row = a.kv_offset[b];
 
     // ---- Q for this wave's rows: HBM -> LDS (the upper half of the stream's ring is free at this point) -
-    // Each 32-row query block is laid out like a K tile, with the same segment swizzle.
-    const int q_off = (S / 2) * kStageBytes + wsub * (NQB * kTileBytes);
+    // The 32-row query block is laid out like a K tile, with the same segment swizzle.
+    const int q_off = (S / 2) * kStageBytes + wsub * kTileBytes;
     {
         const unsigned q_stage = __builtin_amdgcn_readfirstlane(ring_addr + q_off);
         const unsigned long long q_sbase =
             scalar_base(static_cast<const unsigned char*>(a.q) + (int64_t)b * M * a.Hq * (kD * 2));
 #pragma unroll
-        for (int j = 0; j < 8 * NQB; ++j) {
-            const int row = 4 * (j & 7) + l_row;      // row inside the query block: selects the swizzle
-            const int r = min(row0 + 4 * j + l_row, n_rows - 1);      // padding rows re-read the last packed row
+        for (int j = 0; j < 8; ++j) {
+            const int row = 4 * j + l_row;            // row inside the query block: selects the swizzle
+            const int r = min(row0 + row, n_rows - 1);                 // padding rows re-read the last packed row
             const int hl = (int)(((float)r + 0.5f) * a.inv_M);         // r / M (exact for these sizes)
             const int i = r - hl * M;                                  // (head in group, tree row) of packed row r
             const unsigned off = (unsigned)((i * a.Hq + g * G + hl) * (kD * 2) + ((l_seg ^ (row & 15)) * 16));
@@ -320,178 +319,47 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
     typedef const bf16x8 __attribute__((address_space(3))) * lds_b128_ptr;
     typedef bf16x4 __attribute__((address_space(3))) * lds_b64_ptr;
 
-    // ---- this lane's queries (column ln of each query block): B operands of S^T, kept in registers ------
-    bf16x8 qreg[NQB][8];
-    int tree_row[NQB];       // tree row of the queries (the mask of a tile is derived from it on demand)
+    // ---- this lane's query (column ln of the query block): B operands of S^T, kept in registers ---------
+    bf16x8 qreg[8];
     {
         const unsigned q_it = ring_addr + q_off + k_base;
 #pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                qreg[qb][ks] = *(lds_b128_ptr)((q_it + qb * kTileBytes) ^ (ks << 5));
-                park(qreg[qb][ks]);
-            }
-            const int r = min(row0 + qb * 32 + ln, n_rows - 1);
-            tree_row[qb] = r - (int)(((float)r + 0.5f) * a.inv_M) * M;      // r % M
-        }
+        for (int ks = 0; ks < 8; ++ks) qreg[ks] = *(lds_b128_ptr)(q_it ^ (ks << 5));
     }
+    const int tree_row = [&] {       // tree row of the query (the mask of a tile is derived from it on demand)
+        const int r = min(row0 + ln, n_rows - 1);
+        return r - (int)(((float)r + 0.5f) * a.inv_M) * M;             // r % M
+    }();
     __syncthreads();         // the Q staging area goes back to the ring
 #pragma unroll
-    for (int i = S / 2; i < S - 1; ++i)
+    for (int i = S / 2; i < (RB == 1 ? S - 1 : S); ++i)       // RB = 1 keeps one stage back for the tile in use
         if (i < n_my) issue_tile(t_begin + i, i);
 
     const float c = a.scale * kLog2e;
-    float m_run[NQB], l_run[NQB];       // running max in log2 units (score * c); this lane's share of the sum
-    f32x16 o[4][NQB];
+    float m_run = -INFINITY, l_run = 0.f;       // running max in log2 units (score * c); this lane's share of the sum
+    f32x16 o[4];
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-        m_run[qb] = -INFINITY;
-        l_run[qb] = 0.f;
+    for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) o[dt][qb][j] = 0.f;
-    }
+        for (int j = 0; j < 16; ++j) o[dt][j] = 0.f;
 
-    // One tile per round.  The product O^T += V^T P^T of a tile is issued one round late, next to the
-    // exponentials of the following tile, so that the matrix pipe and the vector ALU work at the same time
-    // inside one wave (the waves of a workgroup move in step: they meet at a barrier every round).  Carried
-    // from round to round: the V^T operands and the probabilities of the previous tile.  Two sets of those
-    // registers alternate (the loop body is written out twice), so nothing has to be copied at the loop edge.
-    bf16x8 va_a[8], va_b[8], pb_a[NQB][2], pb_b[NQB][2];
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-#pragma unroll
-        for (int x = 0; x < 8; ++x) { va_a[e][x] = (__bf16)0.f; va_b[e][x] = (__bf16)0.f; }
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int x = 0; x < 8; ++x) { pb_a[qb][ks][x] = (__bf16)0.f; pb_b[qb][ks][x] = (__bf16)0.f; }
-
-    auto pv_mfma = [&](bf16x8 (&va)[8], bf16x8 (&pb)[NQB][2]) __attribute__((always_inline)) {
+    // O^T += V^T P^T for one tile
+    auto pv_mfma = [&](bf16x8 (&va)[8], bf16x8 (&pb)[2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                for (int qb = 0; qb < NQB; ++qb)
-                    o[dt][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks * 4 + dt], pb[qb][ks], o[dt][qb], 0, 0, 0);
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ks * 4 + dt], pb[ks], o[dt], 0, 0, 0);
     };
-
-    // Round `it`: consumes the previous tile's (va_in, pb_in), leaves this tile's in (va_out, pb_out).
-    auto tile_round = [&](int it, bf16x8 (&va_in)[8], bf16x8 (&pb_in)[NQB][2], bf16x8 (&va_out)[8],
-                          bf16x8 (&pb_out)[NQB][2]) __attribute__((always_inline)) {
-        const bool live = it < n_my;
-        if (live) {                                                     // this wave's part of tile `it` has landed
-            if (n_my - 1 - it >= S - 2) wait_vmcnt<(S - 2) * PER>();    // steady state: S-2 younger tiles in flight
-            else wait_vmcnt<0>();                                       // tail: fewer were issued, wait for all
-        }
-        if (WPS > 1) __syncthreads();                                   // ... and so have the other waves' parts
-        else {
-            __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-        }
-        const bool more = it + S - 1 < n_my;          // another tile to request, into the stage freed last round
-        if (more) issue_tile(t_begin + it + S - 1, (it + S - 1) % S);
-        if (!live) return;
-        const unsigned stage_addr = __builtin_amdgcn_readfirstlane(ring_addr + (it % S) * kStageBytes);
-        const unsigned k_it = stage_addr + k_base, v_it = stage_addr + v_base;
-        const int k0 = (t_begin + it) * kTK;
-
-        // S^T = K Q^T
-        f32x16 s[NQB];
+    // K operands (A of S^T) of one tile: all eight reads are requested back to back
+    auto read_k = [&](int it, bf16x8 (&ka)[8]) __attribute__((always_inline)) {
+        const unsigned k_it = __builtin_amdgcn_readfirstlane(ring_addr + (it % S) * kStageBytes) + k_base;
 #pragma unroll
-        for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) s[qb][j] = 0.f;
-        bf16x8 ka[8];            // all eight reads are requested before the first product (no read waits on a product)
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            ka[ks] = *(lds_b128_ptr)(k_it ^ (ks << 5));
-            park(ka[ks]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-            for (int qb = 0; qb < NQB; ++qb)
-                s[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[qb][ks], s[qb], 0, 0, 0);
-
-
-        // mask (only tiles touching the soft-prompt slots, the new rows or the tail)
-        if ((k0 < a.soft_len) || (k0 + kTK > P)) {
-#pragma unroll
-            for (int qb = 0; qb < NQB; ++qb) {
-                // rare (a few tiles per sequence): the row's ancestor mask, left in LDS by the prologue
-                const unsigned long long bits0 = sm.bits[tree_row[qb]][0], bits1 = sm.bits[tree_row[qb]][1];
-                const bool is_con = (sm.kind[tree_row[qb]] == TV_KIND_CONTEMPLATE);
-                const unsigned vis = tile_visibility(k0, P, a.soft_len, is_con, bits0, bits1) >> (4 * hf);
-#pragma unroll
-                for (int j = 0; j < 16; ++j)
-                    s[qb][j] = (vis & (1u << (8 * (j >> 2) + (j & 3)))) ? s[qb][j] : -INFINITY;
-            }
-        }
-
-        // online softmax; the max is raised lazily (probabilities may reach 2^kTau, harmless in fp32/bf16)
-        float tmax[NQB];
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-            float x = s[qb][0];
-#pragma unroll
-            for (int j = 1; j < 16; ++j) x = fmaxf(x, s[qb][j]);
-            tmax[qb] = cross_half_max(x) * c;
-        }
-        if (it == 0) {
-            // nothing accumulated yet: adopt the tile's max as the reference
-#pragma unroll
-            for (int qb = 0; qb < NQB; ++qb) m_run[qb] = tmax[qb];
-        } else {
-            bool raise[NQB], any = false;
-#pragma unroll
-            for (int qb = 0; qb < NQB; ++qb) {
-                raise[qb] = tmax[qb] > m_run[qb] + kTau;
-                any = any || raise[qb];
-            }
-            if (__any(any)) {
-                // rare: bring O up to date with the pending product, then rescale it to the new reference
-                pv_mfma(va_in, pb_in);
-#pragma unroll
-                for (int qb = 0; qb < NQB; ++qb) {
-#pragma unroll
-                    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                        for (int x = 0; x < 8; ++x) pb_in[qb][ks][x] = (__bf16)0.f;
-                    const float m_new = raise[qb] ? tmax[qb] : m_run[qb];
-                    const float alpha = raise[qb] ? __builtin_amdgcn_exp2f(m_run[qb] - m_new) : 1.f;   // exp2(-inf) = 0
-                    m_run[qb] = m_new;
-                    l_run[qb] *= alpha;
-#pragma unroll
-                    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                        for (int j = 0; j < 16; ++j) o[dt][qb][j] *= alpha;
-                }
-            }
-        }
-
-        // previous tile's O^T += V^T P^T (matrix pipe) next to this tile's exponentials (vector ALU)
-        pv_mfma(va_in, pb_in);
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-            const float mc = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
-            float sum = 0.f;
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(s[qb][j], c, -mc));
-                sum += p;
-                pb_out[qb][j >> 3][j & 7] = (__bf16)p;
-            }
-            l_run[qb] += sum;
-        }
-
-        // this tile's V^T operands, used one round later
+        for (int ks = 0; ks < 8; ++ks) ka[ks] = *(lds_b128_ptr)(k_it ^ (ks << 5));
+    };
+    // V^T operands (A of O^T) of one tile
+    auto read_v = [&](int it, bf16x8 (&va)[8]) __attribute__((always_inline)) {
+        const unsigned v_it = __builtin_amdgcn_readfirstlane(ring_addr + (it % S) * kStageBytes) + v_base;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -499,11 +367,111 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
                 const unsigned p0 = (v_it ^ (dt << 6)) + ks * (16 * kRowBytes);
                 const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(p0));
                 const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_b64_ptr)(p0 + 8 * kRowBytes));
-                va_out[ks * 4 + dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                park(va_out[ks * 4 + dt]);
+                va[ks * 4 + dt] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
     };
-    if (NQB == 1 && RB == 1) {
+    // S^T = K Q^T for one tile
+    auto score_tile = [&](bf16x8 (&ka)[8], f32x16& s) __attribute__((always_inline)) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s[j] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[ks], qreg[ks], s, 0, 0, 0);
+    };
+    // Mask of a tile that touches the soft-prompt slots, the new rows or the tail (a few tiles per sequence):
+    // from the row's ancestor mask, left in LDS by the prologue
+    auto mask_tile = [&](int it, f32x16& s) __attribute__((always_inline)) {
+        const int k0 = (t_begin + it) * kTK;
+        if ((k0 < a.soft_len) || (k0 + kTK > P)) {
+            const unsigned long long bits0 = sm.bits[tree_row][0], bits1 = sm.bits[tree_row][1];
+            const bool is_con = (sm.kind[tree_row] == TV_KIND_CONTEMPLATE);
+            const unsigned vis = tile_visibility(k0, P, a.soft_len, is_con, bits0, bits1) >> (4 * hf);
+#pragma unroll
+            for (int j = 0; j < 16; ++j) s[j] = (vis & (1u << (8 * (j >> 2) + (j & 3)))) ? s[j] : -INFINITY;
+        }
+    };
+    // Largest score of the lane's query in the tile, in log2 units
+    auto tile_max = [&](const f32x16& s) __attribute__((always_inline)) {
+        float x = s[0];
+#pragma unroll
+        for (int j = 1; j < 16; ++j) x = fmaxf(x, s[j]);
+        return cross_half_max(x) * c;
+    };
+    // The lane's query takes `tmax` as its new reference if that is what was asked for: O and the sum are rescaled
+    auto rescale = [&](bool raise, float tmax) __attribute__((always_inline)) {
+        const float m_new = raise ? tmax : m_run;
+        const float alpha = raise ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;   // exp2(-inf) = 0
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) o[dt][j] *= alpha;
+    };
+    // Probabilities of the tile (relative to the running reference) as B operands of O^T, and their sum
+    auto probabilities = [&](const f32x16& s, bf16x8 (&pb)[2]) __attribute__((always_inline)) {
+        const float mc = (m_run == -INFINITY) ? 0.f : m_run;
+        float sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[j], c, -mc));
+            sum += p;
+            pb[j >> 3][j & 7] = (__bf16)p;
+        }
+        l_run += sum;
+    };
+    // The running max is raised lazily: only when a tile's max exceeds it by more than 2^kTau (probabilities may
+    // reach 2^kTau, harmless in fp32/bf16), so the rescale of O is rare.
+
+    if (RB == 1) {
+        // One tile per round and one barrier per round.  The product O^T += V^T P^T of a tile is issued one round
+        // late, next to the exponentials of the following tile, so that the matrix pipe and the vector ALU work at
+        // the same time inside one wave.  Carried from round to round: the V^T operands and the probabilities of
+        // the previous tile.  Two sets of those registers alternate (the loop body is written out twice), so
+        // nothing has to be copied at the loop edge.
+        bf16x8 va_a[8], va_b[8], pb_a[2], pb_b[2];
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+#pragma unroll
+            for (int x = 0; x < 8; ++x) { va_a[e][x] = (__bf16)0.f; va_b[e][x] = (__bf16)0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int x = 0; x < 8; ++x) { pb_a[ks][x] = (__bf16)0.f; pb_b[ks][x] = (__bf16)0.f; }
+        // Round `it`: consumes the previous tile's (va_in, pb_in), leaves this tile's in (va_out, pb_out).
+        auto tile_round = [&](int it, bf16x8 (&va_in)[8], bf16x8 (&pb_in)[2], bf16x8 (&va_out)[8],
+                              bf16x8 (&pb_out)[2]) __attribute__((always_inline)) {
+            const bool live = it < n_my;
+            if (live) {                                                     // this wave's part of tile `it` has landed
+                if (n_my - 1 - it >= S - 2) wait_vmcnt<(S - 2) * PER>();    // steady state: S-2 younger tiles in flight
+                else wait_vmcnt<0>();                                       // tail: fewer were issued, wait for all
+            }
+            __syncthreads();                                                // ... and so have the other waves' parts
+            const bool more = it + S - 1 < n_my;      // another tile to request, into the stage freed last round
+            if (more) issue_tile(t_begin + it + S - 1, (it + S - 1) % S);
+            if (!live) return;
+            bf16x8 ka[8];        // all eight reads are requested before the first product (no read waits on a product)
+            read_k(it, ka);
+            __builtin_amdgcn_sched_barrier(0);
+            f32x16 s;
+            score_tile(ka, s);
+            mask_tile(it, s);
+            const float tmax = tile_max(s);
+            if (it == 0) {
+                m_run = tmax;                          // nothing accumulated yet: adopt the tile's max as the reference
+            } else if (__any(tmax > m_run + kTau)) {
+                // rare: bring O up to date with the pending product, then rescale it to the new reference
+                pv_mfma(va_in, pb_in);
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                    for (int x = 0; x < 8; ++x) pb_in[ks][x] = (__bf16)0.f;
+                rescale(tmax > m_run + kTau, tmax);
+            }
+            // previous tile's O^T += V^T P^T (matrix pipe) next to this tile's exponentials (vector ALU)
+            pv_mfma(va_in, pb_in);
+            probabilities(s, pb_out);
+            read_v(it, va_out);                        // this tile's V^T operands, used one round later
+        };
         for (int it = 0; it < n_iter; it += 2) {
             tile_round(it, va_a, pb_a, va_b, pb_b);
             if (it + 1 < n_iter) tile_round(it + 1, va_b, pb_b, va_a, pb_a);
@@ -512,9 +480,68 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
         if (n_my & 1) pv_mfma(va_b, pb_b);
         else pv_mfma(va_a, pb_a);
     } else {
-        // 64-row waves have no registers to spare for a second set: one set, consumed before it is refilled
-        for (int it = 0; it < n_iter; ++it) tile_round(it, va_a, pb_a, va_a, pb_a);
-        pv_mfma(va_a, pb_a);
+        // Waves that share one or two key streams (eight or four stages) take a tile in two phases, in two barrier
+        // slots: phase A = K operands and the score products; phase B = V^T operands (requested first), mask,
+        // softmax, then O^T += V^T P^T.  The two waves of a SIMD (w and w+4) are one phase apart, so that one's
+        // matrix-heavy phase runs under the other's vector-heavy one; only the scores are carried between phases.
+        //   slot 2t   : waves 0-3 phase A of tile t,  waves 4-7 phase B of tile t-1
+        //   slot 2t+1 : waves 0-3 phase B of tile t,  waves 4-7 phase A of tile t
+        // Every wave has waited for its part of tile t before the barrier that opens slot 2t.  The stage of tile t
+        // is read for the last time in slot 2t+2 and refilled (tile t+S) after the barrier that opens slot 2t+3.
+        // The two halves of the workgroup run separate copies of the loop (both meet 2*n_iter+1 barriers): with the
+        // phase order fixed in each copy the accumulators stay in place.
+        f32x16 s;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s[j] = 0.f;
+        // the barrier that opens slot 2t, once this wave's part of tile t has landed
+        auto open_even = [&](int t) __attribute__((always_inline)) {
+            if (t < n_my) {
+                const int younger = min(n_my - 1, S - 1 + max(0, t - 1)) - t;       // tiles requested after tile t
+                if (younger >= S - 1) wait_vmcnt<(S - 1) * PER>();
+                else if (younger == S - 2) wait_vmcnt<(S - 2) * PER>();
+                else wait_vmcnt<0>();
+            }
+            __syncthreads();
+        };
+        // the barrier that opens slot 2t+1; the stage of tile t-1 is free from here on
+        auto open_odd = [&](int t) __attribute__((always_inline)) {
+            __syncthreads();
+            if (t >= 1 && t - 1 + S < n_my) issue_tile(t_begin + t - 1 + S, (t - 1) % S);
+        };
+        auto phase_a = [&](int t) __attribute__((always_inline)) {
+            bf16x8 ka[8];
+            read_k(t, ka);
+            score_tile(ka, s);
+        };
+        auto phase_b = [&](int t) __attribute__((always_inline)) {
+            bf16x8 va[8], pb[2];
+            read_v(t, va);
+            __builtin_amdgcn_sched_barrier(0);
+            mask_tile(t, s);
+            const float tmax = tile_max(s);
+            if (t == 0) m_run = tmax;
+            else if (__any(tmax > m_run + kTau)) rescale(tmax > m_run + kTau, tmax);      // rare
+            probabilities(s, pb);
+            pv_mfma(va, pb);
+        };
+        if ((wave >> 2) == 0) {
+            for (int t = 0; t < n_iter; ++t) {
+                open_even(t);
+                if (t < n_my) phase_a(t);
+                open_odd(t);
+                if (t < n_my) phase_b(t);
+            }
+            open_even(n_iter);
+        } else {
+            for (int t = 0; t < n_iter; ++t) {
+                open_even(t);
+                if (t >= 1 && t - 1 < n_my) phase_b(t - 1);
+                open_odd(t);
+                if (t < n_my) phase_a(t);
+            }
+            open_even(n_iter);
+            if (n_iter - 1 < n_my) phase_b(n_iter - 1);
+        }
     }
 
     // ---- merge the streams through LDS -------------------------------------------------------------------
@@ -522,12 +549,11 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
     wait_vmcnt<0>();
     __syncthreads();       // every wave is done with the stage ring
     f32x4* mbuf = reinterpret_cast<f32x4*>(sm.big);
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-        const float l_tot = cross_half_sum(l_run[qb]);
-        const int mrow = wave * WROWS + qb * 32 + ln;
+    {
+        const float l_tot = cross_half_sum(l_run);
+        const int mrow = wave * WROWS + ln;
         if (hf == 0) {
-            sm.ml[mrow][0] = m_run[qb];
+            sm.ml[mrow][0] = m_run;
             sm.ml[mrow][1] = l_tot;
         }
         f32x4* orow = mbuf + mrow * 32;
@@ -535,7 +561,7 @@ __global__ __launch_bounds__(512 / NQB, 1) void attn_bf16_kernel(AttnArgs a) {
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
             for (int jg = 0; jg < 4; ++jg) {
-                f32x4 x = {o[dt][qb][4 * jg], o[dt][qb][4 * jg + 1], o[dt][qb][4 * jg + 2], o[dt][qb][4 * jg + 3]};
+                f32x4 x = {o[dt][4 * jg], o[dt][4 * jg + 1], o[dt][4 * jg + 2], o[dt][4 * jg + 3]};
                 orow[(dt * 8 + 2 * jg + hf) ^ ln] = x;
             }
     }
@@ -651,7 +677,7 @@ __global__ __launch_bounds__(256) void attn_bf16_combine_kernel(AttnArgs a) {
     if (a.lse && d0 == 0) a.lse[((int64_t)b * a.Hq + h) * a.M + i] = (mx + log2f(L)) * kLn2;
 }
 
-template <int RB, int NQB>
+template <int RB>
 hipError_t launch_variant(const AttnArgs& a, hipStream_t s) {
     static std::atomic<unsigned> attr_done{0};       // one bit per device
     int dev = 0;
@@ -659,13 +685,13 @@ hipError_t launch_variant(const AttnArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     const unsigned bit = 1u << (dev & 31);
     if (!(attr_done.load(std::memory_order_acquire) & bit)) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<RB, NQB>),
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<RB>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Bf16Smem));
         if (e != hipSuccess) return e;
         attr_done.fetch_or(bit, std::memory_order_release);
     }
     const dim3 grid(a.Hkv * (a.row_blocks / RB) * a.n_chunks, a.B);
-    attn_bf16_kernel<RB, NQB><<<grid, 512 / NQB, sizeof(Bf16Smem), s>>>(a);
+    attn_bf16_kernel<RB><<<grid, 512, sizeof(Bf16Smem), s>>>(a);
     return hipGetLastError();
 }
 
@@ -673,18 +699,10 @@ hipError_t launch_variant(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
     hipError_t e;
-    if (a.wave_rows == 64) {
-        switch (a.rb_per_wg) {
-            case 1: e = launch_variant<1, 2>(a, s); break;
-            case 2: e = launch_variant<2, 2>(a, s); break;
-            default: e = launch_variant<4, 2>(a, s); break;
-        }
-    } else {
-        switch (a.rb_per_wg) {
-            case 1: e = launch_variant<1, 1>(a, s); break;
-            case 2: e = launch_variant<2, 1>(a, s); break;
-            default: e = launch_variant<4, 1>(a, s); break;
-        }
+    switch (a.rb_per_wg) {
+        case 1: e = launch_variant<1>(a, s); break;
+        case 2: e = launch_variant<2>(a, s); break;
+        default: e = launch_variant<4>(a, s); break;
     }
     if (e != hipSuccess) return e;
     if (a.n_chunks > 1) {
