@@ -90,9 +90,9 @@ int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
     // 64-row workgroups (four key streams, the smallest partial results) unless the caller says otherwise or
     // every workgroup would get a long run of tiles: then 128-row workgroups, whose deeper stage ring and
     // two-phase rounds stream K/V faster, win over their larger prologue and partial results (measured
-    // crossover on MI355X: about 40 tiles per 64-row workgroup)
+    // crossover on MI355X: about 56 tiles per 64-row workgroup)
     p.rb_per_wg = d.wg_row_blocks ? d.wg_row_blocks : 1;
-    if (d.wg_row_blocks == 0 && rb_needed % 2 == 0 && n_tiles / chunks_for(1) >= 40) p.rb_per_wg = 2;
+    if (d.wg_row_blocks == 0 && rb_needed % 2 == 0 && n_tiles / chunks_for(1) >= 56) p.rb_per_wg = 2;
     p.row_blocks = (rb_needed + p.rb_per_wg - 1) / p.rb_per_wg * p.rb_per_wg;
     const int n = chunks_for(p.rb_per_wg);
     p.n_chunks = n;

@@ -438,22 +438,32 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(AttnArgs a) {
 #pragma unroll
             for (int x = 0; x < 8; ++x) { pb_a[ks][x] = (__bf16)0.f; pb_b[ks][x] = (__bf16)0.f; }
         // Round `it`: consumes the previous tile's (va_in, pb_in), leaves this tile's in (va_out, pb_out).
+        // With two stages per stream a whole tile could only be requested one round ahead.  The two halves of a
+        // stage are therefore refilled separately, each as soon as its last reader is done: the K half in the
+        // middle of the round (the K operands are in registers by then) with the K rows of tile it+2, the V half
+        // at the top of the next round with the V rows of tile it+2; both are then a round and a half ahead of
+        // their use.  Requests of a wave, in order: ... K(it) V(it) K(it+1) | V(it+1) K(it+2) | ...
         auto tile_round = [&](int it, bf16x8 (&va_in)[8], bf16x8 (&pb_in)[2], bf16x8 (&va_out)[8],
                               bf16x8 (&pb_out)[2]) __attribute__((always_inline)) {
-            const bool live = it < n_my;
-            if (live) {                                                     // this wave's part of tile `it` has landed
-                if (n_my - 1 - it >= S - 2) wait_vmcnt<(S - 2) * PER>();    // steady state: S-2 younger tiles in flight
-                else wait_vmcnt<0>();                                       // tail: fewer were issued, wait for all
+            const bool live = it < n_my, next = it + 1 < n_my;
+            if (live) {                                        // this wave's part of K(it) has landed
+                if (next) wait_vmcnt<PER>();                   // younger: V(it), K(it+1)
+                else wait_vmcnt<PER / 2>();                    // younger: V(it)
             }
-            __syncthreads();                                                // ... and so have the other waves' parts
-            const bool more = it + S - 1 < n_my;      // another tile to request, into the stage freed last round
-            if (more) issue_tile(t_begin + it + S - 1, (it + S - 1) % S);
-            if (!live) return;
-            bf16x8 ka[8];        // all eight reads are requested before the first product (no read waits on a product)
-            read_k(it, ka);
-            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();                                   // ... and so have the other waves' parts
+            if (next) issue_half(t_begin + it + 1, (it + 1) % S, 1);       // V(it+1): V(it-1) was read last round
             f32x16 s;
-            score_tile(ka, s);
+            if (live) {
+                bf16x8 ka[8];    // all eight reads are requested before the first product (no read waits on a product)
+                read_k(it, ka);
+                __builtin_amdgcn_sched_barrier(0);
+                score_tile(ka, s);
+                if (next) wait_vmcnt<PER>();                   // V(it) has landed; younger: K(it+1), V(it+1)
+                else wait_vmcnt<0>();
+            }
+            __syncthreads();                                   // every wave holds its K operands; V(it) is complete
+            if (it + 2 < n_my) issue_half(t_begin + it + 2, it % S, 0);     // K(it+2)
+            if (!live) return;
             mask_tile(it, s);
             const float tmax = tile_max(s);
             if (it == 0) {
@@ -472,6 +482,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(AttnArgs a) {
             probabilities(s, pb_out);
             read_v(it, va_out);                        // this tile's V^T operands, used one round later
         };
+        if (1 < n_my) issue_half(t_begin + 1, 1, 0);   // K(1): the Q staging area is free
         for (int it = 0; it < n_iter; it += 2) {
             tile_round(it, va_a, pb_a, va_b, pb_b);
             if (it + 1 < n_iter) tile_round(it + 1, va_b, pb_b, va_a, pb_a);
