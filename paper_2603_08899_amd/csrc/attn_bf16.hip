@@ -629,63 +629,62 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(AttnArgs a) {
     }
 }
 
-// Merges the n_chunks partial results of every output row.  32 threads per row (4 columns each).
+// Merges the n_chunks partial results of every output row.  Grid (Hkv * ceil(G*M / 16), B): workgroup
+// blockIdx.x = g + Hkv * k takes the packed rows 16k .. 16k+15 of KV head g, 16 threads per row (8 columns each,
+// 16-byte loads).  With the KV head in the low part of the index a workgroup lands on the XCD whose workgroups
+// wrote the partial results it reads (both kernels deal workgroups round-robin to the XCDs, KV head first).
+constexpr int kCombineRows = 16;
 __global__ __launch_bounds__(256) void attn_bf16_combine_kernel(AttnArgs a) {
-    const int rows_per_wg = 256 / 32;
-    const int64_t row = (int64_t)blockIdx.x * rows_per_wg + threadIdx.x / 32;     // over B*M*Hq
-    const int64_t total = (int64_t)a.B * a.M * a.Hq;
-    if (row >= total) return;
-    const int h = (int)(row % a.Hq);
-    const int i = (int)((row / a.Hq) % a.M);
-    const int b = (int)(row / ((int64_t)a.Hq * a.M));
-    const int d0 = (threadIdx.x % 32) * 4;
-    unsigned short* dst = static_cast<unsigned short*>(a.out) + row * kD + d0;
-    if (a.status[b] != 0) {
-        *reinterpret_cast<uint2*>(dst) = make_uint2(0u, 0u);
-        if (a.lse && d0 == 0) a.lse[((int64_t)b * a.Hq + h) * a.M + i] = 0.f;
-        return;
-    }
-    const int g = h / a.G, r = (h % a.G) * a.M + i;
+    const int g = blockIdx.x % a.Hkv, b = blockIdx.y;
+    const int r = (blockIdx.x / a.Hkv) * kCombineRows + threadIdx.x / 16;      // packed row of KV head g
+    if (r >= a.G * a.M) return;
+    const int bad = a.status[b];          // requested first, looked at last: the partial loads do not wait for it
+    const int hl = (int)(((float)r + 0.5f) * a.inv_M);              // r / M (exact for these sizes)
+    const int i = r - hl * a.M, h = g * a.G + hl;
+    const int d0 = (threadIdx.x % 16) * 8;
+    unsigned short* dst = static_cast<unsigned short*>(a.out) + (((int64_t)b * a.M + i) * a.Hq + h) * kD + d0;
     const int rb = r / kQRows, qi = r % kQRows;
     const int64_t blk0 = ((int64_t)b * a.n_chunks * a.Hkv + g) * a.row_blocks + rb;
     const int64_t blk_step = (int64_t)a.Hkv * a.row_blocks;
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float L = 0.f, mx = -INFINITY;
     for (int ch0 = 0; ch0 < a.n_chunks; ch0 += 8) {
         // up to 8 partials at a time: all loads of a batch are issued before any is used
-        float mm[8], ll[8];
-        bf16x4 oo[8];
+        float2 ml[8];
+        bf16x8 oo[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const bool ok = ch0 + e < a.n_chunks;
-            const int64_t blk = blk0 + (int64_t)(ok ? ch0 + e : ch0) * blk_step;
-            mm[e] = ok ? a.part_ml[(blk * kQRows + qi) * 2] : -INFINITY;
-            ll[e] = a.part_ml[(blk * kQRows + qi) * 2 + 1];
-            oo[e] = *reinterpret_cast<const bf16x4*>(static_cast<const unsigned short*>(a.part_o) + (blk * kQRows + qi) * kD + d0);
+            const int64_t blk = blk0 + (int64_t)(ch0 + e < a.n_chunks ? ch0 + e : ch0) * blk_step;
+            ml[e] = *reinterpret_cast<const float2*>(a.part_ml + (blk * kQRows + qi) * 2);
+            oo[e] = *reinterpret_cast<const bf16x8*>(static_cast<const unsigned short*>(a.part_o) + (blk * kQRows + qi) * kD + d0);
         }
         float bm = mx;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) bm = fmaxf(bm, mm[e]);
+        for (int e = 0; e < 8; ++e) {
+            if (ch0 + e >= a.n_chunks) ml[e].x = -INFINITY;         // absent partials weigh nothing
+            bm = fmaxf(bm, ml[e].x);
+        }
         const float bms = (bm == -INFINITY) ? 0.f : bm;
         const float resc = __builtin_amdgcn_exp2f(mx - bms);        // 0 on the first batch
-        acc *= resc;
+#pragma unroll
+        for (int x = 0; x < 8; ++x) acc[x] *= resc;
         L *= resc;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const float w = __builtin_amdgcn_exp2f(mm[e] - bms);    // 0 for absent partials
-            const float wl = w * ll[e];                             // the partial holds O / L
+            const float wl = __builtin_amdgcn_exp2f(ml[e].x - bms) * ml[e].y;   // the partial holds O / L
             L += wl;
-            acc[0] += wl * (float)oo[e][0]; acc[1] += wl * (float)oo[e][1];
-            acc[2] += wl * (float)oo[e][2]; acc[3] += wl * (float)oo[e][3];
+#pragma unroll
+            for (int x = 0; x < 8; ++x) acc[x] += wl * (float)oo[e][x];
         }
         mx = bm;
     }
-    const float inv = 1.f / L;
-    bf16x4 ob;
-    ob[0] = (__bf16)(acc[0] * inv); ob[1] = (__bf16)(acc[1] * inv);
-    ob[2] = (__bf16)(acc[2] * inv); ob[3] = (__bf16)(acc[3] * inv);
-    *reinterpret_cast<bf16x4*>(dst) = ob;
-    if (a.lse && d0 == 0) a.lse[((int64_t)b * a.Hq + h) * a.M + i] = (mx + log2f(L)) * kLn2;
+    // a flagged sequence gets zeros (its workgroups wrote no partial results; what was read above is discarded)
+    const float inv = bad ? 0.f : 1.f / L;
+    bf16x8 ob;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) ob[x] = (__bf16)(bad ? 0.f : acc[x] * inv);
+    *reinterpret_cast<bf16x8*>(dst) = ob;
+    if (a.lse && d0 == 0) a.lse[((int64_t)b * a.Hq + h) * a.M + i] = bad ? 0.f : (mx + log2f(L)) * kLn2;
 }
 
 template <int RB>
@@ -717,8 +716,7 @@ hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
     }
     if (e != hipSuccess) return e;
     if (a.n_chunks > 1) {
-        const int64_t rows = (int64_t)a.B * a.M * a.Hq;
-        attn_bf16_combine_kernel<<<dim3((unsigned)((rows + 7) / 8)), 256, 0, s>>>(a);
+        attn_bf16_combine_kernel<<<dim3((unsigned)(a.Hkv * ((a.G * a.M + kCombineRows - 1) / kCombineRows)), (unsigned)a.B), 256, 0, s>>>(a);
         e = hipGetLastError();
     }
     return e;
