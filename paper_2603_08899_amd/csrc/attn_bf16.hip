@@ -423,73 +423,92 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(AttnArgs a) {
     // reach 2^kTau, harmless in fp32/bf16), so the rescale of O is rare.
 
     if (RB == 1) {
-        // One tile per round and one barrier per round.  The product O^T += V^T P^T of a tile is issued one round
-        // late, next to the exponentials of the following tile, so that the matrix pipe and the vector ALU work at
-        // the same time inside one wave.  Carried from round to round: the V^T operands and the probabilities of
-        // the previous tile.  Two sets of those registers alternate (the loop body is written out twice), so
-        // nothing has to be copied at the loop edge.
-        bf16x8 va_a[8], va_b[8], pb_a[2], pb_b[2];
+        // Four streams of two stages.  A tile takes two barrier slots: phase A = K operands and the score products;
+        // phase B = mask, softmax next to the PREVIOUS tile's O^T += V^T P^T (issued one tile late so that the
+        // matrix pipe and the vector ALU work at the same time inside one wave), then the tile's V^T operands.
+        // The two waves of a SIMD (w and w+4, i.e. streams 0-1 and streams 2-3) are one phase apart:
+        //   slot 2t   : waves 0-3 phase A of tile t,  waves 4-7 phase B of tile t-1
+        //   slot 2t+1 : waves 0-3 phase B of tile t,  waves 4-7 phase A of tile t
+        // With two stages a whole tile could only be requested one round ahead, so the halves of a stage are
+        // refilled separately, each by the stream's own waves right after the barrier that follows its last
+        // read: the K half with K(t+2) when the slot of phase B(t) opens, the V half with V(t+2) when the slot
+        // of phase A(t+1) opens - three slots (a round and a half) ahead of their use.  Requests of a wave, in
+        // order: K0 V0 (prologue) K1 V1 | K2 | V2 | K3 | V3 ...  Both halves of the workgroup run their own copy
+        // of the loop (2*n_iter+1 barriers each): with the phase order fixed the accumulators stay in place.
+        bf16x8 va[8], pb[2];     // V^T operands and probabilities of the previous tile
 #pragma unroll
         for (int e = 0; e < 8; ++e)
 #pragma unroll
-            for (int x = 0; x < 8; ++x) { va_a[e][x] = (__bf16)0.f; va_b[e][x] = (__bf16)0.f; }
+            for (int x = 0; x < 8; ++x) va[e][x] = (__bf16)0.f;
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-            for (int x = 0; x < 8; ++x) { pb_a[ks][x] = (__bf16)0.f; pb_b[ks][x] = (__bf16)0.f; }
-        // Round `it`: consumes the previous tile's (va_in, pb_in), leaves this tile's in (va_out, pb_out).
-        // With two stages per stream a whole tile could only be requested one round ahead.  The two halves of a
-        // stage are therefore refilled separately, each as soon as its last reader is done: the K half in the
-        // middle of the round (the K operands are in registers by then) with the K rows of tile it+2, the V half
-        // at the top of the next round with the V rows of tile it+2; both are then a round and a half ahead of
-        // their use.  Requests of a wave, in order: ... K(it) V(it) K(it+1) | V(it+1) K(it+2) | ...
-        auto tile_round = [&](int it, bf16x8 (&va_in)[8], bf16x8 (&pb_in)[2], bf16x8 (&va_out)[8],
-                              bf16x8 (&pb_out)[2]) __attribute__((always_inline)) {
-            const bool live = it < n_my, next = it + 1 < n_my;
-            if (live) {                                        // this wave's part of K(it) has landed
-                if (next) wait_vmcnt<PER>();                   // younger: V(it), K(it+1)
-                else wait_vmcnt<PER / 2>();                    // younger: V(it)
+            for (int x = 0; x < 8; ++x) pb[ks][x] = (__bf16)0.f;
+        f32x16 s;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s[j] = 0.f;
+        if (1 < n_my) issue_tile(t_begin + 1, 1);      // K1, V1: the Q staging area is free
+        // opens the slot of phase A(t): K(t) has landed (younger requests: V(t), K(t+1)); V(t+1) may be requested
+        auto open_a = [&](int t) __attribute__((always_inline)) {
+            if (t < n_my) {
+                if (t + 1 < n_my) wait_vmcnt<PER>();
+                else wait_vmcnt<PER / 2>();
             }
-            __syncthreads();                                   // ... and so have the other waves' parts
-            if (next) issue_half(t_begin + it + 1, (it + 1) % S, 1);       // V(it+1): V(it-1) was read last round
-            f32x16 s;
-            if (live) {
-                bf16x8 ka[8];    // all eight reads are requested before the first product (no read waits on a product)
-                read_k(it, ka);
-                __builtin_amdgcn_sched_barrier(0);
-                score_tile(ka, s);
-                if (next) wait_vmcnt<PER>();                   // V(it) has landed; younger: K(it+1), V(it+1)
+            __syncthreads();
+            if (t >= 1 && t + 1 < n_my) issue_half(t_begin + t + 1, (t + 1) % S, 1);
+        };
+        // opens the slot of phase B(t): V(t) has landed (younger requests: K(t+1), V(t+1)); K(t+2) may be requested
+        auto open_b = [&](int t) __attribute__((always_inline)) {
+            if (t >= 0 && t < n_my) {
+                if (t + 1 < n_my) wait_vmcnt<PER>();
                 else wait_vmcnt<0>();
             }
-            __syncthreads();                                   // every wave holds its K operands; V(it) is complete
-            if (it + 2 < n_my) issue_half(t_begin + it + 2, it % S, 0);     // K(it+2)
-            if (!live) return;
-            mask_tile(it, s);
+            __syncthreads();
+            if (t >= 0 && t + 2 < n_my) issue_half(t_begin + t + 2, t % S, 0);
+        };
+        auto phase_a = [&](int t) __attribute__((always_inline)) {
+            bf16x8 ka[8];        // all eight reads are requested before the first product (no read waits on a product)
+            read_k(t, ka);
+            __builtin_amdgcn_sched_barrier(0);
+            score_tile(ka, s);
+        };
+        auto phase_b = [&](int t) __attribute__((always_inline)) {
+            mask_tile(t, s);
             const float tmax = tile_max(s);
-            if (it == 0) {
+            if (t == 0) {
                 m_run = tmax;                          // nothing accumulated yet: adopt the tile's max as the reference
             } else if (__any(tmax > m_run + kTau)) {
                 // rare: bring O up to date with the pending product, then rescale it to the new reference
-                pv_mfma(va_in, pb_in);
+                pv_mfma(va, pb);
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                    for (int x = 0; x < 8; ++x) pb_in[ks][x] = (__bf16)0.f;
+                    for (int x = 0; x < 8; ++x) pb[ks][x] = (__bf16)0.f;
                 rescale(tmax > m_run + kTau, tmax);
             }
-            // previous tile's O^T += V^T P^T (matrix pipe) next to this tile's exponentials (vector ALU)
-            pv_mfma(va_in, pb_in);
-            probabilities(s, pb_out);
-            read_v(it, va_out);                        // this tile's V^T operands, used one round later
+            pv_mfma(va, pb);                           // previous tile's product (matrix pipe) ...
+            probabilities(s, pb);                      // ... next to this tile's exponentials (vector ALU)
+            read_v(t, va);                             // this tile's V^T operands, used one tile later
         };
-        if (1 < n_my) issue_half(t_begin + 1, 1, 0);   // K(1): the Q staging area is free
-        for (int it = 0; it < n_iter; it += 2) {
-            tile_round(it, va_a, pb_a, va_b, pb_b);
-            if (it + 1 < n_iter) tile_round(it + 1, va_b, pb_b, va_a, pb_a);
+        if ((wave >> 2) == 0) {
+            for (int t = 0; t < n_iter; ++t) {
+                open_a(t);
+                if (t < n_my) phase_a(t);
+                open_b(t);
+                if (t < n_my) phase_b(t);
+            }
+            __syncthreads();
+        } else {
+            for (int t = 0; t < n_iter; ++t) {
+                open_b(t - 1);
+                if (t >= 1 && t - 1 < n_my) phase_b(t - 1);
+                open_a(t);
+                if (t < n_my) phase_a(t);
+            }
+            open_b(n_iter - 1);
+            if (n_iter - 1 < n_my) phase_b(n_iter - 1);
         }
-        // the last tile's product: its operands are in set b after an odd number of tiles, else in set a
-        if (n_my & 1) pv_mfma(va_b, pb_b);
-        else pv_mfma(va_a, pb_a);
+        pv_mfma(va, pb);         // the last tile's product
     } else {
         // Waves that share one or two key streams (eight or four stages) take a tile in two phases, in two barrier
         // slots: phase A = K operands and the score products; phase B = V^T operands (requested first), mask,
