@@ -138,6 +138,14 @@ def main() -> int:
     def accept_greedy():
         tv.tree_accept(gdesc, gtl, None, gtoken, aparent, None, ca, path, o_n, o_tok, o_kind, o_last, o_con, o_st, cws)
 
+    # the same call with the logits handed over as bf16 (the LM head's output type in a bf16 model)
+    bdesc = tv.make_accept_desc(B=1, T=acc.T, V=acc.V, C=acc.C, rule=acc.rule, temperature=acc.temperature,
+                                logits_dtype=tv.TV_DTYPE_BF16)
+    tl16 = tl.to(torch.bfloat16)
+
+    def accept_bf16():
+        tv.tree_accept(bdesc, tl16, None, token, aparent, un, ca, path, o_n, o_tok, o_kind, o_last, o_con, o_st, cws)
+
     def full_step():
         attention_layers()
         accept()
@@ -180,6 +188,7 @@ def main() -> int:
     ms_attn = timed(attention_layers, args.steps, args.warmup)
     ms_accept = timed(accept, args.steps * 4, args.warmup)
     ms_greedy = timed(accept_greedy, args.steps * 4, args.warmup)
+    ms_accept16 = timed(accept_bf16, args.steps * 4, args.warmup)
     us_layer = ms_attn * 1e3 / L
 
     # ---- the steps around the pass: commit of the accepted path (all layers, one call), contemplate embedding -----
@@ -261,7 +270,8 @@ def main() -> int:
         "achieved_gbps_on_moved": round(moved / (ms_accept * 1e-3) / 1e9, 1),
         "visited_rows": n_visit, "algorithmic_bytes": n_visit * acc.V * 4,
         "frac_of_hbm_peak_on_algorithmic": round(n_visit * acc.V * 4 / (ms_accept * 1e-3) / 1e9 / HBM_PEAK_GBPS, 5),
-        "greedy_us_per_step": round(ms_greedy * 1e3, 2)}
+        "greedy_us_per_step": round(ms_greedy * 1e3, 2),
+        "bf16_logits_us_per_step": round(ms_accept16 * 1e3, 2), "bf16_logits_bytes_moved": moved // 2}
 
     # ---- CPU oracle on the host cores, bounded sample: one of the 32 layers + three acceptance walks.  The same
     #      leg compares what the GPU produced with what the oracle says (the only place the oracle is used). ------

@@ -159,15 +159,16 @@ typedef struct tv_accept_desc {
     int32_t  rule;               /* TV_RULE_* */
     float    temperature;        /* > 0 unless rule = GREEDY */
     int64_t  logits_row_stride;  /* elements between consecutive rows of the logits; 0 = V */
-    int32_t  reserved[2];        /* must be 0 */
+    int32_t  logits_dtype;       /* element type of both logits matrices: TV_DTYPE_F32 (0) or TV_DTYPE_BF16 */
+    int32_t  reserved;           /* must be 0 */
 } tv_accept_desc;
 
 int tv_accept_workspace_bytes(const tv_accept_desc* desc, size_t* out_bytes);
 
 int tree_accept(
     const tv_accept_desc* desc,     /* host */
-    const float*   target_logits,   /* device [B, T, V] fp32 (rows logits_row_stride apart) */
-    const float*   draft_logits,    /* device [B, T, V] fp32; required by the DRAFT rules, else NULL */
+    const void*    target_logits,   /* device [B, T, V], logits_dtype (rows logits_row_stride elements apart) */
+    const void*    draft_logits,    /* device [B, T, V], logits_dtype; required by the DRAFT rules, else NULL */
     const int32_t* token,           /* device [B, T]: token drafted at each node (token[0]: the root's) */
     const int32_t* parent,          /* device [B, T]: parent node, -1 for the root, parent[i] < i */
     const float*   uniforms,        /* device [B, 2T]: u[c] tests node c, u[T+n] draws the final token at stop node n; unused by GREEDY (may be NULL) */

@@ -49,7 +49,7 @@ class tv_accept_desc(ctypes.Structure):
         ("struct_size", ctypes.c_uint32), ("B", ctypes.c_int32), ("T", ctypes.c_int32),
         ("V", ctypes.c_int32), ("C", ctypes.c_int32), ("rule", ctypes.c_int32),
         ("temperature", ctypes.c_float), ("logits_row_stride", ctypes.c_int64),
-        ("reserved", ctypes.c_int32 * 2),
+        ("logits_dtype", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -133,9 +133,9 @@ def make_attn_desc(*, dtype: int, B: int, M: int, Hq: int, Hkv: int, D: int, sof
 
 
 def make_accept_desc(*, B: int, T: int, V: int, C: int, rule: int, temperature: float,
-                     logits_row_stride: int = 0) -> tv_accept_desc:
+                     logits_row_stride: int = 0, logits_dtype: int = 0) -> tv_accept_desc:
     return tv_accept_desc(ctypes.sizeof(tv_accept_desc), B, T, V, C, rule, temperature, logits_row_stride,
-                          (ctypes.c_int32 * 2)(0, 0))
+                          logits_dtype, 0)
 
 
 def tv_attention_workspace_bytes(desc: tv_attn_desc) -> int:

@@ -84,6 +84,27 @@ __device__ __forceinline__ void red_push4(Red& r, const float4 x, int v0, float 
 
 __device__ __forceinline__ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
+// One row of a logits matrix: fp32 elements, or bf16 (the upper half of the fp32 with the same value).
+struct Row {
+    const void* p;
+    bool bf16;
+    __device__ __forceinline__ float operator[](int v) const {
+        return bf16 ? __uint_as_float((unsigned)static_cast<const unsigned short*>(p)[v] << 16)
+                    : static_cast<const float*>(p)[v];
+    }
+    // entries 4k .. 4k+3 can be fetched with one load (16 bytes of fp32, 8 bytes of bf16)
+    __device__ __forceinline__ bool quad_aligned() const {
+        return (reinterpret_cast<uintptr_t>(p) & (bf16 ? 7 : 15)) == 0;
+    }
+};
+__device__ __forceinline__ Row logits_row(const AcceptArgs& a, const void* mat, int b, int node) {
+    const int64_t e = ((int64_t)b * a.T + node) * a.row_stride;
+    return Row{static_cast<const unsigned char*>(mat) + e * (a.logits_bf16 ? 2 : 4), a.logits_bf16 != 0};
+}
+// the two bf16 values of one 32-bit word, in memory order
+__device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
+
 // ---- 1. statistics -----------------------------------------------------------------------------------
 template <bool kGreedy>
 __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a) {
@@ -101,29 +122,53 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a
         unsigned long long* parts = a.chain_parts + ((int64_t)b * a.T + row) * 2 * a.chain_slices;
         for (int i = threadIdx.x; i < 2 * a.chain_slices; i += kStatThreads) parts[i] = 3ull;
     }
-    const float* base = (mat == 0 ? a.target : a.draft) + ((int64_t)b * a.T + row) * a.row_stride;
+    const Row lrow = logits_row(a, mat == 0 ? a.target : a.draft, b, row);
     const int begin = split * a.split_len;
     const int end = min(a.V, begin + a.split_len);
     const float it = kGreedy ? 0.f : kLog2e / a.temperature;
 
     Red r{-INFINITY, 0x7fffffff, 0.0};
     int v = begin;
-    if (aligned16(base + begin)) {
-        const int n4 = (end - begin) / 4;
-        const float4* b4 = reinterpret_cast<const float4*>(base + begin);
-        int i = threadIdx.x;
-        for (; i + 3 * kStatThreads < n4; i += 4 * kStatThreads) {      // four loads in flight per lane
-            const float4 x0 = b4[i], x1 = b4[i + kStatThreads], x2 = b4[i + 2 * kStatThreads],
-                         x3 = b4[i + 3 * kStatThreads];
-            red_push4<kGreedy>(r, x0, begin + 4 * i, it);
-            red_push4<kGreedy>(r, x1, begin + 4 * (i + kStatThreads), it);
-            red_push4<kGreedy>(r, x2, begin + 4 * (i + 2 * kStatThreads), it);
-            red_push4<kGreedy>(r, x3, begin + 4 * (i + 3 * kStatThreads), it);
+    if (!lrow.bf16) {
+        const float* base = static_cast<const float*>(lrow.p);
+        if (aligned16(base + begin)) {
+            const int n4 = (end - begin) / 4;
+            const float4* b4 = reinterpret_cast<const float4*>(base + begin);
+            int i = threadIdx.x;
+            for (; i + 3 * kStatThreads < n4; i += 4 * kStatThreads) {      // four loads in flight per lane
+                const float4 x0 = b4[i], x1 = b4[i + kStatThreads], x2 = b4[i + 2 * kStatThreads],
+                             x3 = b4[i + 3 * kStatThreads];
+                red_push4<kGreedy>(r, x0, begin + 4 * i, it);
+                red_push4<kGreedy>(r, x1, begin + 4 * (i + kStatThreads), it);
+                red_push4<kGreedy>(r, x2, begin + 4 * (i + 2 * kStatThreads), it);
+                red_push4<kGreedy>(r, x3, begin + 4 * (i + 3 * kStatThreads), it);
+            }
+            for (; i < n4; i += kStatThreads) red_push4<kGreedy>(r, b4[i], begin + 4 * i, it);
+            v = begin + 4 * n4;
         }
-        for (; i < n4; i += kStatThreads) red_push4<kGreedy>(r, b4[i], begin + 4 * i, it);
-        v = begin + 4 * n4;
+    } else {
+        const unsigned short* base = static_cast<const unsigned short*>(lrow.p);
+        if (aligned16(base + begin)) {                                      // eight entries per 16-byte load
+            const int n8 = (end - begin) / 8;
+            const uint4* b8 = reinterpret_cast<const uint4*>(base + begin);
+            auto push8 = [&](const uint4 x, int v0) {
+                red_push4<kGreedy>(r, make_float4(bf16_lo(x.x), bf16_hi(x.x), bf16_lo(x.y), bf16_hi(x.y)), v0, it);
+                red_push4<kGreedy>(r, make_float4(bf16_lo(x.z), bf16_hi(x.z), bf16_lo(x.w), bf16_hi(x.w)), v0 + 4, it);
+            };
+            int i = threadIdx.x;
+            for (; i + 3 * kStatThreads < n8; i += 4 * kStatThreads) {      // four loads in flight per lane
+                const uint4 x0 = b8[i], x1 = b8[i + kStatThreads], x2 = b8[i + 2 * kStatThreads],
+                            x3 = b8[i + 3 * kStatThreads];
+                push8(x0, begin + 8 * i);
+                push8(x1, begin + 8 * (i + kStatThreads));
+                push8(x2, begin + 8 * (i + 2 * kStatThreads));
+                push8(x3, begin + 8 * (i + 3 * kStatThreads));
+            }
+            for (; i < n8; i += kStatThreads) push8(b8[i], begin + 8 * i);
+            v = begin + 8 * n8;
+        }
     }
-    for (int i = v + threadIdx.x; i < end; i += kStatThreads) red_push<kGreedy>(r, base[i], i, it);
+    for (int i = v + threadIdx.x; i < end; i += kStatThreads) red_push<kGreedy>(r, lrow[i], i, it);
 
     // wave reduction: the maximum (lowest index on ties) first, then one rescale per lane and a plain sum
     float wm = r.m;
@@ -245,10 +290,15 @@ constexpr int kChainQuads = kChainPer / 4;
 
 // Four consecutive logits of a row (entries past the end of the row read as -infinity, which the
 // laws map to zero mass).
-__device__ __forceinline__ void load_quad(const float* row, bool vec_ok, int v, int V, float* dst) {
+__device__ __forceinline__ void load_quad(const Row& row, bool vec_ok, int v, int V, float* dst) {
     if (vec_ok && v + 3 < V) {
-        const float4 x = *reinterpret_cast<const float4*>(row + v);
-        dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
+        if (row.bf16) {
+            const uint2 x = *reinterpret_cast<const uint2*>(static_cast<const unsigned short*>(row.p) + v);
+            dst[0] = bf16_lo(x.x); dst[1] = bf16_hi(x.x); dst[2] = bf16_lo(x.y); dst[3] = bf16_hi(x.y);
+        } else {
+            const float4 x = *reinterpret_cast<const float4*>(static_cast<const float*>(row.p) + v);
+            dst[0] = x.x; dst[1] = x.y; dst[2] = x.z; dst[3] = x.w;
+        }
     } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e) dst[e] = (v + e < V) ? row[v + e] : -INFINITY;
@@ -331,9 +381,8 @@ __global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs 
         __syncthreads();
         const Red sp = s_stat[0], sq = s_stat[1];
         const double inv_sp = 1.0 / sp.s, inv_sq = 1.0 / sq.s;
-        const float* prow = a.target + ((int64_t)b * T + u) * a.row_stride;
-        const float* qrow = a.draft + ((int64_t)b * T + u) * a.row_stride;
-        const bool vec_ok = aligned16(prow) && aligned16(qrow);
+        const Row prow = logits_row(a, a.target, b, u), qrow = logits_row(a, a.draft, b, u);
+        const bool vec_ok = prow.quad_aligned() && qrow.quad_aligned();
         __shared__ float s_zp[kMaxRows], s_zq[kMaxRows], s_u[kMaxRows];      // per child: its token's logits, its uniform
         if (tid < k) {
             const int c = s_child[tid];
@@ -484,7 +533,7 @@ __global__ __launch_bounds__(kDrawThreads) void accept_sample_kernel(AcceptArgs 
     __syncthreads();
 
     // the chosen range, contiguous runs per lane in vocabulary order
-    const float* row = a.target + ((int64_t)b * T + i) * a.row_stride;
+    const Row row = logits_row(a, a.target, b, i);
     const int begin = s_split * a.split_len, end = min(V, begin + a.split_len);
     const int per = (end - begin + kDrawThreads - 1) / kDrawThreads;
     const int v0 = begin + tid * per, v1 = min(end, v0 + per);
@@ -550,7 +599,7 @@ struct WalkShared {
 // final law over the run and the last entry that carries mass.  kFind = true: the running sum starts at
 // *mass and the first entry at which it exceeds u is returned in *found (-1 if none).
 template <int kRule, bool kFind>
-__device__ __forceinline__ void segment_scan(const WalkShared& sh, const float* prow, const float* qrow,
+__device__ __forceinline__ void segment_scan(const WalkShared& sh, const Row& prow, const Row& qrow,
                                              bool vec_ok, int node, int v0, int quads, int V, float it,
                                              double u, double* mass, int* last, int* found) {
     constexpr bool kDraft = (kRule == TV_RULE_DRAFT_WOR || kRule == TV_RULE_DRAFT_WR);
@@ -660,10 +709,9 @@ __device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared&
         }
         if (!kGreedy)
             for (int i = 1 + tid; i < T; i += kDrawThreads) {
-                const int64_t r = ((int64_t)b * T + sh.parent[i]) * a.row_stride + sh.token[i];
-                sh.z_tok_p[i] = a.target[r];
+                sh.z_tok_p[i] = logits_row(a, a.target, b, sh.parent[i])[sh.token[i]];
                 if (kDraft) {                          // what the chain kernel left for this node
-                    sh.z_tok_q[i] = a.draft[r];
+                    sh.z_tok_q[i] = logits_row(a, a.draft, b, sh.parent[i])[sh.token[i]];
                     sh.abit[i] = a.accept_bit[(int64_t)b * T + i];
                     sh.chain_z[i] = a.chain_z[(int64_t)b * T + i];
                 }
@@ -737,9 +785,9 @@ __device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared&
         if (tid == 0) sh.tok_out = sh.argmax[cur];       // launched with one workgroup per sequence
     } else {
         // ---- inverse CDF at the stop node: first v whose running sum of the law exceeds u --------
-        const float* prow = a.target + ((int64_t)b * T + cur) * a.row_stride;
-        const float* qrow = kDraft ? a.draft + ((int64_t)b * T + cur) * a.row_stride : prow;
-        const bool vec_ok = aligned16(prow) && aligned16(qrow);
+        const Row prow = logits_row(a, a.target, b, cur);
+        const Row qrow = kDraft ? logits_row(a, a.draft, b, cur) : prow;
+        const bool vec_ok = prow.quad_aligned() && qrow.quad_aligned();
         const double u = (double)sh.unif[T + cur];
         const int quads = a.slice_len / (4 * kDrawThreads);     // quads of entries per lane, contiguous
         unsigned long long* slots = a.slice_bits + (int64_t)b * kMaxSlices;
@@ -903,7 +951,7 @@ int plan_accept(const tv_accept_desc& d, AcceptPlan* plan) {
     if (splits < 1) splits = 1;
     if (splits > 64) splits = 64;
     int len = (d.V + splits - 1) / splits;
-    len = (len + 3) / 4 * 4;
+    len = (len + 7) / 8 * 8;          // ranges start on a 16-byte boundary of an aligned row (fp32 and bf16)
     p.splits = (d.V + len - 1) / len;
     p.split_len = len;
     // the final draw: at most kMaxSlices slices, each a whole number of quads per lane

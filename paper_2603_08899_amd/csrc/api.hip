@@ -201,7 +201,8 @@ static int check_accept_desc(const tv_accept_desc* d) {
     if (d->rule < TV_RULE_GREEDY || d->rule > TV_RULE_SAMPLE_MATCH) return TV_ERR_INVALID_ARG;
     if (d->rule != TV_RULE_GREEDY && !(d->temperature > 0.f)) return TV_ERR_INVALID_ARG;
     if (d->logits_row_stride != 0 && d->logits_row_stride < d->V) return TV_ERR_INVALID_ARG;
-    if (d->reserved[0] != 0 || d->reserved[1] != 0) return TV_ERR_INVALID_ARG;
+    if (d->logits_dtype != TV_DTYPE_F32 && d->logits_dtype != TV_DTYPE_BF16) return TV_ERR_INVALID_ARG;
+    if (d->reserved != 0) return TV_ERR_INVALID_ARG;
     if ((int64_t)d->B * d->T > 65535) return TV_ERR_INVALID_ARG;       // grid dimension limits
     return TV_OK;
 }
@@ -216,7 +217,7 @@ int tv_accept_workspace_bytes(const tv_accept_desc* desc, size_t* out_bytes) {
     return TV_OK;
 }
 
-int tree_accept(const tv_accept_desc* desc, const float* target_logits, const float* draft_logits,
+int tree_accept(const tv_accept_desc* desc, const void* target_logits, const void* draft_logits,
                 const int32_t* token, const int32_t* parent, const float* uniforms, const int32_t* con_anchor,
                 int32_t* path, int32_t* n_accepted, int32_t* final_token, int32_t* final_kind,
                 int32_t* last_node, int32_t* selected_con, int32_t* status, void* workspace,
@@ -235,6 +236,7 @@ int tree_accept(const tv_accept_desc* desc, const float* target_logits, const fl
     if (!workspace || workspace_bytes < p.total_bytes || ((uintptr_t)workspace & 255)) return TV_ERR_WORKSPACE;
     AcceptArgs a{};
     a.target = target_logits; a.draft = draft_rule ? draft_logits : nullptr;
+    a.logits_bf16 = (desc->logits_dtype == TV_DTYPE_BF16) ? 1 : 0;
     a.token = token; a.parent = parent; a.uniforms = uniforms; a.con_anchor = con_anchor;
     a.path = path; a.n_accepted = n_accepted; a.final_token = final_token; a.final_kind = final_kind;
     a.last_node = last_node; a.selected_con = selected_con; a.status = status;

@@ -73,8 +73,9 @@ constexpr int kMaxSlices = 128;      // a multiple of the wave size
 int plan_accept(const tv_accept_desc& d, AcceptPlan* plan);
 
 struct AcceptArgs {
-    const float* target;
-    const float* draft;
+    const void* target;   // [B][T] rows of V logits, row_stride elements apart: fp32, or bf16 when logits_bf16
+    const void* draft;
+    int logits_bf16;
     const int32_t* token;
     const int32_t* parent;
     const float* uniforms;

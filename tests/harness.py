@@ -76,20 +76,39 @@ def oracle_attention_rows(inp: AttnInputs, b: int, rows, heads):
     return outs
 
 
-def run_accept(inp: AcceptInputs, *, row_stride: int = 0):
+def logits_rounded_to_bf16(inp: AcceptInputs) -> AcceptInputs:
+    """The same case with both logits matrices rounded to bf16 values (kept as float32): what the oracle is
+    given when the HIP path reads bf16 logits, so that both sides see identical numbers."""
+    import dataclasses
+    from synth_inputs import f32_to_bf16_bits
+
+    def rnd(a):
+        return None if a is None else bf16_bits_to_f32(f32_to_bf16_bits(np.asarray(a, dtype=np.float32)))
+    return dataclasses.replace(inp, target_logits=rnd(inp.target_logits), draft_logits=rnd(inp.draft_logits))
+
+
+def run_accept(inp: AcceptInputs, *, row_stride: int = 0, logits_dtype: str = "f32"):
+    """logits_dtype 'bf16': the logits (which must hold bf16 values, see logits_rounded_to_bf16) are handed
+    over as bf16."""
     import paper_2603_08899_amd as tv
     torch = _torch()
+    bf16 = logits_dtype == "bf16"
     desc = tv.make_accept_desc(B=inp.B, T=inp.T, V=inp.V, C=inp.C, rule=inp.rule,
-                               temperature=inp.temperature, logits_row_stride=row_stride)
+                               temperature=inp.temperature, logits_row_stride=row_stride,
+                               logits_dtype=tv.TV_DTYPE_BF16 if bf16 else tv.TV_DTYPE_F32)
+    ldt = torch.bfloat16 if bf16 else torch.float32
 
     def logits_dev(a):
         if a is None:
             return None
+        x = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        if bf16:
+            assert torch.equal(x.to(ldt).to(torch.float32), x), "logits are not bf16 values"
         if row_stride:
-            buf = torch.full((inp.B, inp.T, row_stride), float("nan"), device="cuda", dtype=torch.float32)
-            buf[:, :, :inp.V] = torch.from_numpy(a).cuda()
+            buf = torch.full((inp.B, inp.T, row_stride), float("nan"), device="cuda", dtype=ldt)
+            buf[:, :, :inp.V] = x.to(ldt)
             return buf
-        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        return x.to(ldt)
 
     tl = logits_dev(inp.target_logits)
     dl = logits_dev(inp.draft_logits)

@@ -179,3 +179,29 @@ def test_sample_and_match_full_vocabulary_and_padded_rows():
     # batch of eight at full size
     b8 = dataclasses.replace(si.accept_case(3, 0, child_boost=5.0), rule=RULES["match"])
     _run_and_compare(b8)
+
+
+# ---- bf16 logits ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("rule", ["greedy", "det", "wor", "wr", "match"])
+def test_bf16_logits_many_small_sequences(rule):
+    """The logits handed over as bf16; the oracle gets the same bf16 values (exact in fp32/fp64).  bf16 logits
+    tie often (8 mantissa bits), which exercises the lowest-index rules."""
+    temp = 0.0 if rule == "greedy" else 1.0
+    inp = H.logits_rounded_to_bf16(_batch(41, B=128, T=24, V=5003, rule=RULES[rule], temp=temp, C=3, boost=7.0))
+    got = _run_and_compare(inp, logits_dtype="bf16")
+    assert got["n_accepted"].max() >= 2
+
+
+def test_bf16_logits_padded_and_unaligned_rows():
+    inp = H.logits_rounded_to_bf16(_batch(42, B=4, T=20, V=3001, rule=RULES["wor"], temp=0.7))
+    _run_and_compare(inp, row_stride=3008, logits_dtype="bf16")
+    _run_and_compare(inp, row_stride=3003, logits_dtype="bf16")     # rows not 8-byte aligned: scalar loads
+    _run_and_compare(inp, row_stride=3004, logits_dtype="bf16")     # 8-byte but not 16-byte aligned rows
+
+
+@pytest.mark.parametrize("index,mode,boost", [(2, 0, 5.0), (2, 1, 5.0), (4, 0, 5.0), (1, 0, 0.0)])
+def test_bf16_logits_full_vocabulary(index, mode, boost):
+    inp = H.logits_rounded_to_bf16(si.accept_case(index, mode, draft_target_corr=0.9 if index != 2 else 0.0,
+                                                  child_boost=boost))
+    got = _run_and_compare(inp, logits_dtype="bf16")
+    print("accepted", int(got["n_accepted"][0]))
