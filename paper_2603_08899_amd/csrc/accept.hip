@@ -82,6 +82,40 @@ __device__ __forceinline__ void red_push4(Red& r, const float4 x, int v0, float 
     }
 }
 
+// A batch of quads held in registers, quads in increasing vocabulary order (quad k starts at entry v0[k]; k
+// with live[k] false holds nothing): the running maximum is raised once for the whole batch, so the fp64 rescale
+// of the running sum - a long instruction sequence that a wave executes whenever any of its lanes needs it -
+// runs once per batch, not once per quad.
+template <bool kGreedy, int N>
+__device__ __forceinline__ void red_push_batch(Red& r, const float4 (&x)[N], const int (&v0)[N], const bool (&live)[N],
+                                               float it) {
+    float bm = -INFINITY;
+    int bam = 0x7fffffff;
+#pragma unroll
+    for (int k = 0; k < N; ++k) {
+        const float mx = fmaxf(fmaxf(x[k].x, x[k].y), fmaxf(x[k].z, x[k].w));
+        if (live[k] && mx > bm) {            // strictly greater: the lowest index wins ties
+            bm = mx;
+            bam = (x[k].x == mx) ? v0[k] : (x[k].y == mx) ? v0[k] + 1 : (x[k].z == mx) ? v0[k] + 2 : v0[k] + 3;
+        }
+    }
+    if (bm > r.m) {
+        if (!kGreedy && r.s != 0.0) r.s *= exp2((double)(r.m - bm) * (double)it);
+        r.m = bm;
+        r.am = bam;
+    }
+    if (!kGreedy) {
+#pragma unroll
+        for (int k = 0; k < N; ++k)
+            if (live[k]) {
+                r.s += unnorm_prob(x[k].x, r.m, it);
+                r.s += unnorm_prob(x[k].y, r.m, it);
+                r.s += unnorm_prob(x[k].z, r.m, it);
+                r.s += unnorm_prob(x[k].w, r.m, it);
+            }
+    }
+}
+
 __device__ __forceinline__ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 // One row of a logits matrix: fp32 elements, or bf16 (the upper half of the fp32 with the same value).
@@ -129,42 +163,54 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a
 
     Red r{-INFINITY, 0x7fffffff, 0.0};
     int v = begin;
+    // Vector part: every lane requests a batch of 16-byte pieces before it uses the first (a range of the usual
+    // size is one or two batches, so the workgroup pays few memory round trips).
+    constexpr int kInFlight = 4;
     if (!lrow.bf16) {
         const float* base = static_cast<const float*>(lrow.p);
         if (aligned16(base + begin)) {
             const int n4 = (end - begin) / 4;
             const float4* b4 = reinterpret_cast<const float4*>(base + begin);
-            int i = threadIdx.x;
-            for (; i + 3 * kStatThreads < n4; i += 4 * kStatThreads) {      // four loads in flight per lane
-                const float4 x0 = b4[i], x1 = b4[i + kStatThreads], x2 = b4[i + 2 * kStatThreads],
-                             x3 = b4[i + 3 * kStatThreads];
-                red_push4<kGreedy>(r, x0, begin + 4 * i, it);
-                red_push4<kGreedy>(r, x1, begin + 4 * (i + kStatThreads), it);
-                red_push4<kGreedy>(r, x2, begin + 4 * (i + 2 * kStatThreads), it);
-                red_push4<kGreedy>(r, x3, begin + 4 * (i + 3 * kStatThreads), it);
+            for (int i0 = threadIdx.x; i0 < n4; i0 += kInFlight * kStatThreads) {
+                float4 x[kInFlight];
+                int v0[kInFlight];
+                bool live[kInFlight];
+#pragma unroll
+                for (int k = 0; k < kInFlight; ++k) {
+                    const int i = i0 + k * kStatThreads;
+                    live[k] = i < n4;
+                    v0[k] = begin + 4 * i;
+                    x[k] = b4[live[k] ? i : i0];
+                }
+                red_push_batch<kGreedy, kInFlight>(r, x, v0, live, it);
             }
-            for (; i < n4; i += kStatThreads) red_push4<kGreedy>(r, b4[i], begin + 4 * i, it);
             v = begin + 4 * n4;
         }
     } else {
         const unsigned short* base = static_cast<const unsigned short*>(lrow.p);
-        if (aligned16(base + begin)) {                                      // eight entries per 16-byte load
+        if (aligned16(base + begin)) {                                      // eight entries per 16-byte piece
             const int n8 = (end - begin) / 8;
             const uint4* b8 = reinterpret_cast<const uint4*>(base + begin);
-            auto push8 = [&](const uint4 x, int v0) {
-                red_push4<kGreedy>(r, make_float4(bf16_lo(x.x), bf16_hi(x.x), bf16_lo(x.y), bf16_hi(x.y)), v0, it);
-                red_push4<kGreedy>(r, make_float4(bf16_lo(x.z), bf16_hi(x.z), bf16_lo(x.w), bf16_hi(x.w)), v0 + 4, it);
-            };
-            int i = threadIdx.x;
-            for (; i + 3 * kStatThreads < n8; i += 4 * kStatThreads) {      // four loads in flight per lane
-                const uint4 x0 = b8[i], x1 = b8[i + kStatThreads], x2 = b8[i + 2 * kStatThreads],
-                            x3 = b8[i + 3 * kStatThreads];
-                push8(x0, begin + 8 * i);
-                push8(x1, begin + 8 * (i + kStatThreads));
-                push8(x2, begin + 8 * (i + 2 * kStatThreads));
-                push8(x3, begin + 8 * (i + 3 * kStatThreads));
+            for (int i0 = threadIdx.x; i0 < n8; i0 += kInFlight * kStatThreads) {
+                uint4 y[kInFlight];
+                float4 x[2 * kInFlight];
+                int v0[2 * kInFlight];
+                bool live[2 * kInFlight];
+#pragma unroll
+                for (int k = 0; k < kInFlight; ++k) {
+                    const int i = i0 + k * kStatThreads;
+                    live[2 * k] = live[2 * k + 1] = i < n8;
+                    v0[2 * k] = begin + 8 * i;
+                    v0[2 * k + 1] = begin + 8 * i + 4;
+                    y[k] = b8[i < n8 ? i : i0];
+                }
+#pragma unroll
+                for (int k = 0; k < kInFlight; ++k) {
+                    x[2 * k] = make_float4(bf16_lo(y[k].x), bf16_hi(y[k].x), bf16_lo(y[k].y), bf16_hi(y[k].y));
+                    x[2 * k + 1] = make_float4(bf16_lo(y[k].z), bf16_hi(y[k].z), bf16_lo(y[k].w), bf16_hi(y[k].w));
+                }
+                red_push_batch<kGreedy, 2 * kInFlight>(r, x, v0, live, it);
             }
-            for (; i < n8; i += kStatThreads) push8(b8[i], begin + 8 * i);
             v = begin + 8 * n8;
         }
     }
@@ -484,92 +530,132 @@ __global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs 
     }   // next node of this group
 }
 
-// ---- 2b. the target's own token at every node (sample-and-match rule) ---------------------------------------
-// Grid (T, B): one workgroup draws, for one node, the token that plain sampling of the target would emit there:
-// inverse CDF of softmax(target row / temperature) at the node's uniform u[T + node].  The row's ranges (already
-// reduced by the statistics kernel) locate the range that holds the crossing; only that range is read again.
-__global__ __launch_bounds__(kDrawThreads) void accept_sample_kernel(AcceptArgs a) {
-    const int i = blockIdx.x, b = blockIdx.y;
+// ---- 2b. inverse CDF at one node from the row's reduced ranges ------------------------------------------------
+constexpr int kDrawQuads = 8;     // quads of entries a lane of range_draw requests at once: 8192 entries per workgroup
+struct DrawScratch {              // shared memory of range_draw
+    double wave_tot[kDrawWaves];
+    double base, inv_total;
+    float row_max;
+    int split, hit, last, tok;
+};
+
+// The first v whose running sum of softmax(target row / temperature) at `node` exceeds u.  The sums of the row's
+// ranges, left by the statistics kernel, locate the range that holds the crossing, and only that range is read
+// again - by one workgroup, without any hand-off between workgroups.  Every thread of the workgroup calls this
+// and gets the token (-1: the law has no mass at all).
+__device__ __forceinline__ int range_draw(const AcceptArgs& a, DrawScratch& ds, int b, int node, double u, float it) {
     const int T = a.T, V = a.V;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const float it = kLog2e / a.temperature;
-    __shared__ double s_wave_tot[kDrawWaves];
-    __shared__ double s_base, s_inv_total;
-    __shared__ float s_max;
-    __shared__ int s_split, s_hit, s_last, s_tok;
-    const double u = (double)a.uniforms[(int64_t)b * 2 * T + T + i];
-    const RowStat* st = a.stats + (((int64_t)b * a.n_mat) * T + i) * a.splits;
-
+    const RowStat* st = a.stats + (((int64_t)b * a.n_mat) * T + node) * a.splits;
     if (wave == 0) {
-        // mass of every range relative to the row's maximum (a lane owns the ranges lane, lane + 64, ... but there
-        // are at most 64), prefix sum in range order, first range whose running sum exceeds u
+        // mass of every range relative to the row's maximum (there are at most 64 ranges: one per lane)
         const bool live = lane < a.splits;
         const float ms = live ? st[lane].max_logit : -INFINITY;
         const float m = wave_max(ms);
-        const double mass = live ? ((ms == m) ? st[lane].sum_exp : st[lane].sum_exp * unnorm_prob(ms, m, it)) : 0.0;
+        double mass = live ? ((ms == m) ? st[lane].sum_exp : st[lane].sum_exp * unnorm_prob(ms, m, it)) : 0.0;
+        const double inv_total = 1.0 / wave_sum(mass);
+        mass *= inv_total;
+        // prefix sum in range order, first range whose running sum exceeds u
         double inc = mass;
 #pragma unroll
         for (int o = 1; o < kWave; o <<= 1) {
             const double t = __shfl_up(inc, o, kWave);
             if (lane >= o) inc += t;
         }
-        const double total = __shfl(inc, kWave - 1, kWave);
-        const double inv_total = 1.0 / total;
-        const unsigned long long cross = __ballot(live && inc * inv_total > u);
+        const unsigned long long cross = __ballot(live && inc > u);
         const unsigned long long has = __ballot(live && mass > 0.0);
         // (if rounding leaves the total at or below u: the last range that carries mass)
         const int split = cross ? __ffsll((long long)cross) - 1 : (has ? 63 - __builtin_clzll(has) : 0);
         const double before = __shfl(inc - mass, split, kWave);
         if (lane == 0) {
-            s_split = split;
-            s_base = before * inv_total;
-            s_inv_total = inv_total;
-            s_max = m;
-            s_hit = kDrawThreads;
-            s_last = -1;
-            s_tok = -1;
+            ds.split = split;
+            ds.base = before;
+            ds.inv_total = inv_total;
+            ds.row_max = m;
+            ds.hit = kDrawThreads;
+            ds.last = -1;
+            ds.tok = -1;
         }
     }
     __syncthreads();
 
-    // the chosen range, contiguous runs per lane in vocabulary order
-    const Row row = logits_row(a, a.target, b, i);
-    const int begin = s_split * a.split_len, end = min(V, begin + a.split_len);
-    const int per = (end - begin + kDrawThreads - 1) / kDrawThreads;
-    const int v0 = begin + tid * per, v1 = min(end, v0 + per);
-    const float m = s_max;
-    const double inv_total = s_inv_total;
-    double mine = 0.0;
-    int last = -1;
-    for (int v = v0; v < v1; ++v) {
-        const double pv = unnorm_prob(row[v], m, it) * inv_total;
-        mine += pv;
-        if (pv > 0.0) last = v;
-    }
-    if (last >= 0) atomicMax(&s_last, last);
+    // the chosen range, a contiguous run of quads per lane in vocabulary order.  A lane requests kDrawQuads quads
+    // before it uses the first; ranges are planned so that this is the whole run (plan_accept), longer ones
+    // (vocabularies beyond 64 x 8192 entries) take several such batches.
+    const Row row = logits_row(a, a.target, b, node);
+    const bool vec_ok = row.quad_aligned();
+    const int begin = ds.split * a.split_len, end = min(V, begin + a.split_len);
+    const int quads = (end - begin + 4 * kDrawThreads - 1) / (4 * kDrawThreads);
+    const int v0 = begin + tid * 4 * quads;
+    const float m = ds.row_max;
+    const double inv_total = ds.inv_total;
+    // find = false: mass of the lane's run and its last entry with mass; true: first entry at which `run` exceeds u
+    auto scan = [&](bool find, double run, int* last_out) {
+        int lst = -1, fnd = -1;
+        for (int g0 = 0; g0 < quads; g0 += kDrawQuads) {
+            float z[kDrawQuads][4];
+#pragma unroll
+            for (int g = 0; g < kDrawQuads; ++g) {
+                const int v = v0 + 4 * (g0 + g);
+                if (g0 + g < quads && v < end) {
+                    load_quad(row, vec_ok, v, end, z[g]);       // entries past the range read as -infinity: no mass
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) z[g][e] = -INFINITY;
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < kDrawQuads; ++g) {
+                const int v = v0 + 4 * (g0 + g);
+                double pv[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) pv[e] = unnorm_prob(z[g][e], m, it) * inv_total;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    run += pv[e];
+                    if (pv[e] > 0.0) lst = v + e;
+                    if (find && fnd < 0 && run > u) fnd = v + e;
+                }
+            }
+        }
+        *last_out = find ? ((fnd >= 0) ? fnd : lst) : lst;
+        return run;
+    };
+    int last;
+    const double mine = scan(false, 0.0, &last);
+    if (last >= 0) atomicMax(&ds.last, last);
     double inc = mine;
 #pragma unroll
     for (int o = 1; o < kWave; o <<= 1) {
         const double t = __shfl_up(inc, o, kWave);
         if (lane >= o) inc += t;
     }
-    if (lane == kWave - 1) s_wave_tot[wave] = inc;
+    if (lane == kWave - 1) ds.wave_tot[wave] = inc;
     __syncthreads();
-    double before = s_base;
-    for (int w = 0; w < wave; ++w) before += s_wave_tot[w];
-    if (before + inc > u) atomicMin(&s_hit, tid);
+    double before = ds.base;
+    for (int w = 0; w < wave; ++w) before += ds.wave_tot[w];
+    if (before + inc > u) atomicMin(&ds.hit, tid);
     __syncthreads();
-    if (tid == s_hit) {
-        double run = before + (inc - mine);
-        int found = -1;
-        for (int v = v0; v < v1 && found < 0; ++v) {
-            run += unnorm_prob(row[v], m, it) * inv_total;
-            if (run > u) found = v;
-        }
-        s_tok = (found >= 0) ? found : last;
+    if (tid == ds.hit) {
+        int tok;
+        scan(true, before + (inc - mine), &tok);
+        ds.tok = tok;
     }
     __syncthreads();
-    if (tid == 0) a.sampled[(int64_t)b * T + i] = (s_hit == kDrawThreads) ? s_last : s_tok;
+    // (no lane's running sum exceeds u: the range sums put the crossing here, the in-order sums round just below
+    //  it, or the total itself rounds to u or less - the last entry that carries mass)
+    return (ds.hit == kDrawThreads) ? ds.last : ds.tok;
+}
+
+// The target's own token at every node (sample-and-match rule).  Grid (T, B): one workgroup draws, for one node,
+// the token that plain sampling of the target would emit there: inverse CDF of softmax(target row /
+// temperature) at the node's uniform u[T + node].
+__global__ __launch_bounds__(kDrawThreads) void accept_sample_kernel(AcceptArgs a) {
+    const int i = blockIdx.x, b = blockIdx.y;
+    __shared__ DrawScratch ds;
+    const double u = (double)a.uniforms[(int64_t)b * 2 * a.T + a.T + i];
+    const int tok = range_draw(a, ds, b, i, u, kLog2e / a.temperature);
+    if (threadIdx.x == 0) a.sampled[(int64_t)b * a.T + i] = tok;
 }
 
 // ---- 3. walk + final draw ---------------------------------------------------------------------------------
@@ -943,11 +1029,14 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a)
 int plan_accept(const tv_accept_desc& d, AcceptPlan* plan) {
     AcceptPlan p{};
     p.n_mat = (d.rule == TV_RULE_DRAFT_WOR || d.rule == TV_RULE_DRAFT_WR) ? 2 : 1;
-    // about a thousand workgroups (four per CU), ranges no shorter than 4096 entries
+    // about a thousand workgroups (four per CU), ranges no shorter than 4096 entries and - so that a workgroup can
+    // hold one in registers when it looks for the crossing of a draw (range_draw) - no longer than 8192
     const int rows = d.B * d.T * p.n_mat;
     int splits = (1024 + rows - 1) / rows;
     const int max_splits = (d.V + 4095) / 4096;
+    const int min_splits = (d.V + kDrawQuads * 4 * kDrawThreads - 1) / (kDrawQuads * 4 * kDrawThreads);
     if (splits > max_splits) splits = max_splits;
+    if (splits < min_splits) splits = min_splits;
     if (splits < 1) splits = 1;
     if (splits > 64) splits = 64;
     int len = (d.V + splits - 1) / splits;
