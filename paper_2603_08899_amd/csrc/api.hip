@@ -60,7 +60,6 @@ int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
     if (d.dtype == TV_DTYPE_F32) {
         p.row_blocks = (d.M + 15) / 16;
         p.n_chunks = 1;
-        p.chunk_len = 0;
         p.total_bytes = 0;
         *plan = p;
         return TV_OK;
@@ -96,7 +95,6 @@ int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
     p.row_blocks = (rb_needed + p.rb_per_wg - 1) / p.rb_per_wg * p.rb_per_wg;
     const int n = chunks_for(p.rb_per_wg);
     p.n_chunks = n;
-    p.chunk_len = 0;
     if (n > 1) {
         const size_t blocks = (size_t)d.B * d.Hkv * p.row_blocks * n;
         p.part_o_bytes = up256(blocks * 64 * 128 * 2);       // bf16
@@ -189,7 +187,7 @@ int tree_verify_attention(const tv_attn_desc* desc, const void* q, const void* k
     a.inv_M = 1.0f / (float)desc->M;
     a.head_stride = desc->kv_head_stride ? desc->kv_head_stride : desc->D;
     a.tok_stride = desc->kv_token_stride ? desc->kv_token_stride : (int64_t)desc->Hkv * desc->D;
-    a.row_blocks = p.row_blocks; a.n_chunks = p.n_chunks; a.chunk_len = p.chunk_len; a.rb_per_wg = p.rb_per_wg;
+    a.row_blocks = p.row_blocks; a.n_chunks = p.n_chunks; a.rb_per_wg = p.rb_per_wg;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const hipError_t e = (desc->dtype == TV_DTYPE_F32) ? launch_attention_f32(a, s) : launch_attention_bf16(a, s);
     return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;

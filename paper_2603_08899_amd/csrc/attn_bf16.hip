@@ -282,26 +282,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(AttnArgs a) {
             sm.bits[tid][1] = w1;
         }
     }
-    if (bad) atomicOr(&sm.flag, bad);
-    __syncthreads();
-    bad = sm.flag;
-    if (bad_prefix) bad |= TV_STATUS_BAD_PREFIX;
-    if (blockIdx.x == 0 && tid == 0) a.status[b] = bad;
-    unsigned short* out16 = static_cast<unsigned short*>(a.out);
-    if (bad) {
-        if (a.n_chunks == 1) {       // otherwise the combine kernel writes the zeros
-            for (int idx = tid; idx < RB * kQRows * kD; idx += kThreads) {
-                const int r = rbg * RB * kQRows + idx / kD;
-                if (r < n_rows)
-                    out16[(((int64_t)b * M + r % M) * a.Hq + g * G + r / M) * kD + idx % kD] = 0;
-            }
-            for (int idx = tid; idx < RB * kQRows; idx += kThreads) {
-                const int r = rbg * RB * kQRows + idx;
-                if (a.lse && r < n_rows) a.lse[((int64_t)b * a.Hq + g * G + r / M) * M + r % M] = 0.f;
-            }
-        }
-        return;
-    }
+    if (bad) atomicOr(&sm.flag, bad);     // looked at after the next barrier (the one that follows the Q reads)
 
     // per-lane LDS offsets of the MFMA operands inside a tile
     // K (A operand of S^T): row ln, logical segment 2*ks + hf, stored at segment (2*ks + hf) ^ (ln & 15): the
@@ -330,7 +311,26 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(AttnArgs a) {
         const int r = min(row0 + ln, n_rows - 1);
         return r - (int)(((float)r + 0.5f) * a.inv_M) * M;             // r % M
     }();
-    __syncthreads();         // the Q staging area goes back to the ring
+    __syncthreads();         // the Q staging area goes back to the ring; every row's verdict is in sm.flag
+    bad = sm.flag;
+    if (bad_prefix) bad |= TV_STATUS_BAD_PREFIX;
+    if (blockIdx.x == 0 && tid == 0) a.status[b] = bad;
+    unsigned short* out16 = static_cast<unsigned short*>(a.out);
+    if (bad) {
+        if (a.n_chunks == 1) {       // otherwise the combine kernel writes the zeros
+            for (int idx = tid; idx < RB * kQRows * kD; idx += kThreads) {
+                const int r = rbg * RB * kQRows + idx / kD;
+                if (r < n_rows)
+                    out16[(((int64_t)b * M + r % M) * a.Hq + g * G + r / M) * kD + idx % kD] = 0;
+            }
+            for (int idx = tid; idx < RB * kQRows; idx += kThreads) {
+                const int r = rbg * RB * kQRows + idx;
+                if (a.lse && r < n_rows) a.lse[((int64_t)b * a.Hq + g * G + r / M) * M + r % M] = 0.f;
+            }
+        }
+        return;
+    }
+
 #pragma unroll
     for (int i = S / 2; i < (RB == 1 ? S - 1 : S); ++i)       // RB = 1 keeps one stage back for the tile in use
         if (i < n_my) issue_tile(t_begin + i, i);

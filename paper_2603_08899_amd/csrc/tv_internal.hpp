@@ -19,7 +19,6 @@ struct AttnPlan {
     int row_blocks;        // 64-row blocks of the G*M packed rows of one KV head (bf16 path), padded to a multiple of rb_per_wg
     int rb_per_wg;         // 64-row blocks covered by one workgroup: 1, 2 or 4
     int n_chunks;          // key ranges the (prefix + new rows) of a sequence are cut into
-    int chunk_len;         // keys per range (multiple of 128 on the bf16 path)
     size_t part_o_bytes;   // workspace: partial outputs
     size_t part_ml_bytes;  // workspace: partial (max, sum) pairs
     size_t total_bytes;
@@ -45,7 +44,7 @@ struct AttnArgs {
     float scale;
     float inv_M;                       // 1 / M
     int64_t tok_stride, head_stride;   // elements
-    int row_blocks, n_chunks, chunk_len, rb_per_wg;
+    int row_blocks, n_chunks, rb_per_wg;
 };
 
 hipError_t launch_attention_f32(const AttnArgs& a, hipStream_t s);
