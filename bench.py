@@ -78,8 +78,10 @@ def main() -> int:
 
     # ---- inputs, resident in HBM -------------------------------------------------------------------
     t0 = time.time()
-    def attention_setup(index, soft_len=0):
-        """All layers of workload `index` in one KV pool on the device, and a function that launches them."""
+    def attention_setup(index, soft_len=0, head_major=False):
+        """All layers of workload `index` in one KV pool on the device, and a function that launches them.
+        The pool is [L, tokens, Hkv, D] (the workload's layout); head_major=True holds the same rows as
+        [L, Hkv, tokens, D] and hands the strides over in the descriptor."""
         wk = si.WORKLOADS[index]
         first = si.attention_case(index, layer=0, soft_len=soft_len)
         m, p = first.M, int(first.prefix_len[0])
@@ -91,6 +93,11 @@ def main() -> int:
             kp[l].copy_(to_device_bf16(x.k_pool))
             vp[l].copy_(to_device_bf16(x.v_pool))
             q[l].copy_(to_device_bf16(x.q))
+        strides = {}
+        if head_major:
+            kp = kp.permute(0, 2, 1, 3).contiguous()
+            vp = vp.permute(0, 2, 1, 3).contiguous()
+            strides = dict(kv_token_stride=wk.D, kv_head_stride=(p + m) * wk.D)
         o = torch.empty_like(q)
         off = torch.zeros(1, dtype=torch.int64, device="cuda")
         pl = torch.from_numpy(first.prefix_len).cuda()
@@ -99,7 +106,7 @@ def main() -> int:
         st = torch.zeros(1, dtype=torch.int32, device="cuda")
         desc = tv.make_attn_desc(dtype=tv.TV_DTYPE_BF16, B=1, M=m, Hq=wk.Hq, Hkv=wk.Hkv, D=wk.D, soft_len=soft_len,
                                  max_prefix_len=p, softmax_scale=first.scale, num_splits=args.splits,
-                                 wg_row_blocks=args.wg_row_blocks)
+                                 wg_row_blocks=args.wg_row_blocks, **strides)
         ws = torch.empty(max(tv.tv_attention_workspace_bytes(desc), 256), device="cuda", dtype=torch.uint8)
 
         def run():
@@ -245,6 +252,15 @@ def main() -> int:
                  "max_abs_err_layer0_head3": None}        # filled in by the CPU-baseline leg
         del pa
 
+    # ---- other shapes of the same kernel (information only; `value` stays the workload's own layout and size) ------
+    other = None
+    if not args.no_paper_layout:
+        hm = attention_setup(WORKLOAD_INDEX, head_major=True)
+        us_hm = timed(hm["run"], max(args.steps // 2, 2), 2) * 1e3 / L
+        hm_same = bool(torch.equal(hm["out"][0], outs[0]))          # same rows, other strides: same bits
+        del hm
+        other = {"kv_head_major_pool_us_per_layer": round(us_hm, 3), "kv_head_major_output_identical": hm_same}
+
     # ---- what the CPU-baseline leg compares with the oracle (layer 0's output; the acceptance result) -----------
     torch.cuda.synchronize()
     got0 = outs[0].float().cpu().numpy()[0].astype(np.float64)
@@ -310,6 +326,7 @@ def main() -> int:
                                     "temp0_greedy": round(1e3 / ms_greedy, 1)},
         "tree_accept": accept_info,
         "contemplate_row_per_node": paper,
+        "other_layouts": other,
         "around_the_pass": around,
         "verify_steps_per_s": round(1e3 / ms_step, 2),
         "attention_tb_per_s": round(achieved / 1e3, 3),
