@@ -142,6 +142,22 @@ def test_bf16_ragged_batch_with_poisoned_padding():
             _check(inp, out, lse, st)
 
 
+def test_bf16_many_sequences_and_largest_tree():
+    """48 sequences in one call (the second grid dimension, the planner's many-sequence branch) and a tree of
+    the largest size the library takes (128 rows: both mask words, two 64-row blocks per query head)."""
+    rng = np.random.default_rng(31)
+    P = [int(x) for x in rng.integers(0, 400, size=48)]
+    inp = _case(31, dtype="bf16", Hq=4, Hkv=2, D=128, P=P, T=12, C=2, B=48, q_std=1.0, kv_std=1.0)
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st, seqs=range(0, 48, 5))
+    inp = _case(32, dtype="bf16", Hq=4, Hkv=4, D=128, P=[150, 33], T=120, C=8, B=2, max_depth=30, max_children=3,
+                q_std=1.0, kv_std=1.0)
+    assert inp.M == 128
+    for wg in (0, 2):
+        out, lse, st = H.run_attention(inp, wg_row_blocks=wg)
+        _check(inp, out, lse, st)
+
+
 def test_bf16_invisible_keys_do_not_change_the_output_bitwise():
     inp = _case(17, dtype="bf16", Hq=8, Hkv=2, D=128, P=100, T=30, C=2, s=8, q_std=1.0, kv_std=1.0)
     base, _, _ = H.run_attention(inp, num_splits=2)
