@@ -169,16 +169,21 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    def timed(fn, steps, warmup):
-        """Average milliseconds per call of fn over `steps` calls, HIP events on the launch stream."""
+    def timed(fn, steps, warmup, calls_per_launch=1):
+        """Average milliseconds per call of fn over `steps` launches, HIP events on the launch stream.  A launch
+        is calls_per_launch calls of fn back to back (one graph when graphs are on): a call of one or two short
+        kernels is timed like a layer of the 32-layer attention graph, without a graph launch of its own."""
+        def several():
+            for _ in range(calls_per_launch):
+                fn()
         with torch.cuda.stream(stream):
-            runner = fn
+            runner = several
             if not args.no_graph:
                 fn()                      # first call sets kernel attributes outside the capture
                 torch.cuda.synchronize()
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g, stream=stream):
-                    fn()
+                    several()
                 runner = g.replay
             for _ in range(warmup):
                 runner()
@@ -189,13 +194,13 @@ def main() -> int:
                 runner()
             e1.record(stream)
             torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / steps
+            return e0.elapsed_time(e1) / (steps * calls_per_launch)
 
     ms_step = timed(full_step, args.steps, args.warmup)
     ms_attn = timed(attention_layers, args.steps, args.warmup)
-    ms_accept = timed(accept, args.steps * 4, args.warmup)
-    ms_greedy = timed(accept_greedy, args.steps * 4, args.warmup)
-    ms_accept16 = timed(accept_bf16, args.steps * 4, args.warmup)
+    ms_accept = timed(accept, args.steps, args.warmup, 16)
+    ms_greedy = timed(accept_greedy, args.steps, args.warmup, 16)
+    ms_accept16 = timed(accept_bf16, args.steps, args.warmup, 16)
     us_layer = ms_attn * 1e3 / L
 
     # ---- the steps around the pass: commit of the accepted path (all layers, one call), contemplate embedding -----
@@ -227,8 +232,8 @@ def main() -> int:
     with torch.cuda.stream(stream):
         accept()                          # path / n_accepted / selected_con for the commit
     torch.cuda.synchronize()
-    ms_commit = timed(commit, args.steps * 4, args.warmup)      # (after the first call the moves are repeats)
-    ms_embed = timed(embed, args.steps * 4, args.warmup)
+    ms_commit = timed(commit, args.steps, args.warmup, 16)      # (after the first call the moves are repeats)
+    ms_embed = timed(embed, args.steps, args.warmup, 16)
     n_moved = int(o_n[0]) + 1
     around = {"tree_commit_us": round(ms_commit * 1e3, 2), "tree_commit_layers": L,
               "tree_commit_bytes_moved": 2 * 2 * L * n_moved * w.Hkv * w.D * 2,
