@@ -250,14 +250,38 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a
 __device__ __forceinline__ Red group_row_stat(const AcceptArgs& a, int b, int mat, int row, bool active,
                                               int sub, int g, float it, bool want_sum) {
     const RowStat* st = a.stats + ((((int64_t)b * a.n_mat + mat) * a.T + (active ? row : 0)) * a.splits);
+    // A lane's ranges are sub, sub + g, ...  They are fetched kStatBatch at a time, 16 bytes each, all requested
+    // before the first is looked at (a loop of single loads would pay one memory round trip per range).
+    constexpr int kStatBatch = 8;
+    auto fetch = [&](int s0, RowStat (&x)[kStatBatch]) {
+#pragma unroll
+        for (int k = 0; k < kStatBatch; ++k) {
+            const int s = s0 + k * g;
+            const uint4 w = *reinterpret_cast<const uint4*>(st + ((active && s < a.splits) ? s : 0));
+            const bool live = active && s < a.splits;     // (an entry that is not there: never the max, no mass)
+            x[k].max_logit = live ? __uint_as_float(w.x) : -INFINITY;
+            x[k].argmax = live ? (int)w.y : 0x7fffffff;
+            x[k].sum_exp = live ? __longlong_as_double((long long)(((unsigned long long)w.w << 32) | w.z)) : 0.0;
+        }
+    };
+    RowStat head[kStatBatch];            // the lane's first batch stays in registers for the second pass
+    fetch(sub, head);
     float m = -INFINITY;
     int am = 0x7fffffff;
-    if (active)
-        for (int s = sub; s < a.splits; s += g) {
-            const float ms = st[s].max_logit;
-            const int as = st[s].argmax;
-            if (ms > m || (ms == m && as < am)) { m = ms; am = as; }
-        }
+    auto take_max = [&](const RowStat (&x)[kStatBatch]) {
+#pragma unroll
+        for (int k = 0; k < kStatBatch; ++k)
+            if (x[k].max_logit > m || (x[k].max_logit == m && x[k].argmax < am)) {
+                m = x[k].max_logit;
+                am = x[k].argmax;
+            }
+    };
+    take_max(head);
+    for (int s0 = sub + kStatBatch * g; s0 < a.splits; s0 += kStatBatch * g) {
+        RowStat x[kStatBatch];
+        fetch(s0, x);
+        take_max(x);
+    }
     for (int o = 1; o < g; o <<= 1) {
         const float om = __shfl_xor(m, o, kWave);
         const int oam = __shfl_xor(am, o, kWave);
@@ -265,12 +289,17 @@ __device__ __forceinline__ Red group_row_stat(const AcceptArgs& a, int b, int ma
     }
     double sum = 0.0;
     if (want_sum) {
-        if (active)
-            for (int s = sub; s < a.splits; s += g) {
-                const double ss = st[s].sum_exp;
-                const float ms = st[s].max_logit;
-                sum += (ms == m) ? ss : ss * unnorm_prob(ms, m, it);
-            }
+        auto add = [&](const RowStat (&x)[kStatBatch]) {
+#pragma unroll
+            for (int k = 0; k < kStatBatch; ++k)
+                sum += (x[k].max_logit == m) ? x[k].sum_exp : x[k].sum_exp * unnorm_prob(x[k].max_logit, m, it);
+        };
+        add(head);
+        for (int s0 = sub + kStatBatch * g; s0 < a.splits; s0 += kStatBatch * g) {
+            RowStat x[kStatBatch];
+            fetch(s0, x);
+            add(x);
+        }
         for (int o = 1; o < g; o <<= 1) sum += __shfl_xor(sum, o, kWave);
     }
     return Red{m, am, sum};
@@ -674,6 +703,7 @@ struct WalkShared {
     int abit[kMaxRows];           // draft rules: the chain kernel's accept bit of node c
     double chain_z[kMaxRows];     // draft rules: normaliser of the corrected law after rejecting node c
     ChainStep steps[kMaxRows];
+    int con_anchor[kMaxRows];     // node of each contemplate row (the first kMaxRows of them)
     double red[kDrawWaves];
     double wave_tot[kDrawWaves];
     double base;                  // mass of the final law in the slices before the chosen one
@@ -742,6 +772,9 @@ __device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared&
             sh.unif[T + i] = a.uniforms[(int64_t)b * 2 * T + T + i];
         }
     }
+    // the contemplate rows' anchors (needed at the very end: fetched now, with everything else)
+    const int n_con = (a.selected_con && a.con_anchor) ? min(a.C, kMaxRows) : 0;
+    for (int i = tid; i < n_con; i += kDrawThreads) sh.con_anchor[i] = a.con_anchor[(int64_t)b * a.C + i];
     __syncthreads();
     int bad = validate_tree(sh.parent, nullptr, T, &sh.flag);
     {
@@ -1003,8 +1036,10 @@ __device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared&
         a.last_node[b] = cur;
         if (a.selected_con) {
             int sel = -1;
-            if (a.con_anchor)
-                for (int c = 0; c < a.C && sel < 0; ++c)
+            for (int c = 0; c < n_con && sel < 0; ++c)
+                if (sh.con_anchor[c] == cur) sel = c;
+            if (a.con_anchor)                                    // (more rows than the table holds: the rest from memory)
+                for (int c = n_con; c < a.C && sel < 0; ++c)
                     if (a.con_anchor[(int64_t)b * a.C + c] == cur) sel = c;
             a.selected_con[b] = sel;
         }
