@@ -131,8 +131,12 @@ __device__ __forceinline__ unsigned tile_visibility(int k0, int P, int soft_len,
 }
 
 // RB: 64-row blocks covered by one workgroup (1, 2 or 4)
+// The two per-sequence arrays come as arguments of their own, ahead of the rest: the first tile's address hangs
+// on them, and leading scalar arguments are in registers when a wave starts (kernel-argument preload, see the
+// build flags), which takes one scalar-load latency off the start of every workgroup.
 template <int RB>
-__global__ __launch_bounds__(512, 1) void attn_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix_len, const int64_t* kv_offset,
+                                                           AttnArgs a) {
     constexpr int NW = 8;                              // waves per workgroup, two per SIMD (waves w and w+4)
     constexpr int kThreads = NW * kWave;
     constexpr int WROWS = 32;                          // packed rows per wave
@@ -164,8 +168,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(AttnArgs a) {
 
     // the two per-sequence scalars everything below waits for: requested first, so that their latency runs
     // under the Q requests (the assembly statements of those keep later loads from moving up past them)
-    const int P = a.prefix_len[b];
-    const int64_t kv_first_row = a.kv_offset[b];
+    const int P = prefix_len[b];
+    const int64_t kv_first_row = kv_offset[b];
 
     // ---- Q for this wave's rows: HBM -> LDS (the upper half of the stream's ring is free at this point) -
     // The 32-row query block is laid out like a K tile, with the same segment swizzle.
@@ -720,7 +724,7 @@ hipError_t launch_variant(const AttnArgs& a, hipStream_t s) {
         attr_done.fetch_or(bit, std::memory_order_release);
     }
     const dim3 grid(a.Hkv * (a.row_blocks / RB) * a.n_chunks, a.B);
-    attn_bf16_kernel<RB><<<grid, 512, sizeof(Bf16Smem), s>>>(a);
+    attn_bf16_kernel<RB><<<grid, 512, sizeof(Bf16Smem), s>>>(a.prefix_len, a.kv_offset, a);
     return hipGetLastError();
 }
 
