@@ -22,8 +22,8 @@ FLAGS = [
     # MFMA accumulators in architectural VGPRs: the online-softmax rescale and the score post-processing
     # then work in place instead of through accumulator-register copies
     "-mllvm", "-amdgpu-mfma-vgpr-form",
-    # leading scalar kernel arguments (up to 4 dwords: two pointers) are delivered in SGPRs at wave start
-    "-mllvm", "-amdgpu-kernarg-preload-count=4",
+    # leading scalar kernel arguments (up to 12 dwords) are delivered in SGPRs at wave start
+    "-mllvm", "-amdgpu-kernarg-preload-count=12",
     "-Wno-unused-command-line-argument",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]

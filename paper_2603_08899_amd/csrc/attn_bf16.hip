@@ -657,34 +657,39 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
 // 16-byte loads).  With the KV head in the low part of the index a workgroup lands on the XCD whose workgroups
 // wrote the partial results it reads (both kernels deal workgroups round-robin to the XCDs, KV head first).
 constexpr int kCombineRows = 16;
-__global__ __launch_bounds__(256) void attn_bf16_combine_kernel(AttnArgs a) {
-    const int g = blockIdx.x % a.Hkv, b = blockIdx.y;
-    const int r = (blockIdx.x / a.Hkv) * kCombineRows + threadIdx.x / 16;      // packed row of KV head g
-    if (r >= a.G * a.M) return;
-    const int bad = a.status[b];          // requested first, looked at last: the partial loads do not wait for it
-    const int hl = (int)(((float)r + 0.5f) * a.inv_M);              // r / M (exact for these sizes)
-    const int i = r - hl * a.M, h = g * a.G + hl;
+// What the addresses of the partial results hang on comes as leading scalar arguments (preloaded into registers
+// at wave start, like the main kernel's), so the loads go out without waiting for the argument block.
+__global__ __launch_bounds__(256) void attn_bf16_combine_kernel(const void* part_o, const float* part_ml,
+                                                                const int32_t* status, int n_chunks, int Hkv,
+                                                                int row_blocks, int G, int M, float inv_M,
+                                                                AttnArgs a) {
+    const int g = blockIdx.x % Hkv, b = blockIdx.y;
+    const int r = (blockIdx.x / Hkv) * kCombineRows + threadIdx.x / 16;      // packed row of KV head g
+    if (r >= G * M) return;
+    const int bad = status[b];          // requested first, looked at last: the partial loads do not wait for it
+    const int hl = (int)(((float)r + 0.5f) * inv_M);              // r / M (exact for these sizes)
+    const int i = r - hl * M, h = g * G + hl;
     const int d0 = (threadIdx.x % 16) * 8;
-    unsigned short* dst = static_cast<unsigned short*>(a.out) + (((int64_t)b * a.M + i) * a.Hq + h) * kD + d0;
+    unsigned short* dst = static_cast<unsigned short*>(a.out) + (((int64_t)b * M + i) * a.Hq + h) * kD + d0;
     const int rb = r / kQRows, qi = r % kQRows;
-    const int64_t blk0 = ((int64_t)b * a.n_chunks * a.Hkv + g) * a.row_blocks + rb;
-    const int64_t blk_step = (int64_t)a.Hkv * a.row_blocks;
+    const int64_t blk0 = ((int64_t)b * n_chunks * Hkv + g) * row_blocks + rb;
+    const int64_t blk_step = (int64_t)Hkv * row_blocks;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float L = 0.f, mx = -INFINITY;
-    for (int ch0 = 0; ch0 < a.n_chunks; ch0 += 8) {
+    for (int ch0 = 0; ch0 < n_chunks; ch0 += 8) {
         // up to 8 partials at a time: all loads of a batch are issued before any is used
         float2 ml[8];
         bf16x8 oo[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const int64_t blk = blk0 + (int64_t)(ch0 + e < a.n_chunks ? ch0 + e : ch0) * blk_step;
-            ml[e] = *reinterpret_cast<const float2*>(a.part_ml + (blk * kQRows + qi) * 2);
-            oo[e] = *reinterpret_cast<const bf16x8*>(static_cast<const unsigned short*>(a.part_o) + (blk * kQRows + qi) * kD + d0);
+            const int64_t blk = blk0 + (int64_t)(ch0 + e < n_chunks ? ch0 + e : ch0) * blk_step;
+            ml[e] = *reinterpret_cast<const float2*>(part_ml + (blk * kQRows + qi) * 2);
+            oo[e] = *reinterpret_cast<const bf16x8*>(static_cast<const unsigned short*>(part_o) + (blk * kQRows + qi) * kD + d0);
         }
         float bm = mx;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            if (ch0 + e >= a.n_chunks) ml[e].x = -INFINITY;         // absent partials weigh nothing
+            if (ch0 + e >= n_chunks) ml[e].x = -INFINITY;         // absent partials weigh nothing
             bm = fmaxf(bm, ml[e].x);
         }
         const float bms = (bm == -INFINITY) ? 0.f : bm;
@@ -707,7 +712,7 @@ __global__ __launch_bounds__(256) void attn_bf16_combine_kernel(AttnArgs a) {
 #pragma unroll
     for (int x = 0; x < 8; ++x) ob[x] = (__bf16)(bad ? 0.f : acc[x] * inv);
     *reinterpret_cast<bf16x8*>(dst) = ob;
-    if (a.lse && d0 == 0) a.lse[((int64_t)b * a.Hq + h) * a.M + i] = bad ? 0.f : (mx + log2f(L)) * kLn2;
+    if (a.lse && d0 == 0) a.lse[((int64_t)b * a.Hq + h) * M + i] = bad ? 0.f : (mx + log2f(L)) * kLn2;
 }
 
 template <int RB>
@@ -739,7 +744,9 @@ hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s) {
     }
     if (e != hipSuccess) return e;
     if (a.n_chunks > 1) {
-        attn_bf16_combine_kernel<<<dim3((unsigned)(a.Hkv * ((a.G * a.M + kCombineRows - 1) / kCombineRows)), (unsigned)a.B), 256, 0, s>>>(a);
+        attn_bf16_combine_kernel<<<dim3((unsigned)(a.Hkv * ((a.G * a.M + kCombineRows - 1) / kCombineRows)), (unsigned)a.B),
+                                   256, 0, s>>>(a.part_o, a.part_ml, a.status, a.n_chunks, a.Hkv, a.row_blocks, a.G, a.M,
+                                                a.inv_M, a);
         e = hipGetLastError();
     }
     return e;
