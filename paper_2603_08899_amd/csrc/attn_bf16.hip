@@ -131,12 +131,12 @@ __device__ __forceinline__ unsigned tile_visibility(int k0, int P, int soft_len,
 }
 
 // RB: 64-row blocks covered by one workgroup (1, 2 or 4)
-// The two per-sequence arrays come as arguments of their own, ahead of the rest: the first tile's address hangs
-// on them, and leading scalar arguments are in registers when a wave starts (kernel-argument preload, see the
+// The two per-sequence arrays and the sequence count come as arguments of their own, ahead of the rest: the first
+// tile's address hangs on them, and leading scalar arguments are in registers when a wave starts (kernel-argument preload, see the
 // build flags), which takes one scalar-load latency off the start of every workgroup.
 template <int RB>
 __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix_len, const int64_t* kv_offset,
-                                                           AttnArgs a) {
+                                                           int n_seq, AttnArgs a) {
     constexpr int NW = 8;                              // waves per workgroup, two per SIMD (waves w and w+4)
     constexpr int kThreads = NW * kWave;
     constexpr int WROWS = 32;                          // packed rows per wave
@@ -159,17 +159,39 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
     const int rbg = bx % row_groups;
     const int chunk = bx / row_groups;
     const int row0 = rbg * RB * kQRows + wsub * WROWS; // this wave's first packed row
-    const int b = blockIdx.y;
+    int b = blockIdx.y;                                // replaced by a length rank below when there are several
     const int M = a.M, G = a.G;
     const int n_rows = G * M;
     unsigned char* ring = sm.big + st * (S * kStageBytes);
     const unsigned ring_addr = lds_address(ring);
     const int l_row = lane >> 4, l_seg = lane & 15;    // a direct-to-LDS load lands lane l at row l/16, segment l%16
 
-    // the two per-sequence scalars everything below waits for: requested first, so that their latency runs
-    // under the Q requests (the assembly statements of those keep later loads from moving up past them)
-    const int P = prefix_len[b];
-    const int64_t kv_first_row = kv_offset[b];
+    // The two per-sequence scalars everything below waits for are requested first, so that their latency runs
+    // under the Q requests (the assembly statements of those keep later loads from moving up past them).
+    int P;
+    int64_t kv_first_row;
+    if (n_seq > 1 && n_seq <= kWave) {
+        // Several sequences: the second grid index counts them by decreasing prefix length (ties by index), so
+        // the workgroups of the longest come first in the dispatch order and the short ones fill in behind
+        // them.  Every wave ranks the sequences for itself, lane l holding sequence l; the ranks are a
+        // permutation of 0 .. n_seq-1 whatever the lengths are, so each sequence is still served exactly once.
+        const bool live = lane < n_seq;
+        const int len = live ? prefix_len[lane] : -1;
+        const long long off = live ? kv_offset[lane] : 0;
+        int rank = 0;
+        for (int j = 0; j < n_seq; ++j) {
+            const int len_j = __builtin_amdgcn_readlane(len, j);
+            rank += (len_j > len || (len_j == len && j < lane)) ? 1 : 0;
+        }
+        b = __ffsll((long long)__ballot(live && rank == (int)blockIdx.y)) - 1;
+        P = __builtin_amdgcn_readlane(len, b);
+        const unsigned lo = __builtin_amdgcn_readlane((unsigned)off, b);
+        const unsigned hi = __builtin_amdgcn_readlane((unsigned)(off >> 32), b);
+        kv_first_row = (long long)(((unsigned long long)hi << 32) | lo);
+    } else {
+        P = prefix_len[b];
+        kv_first_row = kv_offset[b];
+    }
 
     // ---- Q for this wave's rows: HBM -> LDS (the upper half of the stream's ring is free at this point) -
     // The 32-row query block is laid out like a K tile, with the same segment swizzle.
@@ -729,7 +751,7 @@ hipError_t launch_variant(const AttnArgs& a, hipStream_t s) {
         attr_done.fetch_or(bit, std::memory_order_release);
     }
     const dim3 grid(a.Hkv * (a.row_blocks / RB) * a.n_chunks, a.B);
-    attn_bf16_kernel<RB><<<grid, 512, sizeof(Bf16Smem), s>>>(a.prefix_len, a.kv_offset, a);
+    attn_bf16_kernel<RB><<<grid, 512, sizeof(Bf16Smem), s>>>(a.prefix_len, a.kv_offset, a.B, a);
     return hipGetLastError();
 }
 

@@ -192,6 +192,30 @@ def test_results_are_run_to_run_identical():
     assert np.array_equal(a, b) and np.array_equal(la, lb)
 
 
+def test_bf16_sequences_are_served_once_whatever_their_lengths():
+    """The bf16 kernel hands its workgroups to the sequences by decreasing prefix length: equal lengths, empty
+    prefixes, a length outside the bound, and more sequences than a wave has lanes (served in index order) must
+    each still be answered exactly once, in their own output rows."""
+    import paper_2603_08899_amd as tv
+    P = [64, 64, 0, 200, 64, 0, 200, 64, 1]
+    inp = _case(41, dtype="bf16", Hq=4, Hkv=2, D=128, P=P, T=10, C=2, B=len(P), q_std=1.0, kv_std=1.0)
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st)
+    out, lse, st = H.run_attention(inp, max_prefix_len=100)      # sequences 3 and 6 exceed the bound
+    for b in range(len(P)):
+        if P[b] > 100:
+            assert st[b] & tv.TV_STATUS_BAD_PREFIX and np.all(out[b] == 0)
+        else:
+            assert st[b] == 0
+    _check(inp, out, lse, st, seqs=[b for b in range(len(P)) if P[b] <= 100])
+    rng = np.random.default_rng(42)
+    P = [int(x) for x in rng.integers(0, 150, size=70)]
+    inp = _case(42, dtype="bf16", Hq=4, Hkv=2, D=128, P=P, T=8, C=2, B=70, q_std=1.0, kv_std=1.0)
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st, seqs=range(0, 70, 7))
+    assert np.all(st == 0) and np.all(np.isfinite(lse))
+
+
 @pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
 def test_malformed_sequences_are_flagged_and_zeroed(dtype, D):
     import paper_2603_08899_amd as tv
