@@ -96,7 +96,7 @@ extern "C" {
 typedef struct tv_attn_desc {
     uint32_t struct_size;      /* sizeof(tv_attn_desc), checked */
     int32_t  dtype;            /* TV_DTYPE_F32 (D in {64,128}) or TV_DTYPE_BF16 (D = 128) */
-    int32_t  B;                /* sequences, >= 1 */
+    int32_t  B;                /* sequences, 1 .. 65535 */
     int32_t  M;                /* query rows per sequence, 1..TV_MAX_ROWS */
     int32_t  Hq;               /* query heads */
     int32_t  Hkv;              /* KV heads, divides Hq; Hq/Hkv <= 16 */

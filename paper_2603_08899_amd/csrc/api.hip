@@ -27,8 +27,8 @@ size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 int check_attn_desc(const tv_attn_desc* d) {
     if (!d || d->struct_size != sizeof(tv_attn_desc)) return TV_ERR_INVALID_ARG;
-    if (d->B < 1 || d->M < 1 || d->M > TV_MAX_ROWS || d->Hq < 1 || d->Hkv < 1 || d->Hq % d->Hkv != 0)
-        return TV_ERR_INVALID_ARG;
+    if (d->B < 1 || d->B > 65535 || d->M < 1 || d->M > TV_MAX_ROWS || d->Hq < 1 || d->Hkv < 1 || d->Hq % d->Hkv != 0)
+        return TV_ERR_INVALID_ARG;      // (a grid dimension counts the sequences)
     if (d->Hq / d->Hkv > 16) return TV_ERR_INVALID_ARG;
     if (d->soft_len < 0 || d->max_prefix_len < d->soft_len || d->num_splits < 0) return TV_ERR_INVALID_ARG;
     if (d->wg_row_blocks != 0 && d->wg_row_blocks != 1 && d->wg_row_blocks != 2 && d->wg_row_blocks != 4)

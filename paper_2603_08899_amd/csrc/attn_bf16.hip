@@ -26,6 +26,8 @@
 //     RB = 2, 4 (128- and 256-row workgroups, stages enough to keep tiles several rounds ahead, for long
 //     contexts and batches): a tile takes two barrier slots, scores in one, softmax and O^T product in the
 //     next, and the two waves of a SIMD are one slot apart.
+//   - Several sequences are served longest prefix first (the second grid index is a length rank), so that the
+//     long runs of tiles start early and the short ones fill in behind them.
 //   - Streams are merged through LDS; with n_chunks > 1 partial results (O / L in bf16, max and L in fp32)
 //     go to the workspace and attn_bf16_combine_kernel finishes.
 #include <atomic>

@@ -77,7 +77,7 @@ def test_host_mask_builder_rejects_what_the_oracle_rejects(parent, kind, bit):
 @pytest.mark.parametrize("kw", [
     dict(M=0), dict(M=129), dict(Hq=7), dict(D=96), dict(softmax_scale=0.0), dict(soft_len=-1),
     dict(max_prefix_len=3, soft_len=16), dict(kv_head_stride=100), dict(kv_token_stride=1028), dict(B=0),
-    dict(dtype=5),
+    dict(B=65536), dict(dtype=5),
 ])
 def test_attention_descriptor_errors_on_host(kw):
     base = dict(dtype=tv.TV_DTYPE_BF16, B=1, M=64, Hq=32, Hkv=8, D=128, soft_len=0, max_prefix_len=4096,
