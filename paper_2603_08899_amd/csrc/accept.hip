@@ -417,23 +417,40 @@ __global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs 
             __syncthreads();
             bad = s_flag;
             if (!bad)
-                for (int i = 1 + tid; i < T; i += kChainThreads) s_has[s_parent[i]] = 1;
+                for (int i = 1 + tid; i < T; i += kChainThreads) atomicAdd(&s_has[s_parent[i]], 1);
             __syncthreads();
-            if (wave == 0) {        // the nodes that have children, in index order
-                unsigned long long lo = __ballot(lane < T && s_has[lane]);
-                unsigned long long hi = __ballot(lane + kWave < T && s_has[lane + kWave]);
+            if (wave == 0) {
+                // The nodes that have children, those with the most children first (ties by index): a child costs
+                // a round trip through the whole group, so the long chains are what the groups' loads are
+                // balanced by (see the order in which a group takes its nodes, below).
+                const int k_lo = (lane < T) ? s_has[lane] : 0;
+                const int k_hi = (lane + kWave < T) ? s_has[lane + kWave] : 0;
+                int k_max = max(k_lo, k_hi);
+                for (int off = kWave / 2; off; off >>= 1) k_max = max(k_max, __shfl_xor(k_max, off));
+                int n = 0;
+                for (int kk = k_max; kk >= 1; --kk) {
+                    unsigned long long lo = __ballot(k_lo == kk), hi = __ballot(k_hi == kk);
+                    if (lo == 0 && hi == 0) continue;
+                    if (lane == 0) {
+                        while (lo) { s_internal[n++] = __ffsll((long long)lo) - 1; lo &= lo - 1; }
+                        while (hi) { s_internal[n++] = kWave + __ffsll((long long)hi) - 1; hi &= hi - 1; }
+                    }
+                }
                 if (lane == 0) {
-                    int n = 0;
-                    while (lo) { s_internal[n++] = __ffsll((long long)lo) - 1; lo &= lo - 1; }
-                    while (hi) { s_internal[n++] = kWave + __ffsll((long long)hi) - 1; hi &= hi - 1; }
                     s_nint = bad ? 0 : n;       // malformed input: nothing to do (the walk kernel reports it)
                     s_fail = 0;
                 }
             }
             __syncthreads();
         }
-        if (r >= s_nint) continue;
-        const int u = s_internal[r];
+        // Pass p of the groups over the sorted nodes runs forwards for even p and backwards for odd p, so the group
+        // that took the longest chain of one pass takes the shortest of the next.
+        // (a permutation of 0 .. T-1: the last pass may be a short one)
+        const int pass = r / n_groups, pos = r % n_groups;
+        const int pass_len = min(n_groups, T - pass * n_groups);
+        const int ri = pass * n_groups + ((pass & 1) ? pass_len - 1 - pos : pos);
+        if (ri >= s_nint) continue;
+        const int u = s_internal[ri];
         if (wave == 0) {            // the children of u, in index order
             const int par_lo = (lane < T) ? s_parent[lane] : -2;
             const int par_hi = (lane + kWave < T) ? s_parent[lane + kWave] : -2;

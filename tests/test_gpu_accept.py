@@ -123,6 +123,19 @@ def test_full_vocabulary_batch_of_eight():
     assert got["n_accepted"].max() >= 2
 
 
+@pytest.mark.parametrize("rule", ["wor", "wr"])
+def test_draft_rules_more_nodes_with_children_than_groups(rule):
+    """Full vocabulary (32 workgroups per sibling-chain group, so about sixteen groups are resident) and trees
+    with far more nodes that have children than that: a 50-node chain (49 such nodes: four passes of the groups,
+    the last one short) and two bushy sequences in one call (the passes run over both).  The accepted path of
+    the chain goes deep (draft and target laws nearly equal), so the chain kernel's results for late nodes are used."""
+    inp = _batch(64, B=1, T=50, V=128256, rule=RULES[rule], temp=1.0, corr=0.9995, tree=trees.chain_tree(50))
+    got = _run_and_compare(inp)
+    assert int(got["n_accepted"][0]) >= 10
+    _run_and_compare(_batch(62, B=2, T=60, V=128256, rule=RULES[rule], temp=1.0, corr=0.9, boost=4.0, max_depth=12,
+                            max_children=2))
+
+
 def test_many_uniform_draws_on_one_full_size_tree():
     """One Llama-3-sized tree, 24 different sets of uniforms (as a batch sharing logits by copy)."""
     base = si.accept_case(1, 0, draft_target_corr=0.9, child_boost=4.0)
