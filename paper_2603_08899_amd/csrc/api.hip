@@ -67,34 +67,71 @@ int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
     const int rows = p.G * d.M;
     const int rb_needed = (rows + 63) / 64;
     const int n_tiles = (d.max_prefix_len + d.M + 31) / 32;
-    // key ranges for workgroups of rb 64-row blocks
-    auto chunks_for = [&](int rb) {
-        const int64_t base = (int64_t)d.B * d.Hkv * ((rb_needed + rb - 1) / rb);
-        int n;
-        if (d.num_splits > 0) {
-            n = d.num_splits;
-        } else {
-            // one workgroup per CU for a single sequence; ragged batches get twice as many, smaller ones so
-            // the hardware dispatcher can even them out (more than that only multiplies the fixed cost of a
-            // workgroup: measured on a batch of 8 with 512..8192 cached tokens)
-            const int cus = device_cu_count();
-            const int64_t want = (d.B == 1) ? cus : 2 * (int64_t)cus;
-            n = (int)((want + base / 2) / base);
-        }
-        const int max_n = n_tiles / 8 > 1 ? n_tiles / 8 : 1;     // at least two tiles per wave
-        if (n > max_n) n = max_n;
-        if (n > 64) n = 64;
-        if (n < 1) n = 1;
-        return n;
+    // Workgroup shape (rb 64-row blocks per workgroup, 4/rb key streams) and number of key ranges n: what the
+    // caller fixes is taken as given, the rest is chosen by a small cost model of the kernel, in microseconds,
+    // fitted to measurements on MI355X (one and four sequences, 1k .. 64k cached tokens each, all three shapes,
+    // pools larger than the last-level cache).  A workgroup takes
+    //   t = fixed(rb) + rounds * per_round(rb)
+    // with rounds = tiles of its longest key stream, fixed = launch, prologue and epilogue (larger shapes merge
+    // and store more rows), per_round = one 32-key tile per stream (64-row workgroups become request-bound on
+    // long runs); one workgroup runs per CU at a time; the second kernel adds 3.3 when n > 1.
+    // The lengths are on the device, so the model prices two batches: every sequence at max_prefix_len
+    // (all workgroups alike: whole waves of them, waves * t), and a ragged one whose lengths average 0.55 of the
+    // longest, which is near max_prefix_len (the dispatcher evens out workgroups of unlike length, so what counts
+    // is the longest one or the sum over all CUs: U{512..8192} has that mean).  The choice is the candidate
+    // whose worse regret over the two is smallest; one sequence has only the first case.
+    const int cus = device_cu_count();
+    const int max_n = n_tiles / 8 > 1 ? (n_tiles / 8 < 64 ? n_tiles / 8 : 64) : 1;     // at least eight tiles per range
+    constexpr double kRaggedMean = 0.55;
+    auto model_us = [&](int rb, int n, double* t_uniform, double* t_ragged) {
+        const int streams = 4 / rb;
+        const int64_t wgs = (int64_t)d.B * d.Hkv * ((rb_needed + rb - 1) / rb) * n;
+        const int64_t waves = (wgs + cus - 1) / cus;
+        const int rounds = (n_tiles + n * streams - 1) / (n * streams);
+        const double fixed = rb == 1 ? 6.5 : rb == 2 ? 11.6 : 15.5;
+        double per_round;
+        if (rb == 1) per_round = 1.60 + 0.25 * (rounds <= 17 ? 0.0 : rounds >= 33 ? 1.0 : (rounds - 17) / 16.0);
+        else if (rb == 2) per_round = 1.02 + 0.28 * (rounds <= 9 ? 0.0 : rounds >= 33 ? 1.0 : (rounds - 9) / 24.0);
+        else per_round = 1.20;
+        const double combine = n > 1 ? 3.3 : 0.0;
+        const double longest = fixed + rounds * per_round;
+        const double spread = (double)wgs / cus * (fixed + kRaggedMean * rounds * per_round);
+        *t_uniform = (double)waves * longest + combine;
+        *t_ragged = (longest > spread ? longest : spread) + combine;
     };
-    // 64-row workgroups (four key streams, the smallest partial results) unless the caller says otherwise or
-    // every workgroup would get a long run of tiles: then 128-row workgroups, whose deeper stage ring and
-    // two-phase rounds stream K/V faster, win over their larger prologue and partial results (measured
-    // crossover on MI355X: about 56 tiles per 64-row workgroup)
-    p.rb_per_wg = d.wg_row_blocks ? d.wg_row_blocks : 1;
-    if (d.wg_row_blocks == 0 && rb_needed % 2 == 0 && n_tiles / chunks_for(1) >= 56) p.rb_per_wg = 2;
+    auto allowed = [&](int rb, int n) {
+        if (d.wg_row_blocks ? rb != d.wg_row_blocks : (rb_needed % rb != 0)) return false;
+        if (d.num_splits > 0) return n == (d.num_splits < max_n ? d.num_splits : max_n);
+        return n <= max_n;
+    };
+    int best_rb = 0, best_n = 0;
+    {
+        double min_u = 1e30, min_r = 1e30;
+        for (int rb = 1; rb <= 4; rb *= 2)
+            for (int n = 1; n <= 64; ++n) {
+                if (!allowed(rb, n)) continue;
+                double tu, tr;
+                model_us(rb, n, &tu, &tr);
+                if (tu < min_u) min_u = tu;
+                if (tr < min_r) min_r = tr;
+            }
+        double best_regret = 1e30, best_u = 1e30;
+        for (int rb = 1; rb <= 4; rb *= 2)
+            for (int n = 1; n <= 64; ++n) {
+                if (!allowed(rb, n)) continue;
+                double tu, tr;
+                model_us(rb, n, &tu, &tr);
+                const double ru = tu - min_u, rr = (d.B == 1) ? 0.0 : tr - min_r;
+                const double regret = ru > rr ? ru : rr;
+                if (regret < best_regret || (regret == best_regret && tu < best_u)) {
+                    best_regret = regret; best_u = tu; best_rb = rb; best_n = n;
+                }
+            }
+    }
+    if (best_rb == 0) return TV_ERR_INVALID_ARG;
+    p.rb_per_wg = best_rb;
     p.row_blocks = (rb_needed + p.rb_per_wg - 1) / p.rb_per_wg * p.rb_per_wg;
-    const int n = chunks_for(p.rb_per_wg);
+    const int n = best_n;
     p.n_chunks = n;
     if (n > 1) {
         const size_t blocks = (size_t)d.B * d.Hkv * p.row_blocks * n;
