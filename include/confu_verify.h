@@ -115,6 +115,14 @@ typedef struct tv_attn_desc {
  * Returns TV_OK / TV_ERR_INVALID_ARG / TV_ERR_UNSUPPORTED. */
 int tv_attention_workspace_bytes(const tv_attn_desc* desc, size_t* out_bytes);
 
+/* host: the launch shape the library would use for *desc on the current device (bf16 path; the fp32 path
+ * reports 1 and 1): *wg_row_blocks = 64-row blocks of the packed query rows per workgroup (1, 2 or 4),
+ * *key_ranges = ranges the keys of a sequence are cut into (> 1: partial results in the workspace and a second
+ * kernel).  num_splits / wg_row_blocks of the descriptor are honoured (num_splits is capped so that a range
+ * keeps at least eight 32-key tiles).  For logging and tuning; nothing has to call it.
+ * Returns TV_OK / TV_ERR_INVALID_ARG / TV_ERR_UNSUPPORTED. */
+int tv_attention_plan(const tv_attn_desc* desc, int32_t* wg_row_blocks, int32_t* key_ranges);
+
 int tree_verify_attention(
     const tv_attn_desc* desc,      /* host */
     const void*    q,              /* device [B, M, Hq, D], dtype, contiguous */

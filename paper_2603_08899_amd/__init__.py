@@ -26,7 +26,7 @@ TV_RULE_GREEDY, TV_RULE_DETERMINISTIC, TV_RULE_DRAFT_WOR, TV_RULE_DRAFT_WR, TV_R
 TV_FINAL_BONUS, TV_FINAL_RESIDUAL = 0, 1
 
 EXPORTED_SYMBOLS = (
-    "tv_attention_workspace_bytes", "tree_verify_attention",
+    "tv_attention_workspace_bytes", "tv_attention_plan", "tree_verify_attention",
     "tv_accept_workspace_bytes", "tree_accept",
     "tree_commit", "contemplate_embed", "tv_embed_workspace_bytes",
     "tv_build_mask_host", "tv_error_string", "tv_version", "tv_set_wait_limit",
@@ -99,6 +99,9 @@ def lib() -> ctypes.CDLL:
         l.tv_build_mask_host.argtypes = [vp, vp, ctypes.c_int, vp]
         l.tv_attention_workspace_bytes.restype = ctypes.c_int
         l.tv_attention_workspace_bytes.argtypes = [ctypes.POINTER(tv_attn_desc), ctypes.POINTER(sz)]
+        l.tv_attention_plan.restype = ctypes.c_int
+        l.tv_attention_plan.argtypes = [ctypes.POINTER(tv_attn_desc), ctypes.POINTER(ctypes.c_int32),
+                                        ctypes.POINTER(ctypes.c_int32)]
         l.tree_verify_attention.restype = ctypes.c_int
         l.tree_verify_attention.argtypes = [ctypes.POINTER(tv_attn_desc)] + [vp] * 11 + [sz, vp]
         l.tv_accept_workspace_bytes.restype = ctypes.c_int
@@ -144,6 +147,15 @@ def tv_attention_workspace_bytes(desc: tv_attn_desc) -> int:
     if rc:
         raise ConfuVerifyError(rc, "tv_attention_workspace_bytes")
     return int(n.value)
+
+
+def tv_attention_plan(desc: tv_attn_desc):
+    """(64-row blocks per workgroup, key ranges) the library would launch *desc with."""
+    rb, n = ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = lib().tv_attention_plan(ctypes.byref(desc), ctypes.byref(rb), ctypes.byref(n))
+    if rc:
+        raise ConfuVerifyError(rc, "tv_attention_plan")
+    return int(rb.value), int(n.value)
 
 
 def tv_accept_workspace_bytes(desc: tv_accept_desc) -> int:

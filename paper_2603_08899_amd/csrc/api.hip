@@ -123,7 +123,9 @@ int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
                 model_us(rb, n, &tu, &tr);
                 const double ru = tu - min_u, rr = (d.B == 1) ? 0.0 : tr - min_r;
                 const double regret = ru > rr ? ru : rr;
-                if (regret < best_regret || (regret == best_regret && tu < best_u)) {
+                // (ties: the smaller time for equal lengths, then more ranges - the same rounds for the longest stream,
+                //  fewer for the others)
+                if (regret < best_regret || (regret == best_regret && (tu < best_u || (tu == best_u && n > best_n)))) {
                     best_regret = regret; best_u = tu; best_rb = rb; best_n = n;
                 }
             }
@@ -195,6 +197,18 @@ int tv_attention_workspace_bytes(const tv_attn_desc* desc, size_t* out_bytes) {
     AttnPlan p;
     plan_attention(*desc, &p);
     *out_bytes = p.total_bytes;
+    return TV_OK;
+}
+
+int tv_attention_plan(const tv_attn_desc* desc, int32_t* wg_row_blocks, int32_t* key_ranges) {
+    if (!wg_row_blocks || !key_ranges) return TV_ERR_INVALID_ARG;
+    const int rc = check_attn_desc(desc);
+    if (rc != TV_OK) return rc;
+    AttnPlan p;
+    const int prc = plan_attention(*desc, &p);
+    if (prc != TV_OK) return prc;
+    *wg_row_blocks = desc->dtype == TV_DTYPE_BF16 ? p.rb_per_wg : 1;
+    *key_ranges = p.n_chunks;
     return TV_OK;
 }
 

@@ -113,3 +113,33 @@ def test_workspace_grows_with_split_count():
         dtype=tv.TV_DTYPE_BF16, B=1, M=64, Hq=32, Hkv=8, D=128, soft_len=0, max_prefix_len=4096,
         softmax_scale=0.1, num_splits=n))
     assert mk(1) == 0 and mk(2) > 0 and mk(4) == 2 * mk(2)
+
+
+def _plan(**kw):
+    base = dict(dtype=tv.TV_DTYPE_BF16, B=1, M=64, Hq=32, Hkv=8, D=128, soft_len=0, max_prefix_len=4096,
+                softmax_scale=0.1)
+    base.update(kw)
+    return tv.tv_attention_plan(tv.make_attn_desc(**base))
+
+
+def test_attention_planner_choices_on_a_256_cu_device():
+    """Host logic only (without a GPU the library assumes the MI355X's 256 CUs).  The shapes below are the ones the
+    planner's cost model was fitted on; each expectation is the configuration measured fastest there (or, for a
+    batch, the one its uniform/ragged hedge is documented to take)."""
+    assert _plan() == (1, 8)                                     # the benchmark layer: one 64-row workgroup per CU
+    assert _plan(max_prefix_len=1024) == (1, 4)                  # ranges keep at least eight tiles
+    assert _plan(max_prefix_len=16384) == (2, 16)                # long context: 128-row workgroups
+    assert _plan(max_prefix_len=65536)[0] in (2, 4)
+    assert _plan(B=4, max_prefix_len=1024) == (1, 2)             # short batch: one wave of workgroups, not two
+    assert _plan(B=8, max_prefix_len=8192) == (2, 4)             # long batch: twice the CU count, for ragged lengths
+    assert _plan(B=64, max_prefix_len=512)[1] == 1               # enough sequences: no split of the keys
+    # what the caller fixes is kept
+    assert _plan(num_splits=3) == (1, 3) and _plan(wg_row_blocks=4)[0] == 4
+    assert _plan(num_splits=50)[1] == 16                         # capped: 130 tiles, at least eight per range
+    assert _plan(dtype=tv.TV_DTYPE_F32, D=64) == (1, 1)
+    # every workgroup count the planner can produce fits the grid
+    for B in (1, 3, 17, 1000, 65535):
+        for P in (0, 100, 5000, 200000):
+            rb, n = _plan(B=B, max_prefix_len=P)
+            assert rb in (1, 2, 4) and 1 <= n <= 64
+            assert 8 * (4 // rb) * n < 2 ** 31
