@@ -109,6 +109,10 @@ typedef struct tv_attn_desc {
     int32_t  num_splits;       /* 0 = library decides how many ranges the keys are cut into */
     int32_t  wg_row_blocks;    /* bf16 path tuning, 0 = library decides: 64-row blocks of the packed query rows that one
                                   workgroup covers (1, 2 or 4) */
+    int64_t  sum_prefix_len;   /* hint, B > 1: sum of prefix_len[b] as the host expects it, or 0 = unknown.  The lengths
+                                  themselves stay on the device; with the sum the launch is sized for the batch as it
+                                  is (all sequences alike, or ragged), without it for a compromise between the two.
+                                  0 <= sum_prefix_len <= B * max_prefix_len.  Results do not depend on it. */
 } tv_attn_desc;
 
 /* host: writes the workspace size (bytes) tree_verify_attention needs for *desc.

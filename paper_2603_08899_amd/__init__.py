@@ -40,7 +40,7 @@ class tv_attn_desc(ctypes.Structure):
         ("D", ctypes.c_int32), ("soft_len", ctypes.c_int32), ("max_prefix_len", ctypes.c_int32),
         ("softmax_scale", ctypes.c_float),
         ("kv_token_stride", ctypes.c_int64), ("kv_head_stride", ctypes.c_int64),
-        ("num_splits", ctypes.c_int32), ("wg_row_blocks", ctypes.c_int32),
+        ("num_splits", ctypes.c_int32), ("wg_row_blocks", ctypes.c_int32), ("sum_prefix_len", ctypes.c_int64),
     ]
 
 
@@ -130,9 +130,10 @@ def _stream_handle(stream) -> Optional[int]:
 
 def make_attn_desc(*, dtype: int, B: int, M: int, Hq: int, Hkv: int, D: int, soft_len: int,
                    max_prefix_len: int, softmax_scale: float, kv_token_stride: int = 0,
-                   kv_head_stride: int = 0, num_splits: int = 0, wg_row_blocks: int = 0) -> tv_attn_desc:
+                   kv_head_stride: int = 0, num_splits: int = 0, wg_row_blocks: int = 0,
+                   sum_prefix_len: int = 0) -> tv_attn_desc:
     return tv_attn_desc(ctypes.sizeof(tv_attn_desc), dtype, B, M, Hq, Hkv, D, soft_len, max_prefix_len,
-                        softmax_scale, kv_token_stride, kv_head_stride, num_splits, wg_row_blocks)
+                        softmax_scale, kv_token_stride, kv_head_stride, num_splits, wg_row_blocks, sum_prefix_len)
 
 
 def make_accept_desc(*, B: int, T: int, V: int, C: int, rule: int, temperature: float,

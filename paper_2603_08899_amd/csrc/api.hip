@@ -33,6 +33,7 @@ int check_attn_desc(const tv_attn_desc* d) {
     if (d->soft_len < 0 || d->max_prefix_len < d->soft_len || d->num_splits < 0) return TV_ERR_INVALID_ARG;
     if (d->wg_row_blocks != 0 && d->wg_row_blocks != 1 && d->wg_row_blocks != 2 && d->wg_row_blocks != 4)
         return TV_ERR_INVALID_ARG;
+    if (d->sum_prefix_len < 0 || d->sum_prefix_len > (int64_t)d->B * d->max_prefix_len) return TV_ERR_INVALID_ARG;
     if (!(d->softmax_scale > 0.f)) return TV_ERR_INVALID_ARG;
     if (d->kv_token_stride < 0 || d->kv_head_stride < 0) return TV_ERR_INVALID_ARG;
     if (d->dtype == TV_DTYPE_F32) {
@@ -79,10 +80,14 @@ int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
     // (all workgroups alike: whole waves of them, waves * t), and a ragged one whose lengths average 0.55 of the
     // longest, which is near max_prefix_len (the dispatcher evens out workgroups of unlike length, so what counts
     // is the longest one or the sum over all CUs: U{512..8192} has that mean).  The choice is the candidate
-    // whose worse regret over the two is smallest; one sequence has only the first case.
+    // whose worse regret over the two is smallest; one sequence has only the first case.  With the caller's
+    // sum_prefix_len the batch is known instead: equal lengths when the mean is within a tenth of the maximum,
+    // else the ragged model with that mean.
     const int cus = device_cu_count();
     const int max_n = n_tiles / 8 > 1 ? (n_tiles / 8 < 64 ? n_tiles / 8 : 64) : 1;     // at least eight tiles per range
-    constexpr double kRaggedMean = 0.55;
+    const bool mean_known = d.B > 1 && d.sum_prefix_len > 0 && d.max_prefix_len > 0;
+    const double known_mean = mean_known ? (double)d.sum_prefix_len / ((double)d.B * d.max_prefix_len) : 1.0;
+    const double kRaggedMean = mean_known ? known_mean : 0.55;
     auto model_us = [&](int rb, int n, double* t_uniform, double* t_ragged) {
         const int streams = 4 / rb;
         const int64_t wgs = (int64_t)d.B * d.Hkv * ((rb_needed + rb - 1) / rb) * n;
@@ -121,8 +126,11 @@ int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
                 if (!allowed(rb, n)) continue;
                 double tu, tr;
                 model_us(rb, n, &tu, &tr);
-                const double ru = tu - min_u, rr = (d.B == 1) ? 0.0 : tr - min_r;
-                const double regret = ru > rr ? ru : rr;
+                const double ru = tu - min_u, rr = tr - min_r;
+                double regret;
+                if (d.B == 1 || (mean_known && known_mean >= 0.9)) regret = ru;       // equal lengths
+                else if (mean_known) regret = rr;                                     // ragged, mean known
+                else regret = ru > rr ? ru : rr;
                 // (ties: the smaller time for equal lengths, then more ranges - the same rounds for the longest stream,
                 //  fewer for the others)
                 if (regret < best_regret || (regret == best_regret && (tu < best_u || (tu == best_u && n > best_n)))) {

@@ -534,7 +534,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
                 if (t < n_my) phase_a(t);
             }
             open_b(n_iter - 1);
-            if (n_iter - 1 < n_my) phase_b(n_iter - 1);
+            if (n_iter >= 1 && n_iter - 1 < n_my) phase_b(n_iter - 1);       // (no tile at all: no trailing phase)
         }
         pv_mfma(va, pb);         // the last tile's product
     } else {
@@ -598,7 +598,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
                 if (t < n_my) phase_a(t);
             }
             open_even(n_iter);
-            if (n_iter - 1 < n_my) phase_b(n_iter - 1);
+            if (n_iter >= 1 && n_iter - 1 < n_my) phase_b(n_iter - 1);       // (no tile at all: no trailing phase)
         }
     }
 

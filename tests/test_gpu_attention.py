@@ -216,6 +216,42 @@ def test_bf16_sequences_are_served_once_whatever_their_lengths():
     assert np.all(st == 0) and np.all(np.isfinite(lse))
 
 
+@pytest.mark.parametrize("wg", [0, 1, 2, 4])
+def test_bf16_fewer_tiles_than_key_streams(wg):
+    """The launch is sized from max_prefix_len; a sequence far shorter than that bound leaves whole key streams, and
+    whole workgroups, without a tile.  They must contribute nothing (small-magnitude scores, so that a stray
+    contribution with weight 2^0 would show)."""
+    import paper_2603_08899_amd as tv
+    for P, bound in ((40, 4096), (0, 4096), (300, 16384), (1000, 65536)):
+        inp = _case(52, dtype="bf16", Hq=8, Hkv=2, D=128, P=P, T=20, C=2, q_std=0.3, kv_std=0.3)
+        out, lse, st = H.run_attention(inp, max_prefix_len=bound, wg_row_blocks=wg)
+        _check(inp, out, lse, st)
+    P = [40, 2000, 0, 700, 5, 64]
+    inp = _case(53, dtype="bf16", Hq=8, Hkv=2, D=128, P=P, T=20, C=2, B=len(P), q_std=0.3, kv_std=0.3)
+    out, lse, st = H.run_attention(inp, max_prefix_len=8192, wg_row_blocks=wg)
+    _check(inp, out, lse, st)
+    rb, n = tv.tv_attention_plan(tv.make_attn_desc(dtype=tv.TV_DTYPE_BF16, B=len(P), M=inp.M, Hq=8, Hkv=2, D=128,
+                                                   soft_len=0, max_prefix_len=8192, softmax_scale=inp.scale,
+                                                   wg_row_blocks=wg))
+    assert n * (4 // rb) > (40 + inp.M + 31) // 32        # more key streams than the short sequences have tiles
+
+
+def test_bf16_length_hint_changes_the_launch_not_the_answer():
+    """sum_prefix_len only sizes the launch: with the true sum, with the sum of a batch of equal lengths and
+    without it the outputs meet the same bound (the split of the keys may differ, so not bit for bit)."""
+    import paper_2603_08899_amd as tv
+    P = [700, 90, 1500, 333, 2048, 64]
+    inp = _case(51, dtype="bf16", Hq=8, Hkv=2, D=128, P=P, T=16, C=2, B=len(P), q_std=1.0, kv_std=1.0)
+    plans = set()
+    for hint in (0, sum(P), len(P) * max(P)):
+        out, lse, st = H.run_attention(inp, sum_prefix_len=hint)
+        _check(inp, out, lse, st)
+        plans.add(tv.tv_attention_plan(tv.make_attn_desc(dtype=tv.TV_DTYPE_BF16, B=len(P), M=inp.M, Hq=8, Hkv=2, D=128,
+                                                          soft_len=0, max_prefix_len=max(P), softmax_scale=inp.scale,
+                                                          sum_prefix_len=hint)))
+    print("plans", plans)
+
+
 @pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
 def test_malformed_sequences_are_flagged_and_zeroed(dtype, D):
     import paper_2603_08899_amd as tv

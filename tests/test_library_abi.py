@@ -77,7 +77,7 @@ def test_host_mask_builder_rejects_what_the_oracle_rejects(parent, kind, bit):
 @pytest.mark.parametrize("kw", [
     dict(M=0), dict(M=129), dict(Hq=7), dict(D=96), dict(softmax_scale=0.0), dict(soft_len=-1),
     dict(max_prefix_len=3, soft_len=16), dict(kv_head_stride=100), dict(kv_token_stride=1028), dict(B=0),
-    dict(B=65536), dict(dtype=5),
+    dict(B=65536), dict(dtype=5), dict(sum_prefix_len=4097), dict(sum_prefix_len=-1),
 ])
 def test_attention_descriptor_errors_on_host(kw):
     base = dict(dtype=tv.TV_DTYPE_BF16, B=1, M=64, Hq=32, Hkv=8, D=128, soft_len=0, max_prefix_len=4096,
@@ -133,6 +133,12 @@ def test_attention_planner_choices_on_a_256_cu_device():
     assert _plan(B=4, max_prefix_len=1024) == (1, 2)             # short batch: one wave of workgroups, not two
     assert _plan(B=8, max_prefix_len=8192) == (2, 4)             # long batch: twice the CU count, for ragged lengths
     assert _plan(B=64, max_prefix_len=512)[1] == 1               # enough sequences: no split of the keys
+    # the hint: the same batch shape sized for equal lengths, and for the ragged lengths of the batch-of-8 workload
+    assert _plan(B=16, max_prefix_len=2048) == (2, 2) and _plan(B=16, max_prefix_len=2048, sum_prefix_len=16 * 2048) == (2, 1)
+    wgs = lambda plan: 8 * 8 * (4 // plan[0]) * plan[1]           # B * Hkv * row groups * ranges
+    assert wgs(_plan(B=8, max_prefix_len=8192, sum_prefix_len=8 * 8192)) == 256      # equal lengths: one per CU
+    assert wgs(_plan(B=8, max_prefix_len=8192, sum_prefix_len=34868)) > 256          # ragged: more, smaller ones
+    assert _plan(B=8, max_prefix_len=8192) == (2, 4)                                   # unknown: the compromise
     # what the caller fixes is kept
     assert _plan(num_splits=3) == (1, 3) and _plan(wg_row_blocks=4)[0] == 4
     assert _plan(num_splits=50)[1] == 16                         # capped: 130 tiles, at least eight per range
