@@ -21,7 +21,8 @@ def to_device_storage(arr: np.ndarray, dtype: str):
 
 
 def run_attention(inp: AttnInputs, *, want_lse: bool = True, num_splits: int = 0, max_prefix_len=None,
-                  device_inputs=None, wg_row_blocks: int = 0, sum_prefix_len: int = 0):
+                  device_inputs=None, wg_row_blocks: int = 0, sum_prefix_len: int = 0,
+                  kv_token_stride: int = 0, kv_head_stride: int = 0):
     """Returns (out float64 [B,M,Hq,D], lse float64 [B,Hq,M] or None, status int32 [B])."""
     import paper_2603_08899_amd as tv
     torch = _torch()
@@ -29,7 +30,8 @@ def run_attention(inp: AttnInputs, *, want_lse: bool = True, num_splits: int = 0
     mp = int(inp.prefix_len.max()) if max_prefix_len is None else int(max_prefix_len)
     desc = tv.make_attn_desc(dtype=dt, B=inp.B, M=inp.M, Hq=inp.Hq, Hkv=inp.Hkv, D=inp.D,
                              soft_len=inp.soft_len, max_prefix_len=mp, softmax_scale=inp.scale,
-                             num_splits=num_splits, wg_row_blocks=wg_row_blocks, sum_prefix_len=sum_prefix_len)
+                             num_splits=num_splits, wg_row_blocks=wg_row_blocks, sum_prefix_len=sum_prefix_len,
+                             kv_token_stride=kv_token_stride, kv_head_stride=kv_head_stride)
     if device_inputs is None:
         q = to_device_storage(inp.q, inp.dtype)
         k = to_device_storage(inp.k_pool, inp.dtype)

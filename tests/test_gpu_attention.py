@@ -216,6 +216,31 @@ def test_bf16_sequences_are_served_once_whatever_their_lengths():
     assert np.all(st == 0) and np.all(np.isfinite(lse))
 
 
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
+def test_pool_strides_head_major_and_padded_rows(dtype, D):
+    """The same K/V values in three pool layouts - token-major (the default strides), head-major
+    [Hkv][rows][D], and token-major with padded rows and padded heads - give the same output bit for bit."""
+    import torch
+    inp = _case(54, dtype=dtype, Hq=8, Hkv=2, D=D, P=[300, 47], T=12, C=2, B=2, q_std=1.0, kv_std=1.0)
+    q = H.to_device_storage(inp.q, dtype)
+    k = H.to_device_storage(inp.k_pool, dtype)            # [rows, Hkv, D]
+    v = H.to_device_storage(inp.v_pool, dtype)
+    rows = k.shape[0]
+    ref, ref_lse, st = H.run_attention(inp, device_inputs=(q, k, v))
+    _check(inp, ref, ref_lse, st)
+    kh, vh = k.permute(1, 0, 2).contiguous(), v.permute(1, 0, 2).contiguous()
+    out, lse, st = H.run_attention(inp, device_inputs=(q, kh, vh), kv_token_stride=D, kv_head_stride=rows * D)
+    assert np.array_equal(out, ref) and np.array_equal(lse, ref_lse) and np.all(st == 0)
+    hs, ts = D + 16, 2 * (D + 16) + 8                     # padded heads, padded rows (multiples of 8 elements)
+    kp = torch.full((rows, ts), float("nan"), device="cuda", dtype=k.dtype)
+    vp = torch.full((rows, ts), float("nan"), device="cuda", dtype=k.dtype)
+    for g in range(2):
+        kp[:, g * hs:g * hs + D] = k[:, g]
+        vp[:, g * hs:g * hs + D] = v[:, g]
+    out, lse, st = H.run_attention(inp, device_inputs=(q, kp, vp), kv_token_stride=ts, kv_head_stride=hs)
+    assert np.array_equal(out, ref) and np.array_equal(lse, ref_lse) and np.all(st == 0)
+
+
 @pytest.mark.parametrize("wg", [0, 1, 2, 4])
 def test_bf16_fewer_tiles_than_key_streams(wg):
     """The launch is sized from max_prefix_len; a sequence far shorter than that bound leaves whole key streams, and
