@@ -115,7 +115,9 @@ def main() -> int:
 
         bytes_layer = 2 * (p + m) * wk.Hkv * wk.D * 2 + 2 * m * wk.Hq * wk.D * 2
         flops_layer = 4 * m * wk.Hq * (p + m) * wk.D
+        rb, n_ranges = tv.tv_attention_plan(desc)
         return {"run": run, "first": first, "out": o, "M": m, "P": p, "bytes": bytes_layer, "flops": flops_layer,
+                "plan": {"rows_per_workgroup": 64 * rb, "key_ranges": n_ranges},
                 "keep": (kp, vp, q, off, pl, par, kin, st, ws)}
 
     main_attn = attention_setup(WORKLOAD_INDEX)
@@ -338,7 +340,7 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "layers": L, "batch": 1, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "prefix": P,
                    "tree_nodes": w.T, "contemplate_rows": w.C, "vocab": w.V,
-                   "launch": "eager" if args.no_graph else "hip-graph replay"},
+                   "launch": "eager" if args.no_graph else "hip-graph replay", "attention_plan": main_attn["plan"]},
         "tree_accept_steps_per_s": {"temp1.0_deterministic": round(1e3 / ms_accept, 1),
                                     "temp0_greedy": round(1e3 / ms_greedy, 1)},
         "tree_accept": accept_info,
