@@ -217,6 +217,19 @@ def test_bf16_sequences_are_served_once_whatever_their_lengths():
 
 
 @pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
+@pytest.mark.parametrize("P,s", [(16, 16), (48, 48), (64, 64), (100, 96), (33, 32), (400, 399)])
+def test_soft_prompt_slots_up_to_the_whole_prefix(dtype, D, P, s):
+    """soft_len up to P itself: draft nodes then see no cached row at all (only their tree ancestors), contemplate
+    rows see everything; slot ranges that end inside a tile, on a tile edge, and several tiles long."""
+    inp = _case(55, dtype=dtype, Hq=4, Hkv=2, D=D, P=P, T=14, C=3, s=s, q_std=1.0, kv_std=1.0)
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st)
+    if dtype == "bf16":
+        out, lse, st = H.run_attention(inp, max_prefix_len=4096, num_splits=4)      # the slots spread over key ranges
+        _check(inp, out, lse, st)
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
 def test_pool_strides_head_major_and_padded_rows(dtype, D):
     """The same K/V values in three pool layouts - token-major (the default strides), head-major
     [Hkv][rows][D], and token-major with padded rows and padded heads - give the same output bit for bit."""
