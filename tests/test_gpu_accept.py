@@ -84,6 +84,15 @@ def test_identical_draft_and_target_accepts_first_child_chain():
     assert np.all(got["final_kind"] == 0)
 
 
+def test_more_contemplate_rows_than_the_on_chip_table():
+    """200 contemplate rows per sequence (the walk kernel keeps the first 128 anchors on chip and reads the rest from
+    memory); the first 150 belong to no node, so the selected row, when there is one, lies beyond the table."""
+    inp = _batch(71, B=12, T=10, V=500, rule=RULES["det"], temp=1.0, C=200, max_depth=3, boost=4.0)
+    inp.con_anchor[:, :150] = -1
+    got = _run_and_compare(inp)
+    assert (got["selected_con"] >= 150).sum() >= 3 and np.all((got["selected_con"] == -1) | (got["selected_con"] >= 150))
+
+
 def test_padded_logit_rows():
     inp = _batch(27, B=4, T=20, V=3001, rule=RULES["wor"], temp=1.0)
     _run_and_compare(inp, row_stride=3008)

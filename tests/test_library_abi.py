@@ -89,7 +89,7 @@ def test_attention_descriptor_errors_on_host(kw):
 
 
 @pytest.mark.parametrize("kw", [dict(T=0), dict(T=129), dict(V=0), dict(rule=9), dict(temperature=0.0),
-                                dict(logits_row_stride=5)])
+                                dict(logits_row_stride=5), dict(B=2000), dict(logits_dtype=7), dict(C=-1)])
 def test_accept_descriptor_errors_on_host(kw):
     base = dict(B=1, T=60, V=1000, C=0, rule=tv.TV_RULE_DETERMINISTIC, temperature=1.0)
     base.update(kw)
