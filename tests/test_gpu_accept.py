@@ -145,6 +145,15 @@ def test_draft_rules_more_nodes_with_children_than_groups(rule):
                             max_children=2))
 
 
+@pytest.mark.parametrize("rule", ["det", "wor"])
+def test_full_vocabulary_more_sequences_than_resident_groups(rule):
+    """20 sequences at V = 128256: the final draw takes a group of 128 workgroups per sequence and only about eight
+    groups are resident, so the groups go round the sequences several times (fresh hand-off slots each time)."""
+    inp = _batch(81, B=20, T=16, V=128256, rule=RULES[rule], temp=1.0, corr=0.9, boost=4.0, max_depth=5, max_children=3)
+    got = _run_and_compare(inp)
+    assert len(set(got["final_token"].tolist())) > 10
+
+
 def test_many_uniform_draws_on_one_full_size_tree():
     """One Llama-3-sized tree, 24 different sets of uniforms (as a batch sharing logits by copy)."""
     base = si.accept_case(1, 0, draft_target_corr=0.9, child_boost=4.0)
