@@ -159,7 +159,7 @@ using namespace tv;
 
 extern "C" {
 
-int tv_version(void) { return 100; }
+int tv_version(void) { return 101; }
 
 static std::atomic<int> g_wait_limit{0};
 
