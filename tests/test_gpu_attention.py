@@ -214,6 +214,15 @@ def test_bf16_sequences_are_served_once_whatever_their_lengths():
     out, lse, st = H.run_attention(inp)
     _check(inp, out, lse, st, seqs=range(0, 70, 7))
     assert np.all(st == 0) and np.all(np.isfinite(lse))
+    # more sequences than lanes AND several key ranges (one KV head, one row block: few workgroups per sequence)
+    import paper_2603_08899_amd as tv
+    P = [int(x) for x in rng.integers(0, 2000, size=70)]
+    inp = _case(43, dtype="bf16", Hq=1, Hkv=1, D=128, P=P, T=8, C=2, B=70, q_std=1.0, kv_std=1.0)
+    assert tv.tv_attention_plan(tv.make_attn_desc(dtype=tv.TV_DTYPE_BF16, B=70, M=inp.M, Hq=1, Hkv=1, D=128, soft_len=0,
+                                                  max_prefix_len=max(P), softmax_scale=inp.scale))[1] > 1
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st, seqs=range(0, 70, 9))
+    assert np.all(st == 0) and np.all(np.isfinite(lse))
 
 
 @pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
