@@ -236,3 +236,29 @@ def test_bf16_logits_full_vocabulary(index, mode, boost):
                                                   child_boost=boost))
     got = _run_and_compare(inp, logits_dtype="bf16")
     print("accepted", int(got["n_accepted"][0]))
+
+
+# ---- seeded random draws over everything at once ----------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(20))
+def test_random_configurations(seed):
+    """Rule, temperature, batch size, tree size and shape, vocabulary size (any residue mod 8, below and above one
+    4096-entry range), contemplate rows, padded logit rows and the logits' type, all drawn together."""
+    rng = np.random.default_rng(7000 + seed)
+    rule = str(rng.choice(["greedy", "det", "wor", "wr", "match"]))
+    temp = 0.0 if rule == "greedy" else float(rng.choice([0.5, 0.7, 1.0, 1.3]))
+    B = int(rng.choice([1, 2, 7, 40]))
+    T = int(rng.integers(1, 49))
+    V = int(rng.choice([int(rng.integers(2, 200)), int(rng.integers(1000, 9000)), int(rng.integers(9000, 40000))]))
+    C = int(rng.integers(0, 4))
+    dtype = str(rng.choice(["f32", "bf16"]))
+    pad = int(rng.choice([0, 0, 1, 3, 8]))
+    inp = _batch(7100 + seed, B=B, T=T, V=V, rule=RULES[rule], temp=temp, C=C, corr=float(rng.choice([0.0, 0.9])),
+                 boost=float(rng.choice([0.0, 4.0, 8.0])), max_depth=int(rng.integers(6, 13)),
+                 max_children=int(rng.integers(2, 9)))
+    if rule in ("greedy", "det", "match"):
+        inp.draft_logits = None
+    if dtype == "bf16":
+        inp = H.logits_rounded_to_bf16(inp)
+    print(f"[random] seed {seed}: rule={rule} temp={temp} B={B} T={T} V={V} C={C} {dtype} row_stride={V + pad if pad else 0}",
+          flush=True)
+    _run_and_compare(inp, row_stride=V + pad if pad else 0, logits_dtype=dtype)

@@ -317,6 +317,38 @@ def test_malformed_sequences_are_flagged_and_zeroed(dtype, D):
         _check(inp, out, lse, st, seqs=[0])
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_bf16_random_configurations(seed):
+    """Seeded random draws over everything the launch depends on at once: batch size, head grouping, tree size
+    and layout, prefix lengths (some empty, some far below the bound), soft-prompt slots, a loose max_prefix_len,
+    forced or free workgroup shape and range count.  Each draw is checked against the oracle like the hand-picked
+    cases above."""
+    rng = np.random.default_rng(9000 + seed)
+    B = int(rng.choice([1, 1, 2, 3, 5, 9]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 3, 4, 8]))
+    layout = "interleaved" if rng.random() < 0.3 else "appended"
+    T = int(rng.integers(1, 61))
+    C = int(rng.integers(0, 5))
+    if layout == "appended" and T + C > 128: C = 0
+    top = int(rng.choice([40, 300, 1500, 5000]))
+    P = [int(x) for x in rng.integers(0, top + 1, size=B)]
+    if rng.random() < 0.3: P[int(rng.integers(0, B))] = 0
+    s_len = int(rng.integers(0, min(P) + 1)) if rng.random() < 0.4 and min(P) > 0 else 0
+    s_len = min(s_len, 70)
+    bound = max(P) * int(rng.choice([1, 1, 2, 8])) + int(rng.choice([0, 0, 33]))
+    wg = int(rng.choice([0, 0, 1, 2, 4]))
+    splits = int(rng.choice([0, 0, 0, 1, 2, 3, 7]))
+    std = float(rng.choice([0.3, 1.0]))
+    inp = _case(9100 + seed, dtype="bf16", Hq=G * Hkv, Hkv=Hkv, D=128, P=P if B > 1 else P[0], T=T, C=C, s=s_len,
+                layout=layout, B=B, q_std=std, kv_std=std, max_depth=int(rng.integers(6, 13)),
+                max_children=int(rng.integers(2, 9)))
+    print(f"[random] seed {seed}: B={B} Hq={G * Hkv} Hkv={Hkv} M={inp.M} P={P} s={s_len} bound={bound} wg={wg} splits={splits}",
+          flush=True)
+    out, lse, st = H.run_attention(inp, max_prefix_len=bound, wg_row_blocks=wg, num_splits=splits)
+    _check(inp, out, lse, st)
+
+
 # ---- the named workloads at full size -----------------------------------------------------------------------
 @pytest.mark.parametrize("index,peaked", [(1, False), (1, True), (2, False), (2, True)])
 def test_full_size_single_sequence_workloads(index, peaked):
