@@ -202,3 +202,27 @@ def test_embed_llama8b_widths():
     4096; and the draft-side module (4096 -> 4096); 64 experts, top 4."""
     _run_embed("bf16", 1, 3 * 4096, 4096, 64, 4, seed=60)
     _run_embed("bf16", 8, 4096, 4096, 64, 4, seed=61)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_commit_random_configurations(seed):
+    """Everything tree_commit's launch depends on drawn together: type, layers, batch, tree size and row layout,
+    head count and width, prefix lengths (some zero), pool padding or a head-major pool, flagged sequences."""
+    rng = np.random.default_rng(5000 + seed)
+    dtype = str(rng.choice(["bf16", "f32"]))
+    L, B, T = int(rng.integers(1, 6)), int(rng.choice([1, 2, 6, 33])), int(rng.integers(1, 41))
+    Hkv = int(rng.choice([1, 2, 8]))
+    D = int(rng.choice([64, 128])) if dtype == "f32" else int(rng.choice([64, 128, 256]))
+    interleaved = bool(rng.random() < 0.4)
+    M = 2 * T if interleaved else T + int(rng.integers(0, 5))
+    node_row = np.tile(np.arange(0, 2 * T, 2, dtype=np.int32), (B, 1)) if interleaved else None
+    path, n_acc = _random_paths(rng, B, T, int(rng.integers(6, 13)), int(rng.integers(2, 9)))
+    if B > 1 and rng.random() < 0.5:
+        n_acc[int(rng.integers(0, B))] = -1
+    plen = rng.integers(0, 70, size=B).astype(np.int32)
+    if rng.random() < 0.3:
+        plen[int(rng.integers(0, B))] = 0
+    head_major = bool(rng.random() < 0.3)
+    pad = 0 if head_major else int(rng.choice([0, 0, 3]))
+    print(f"[random] seed {seed}: {dtype} L={L} B={B} T={T} M={M} Hkv={Hkv} D={D} head_major={head_major} pad={pad}", flush=True)
+    _run_commit(dtype, L, B, T, M, Hkv, D, plen, path, n_acc, node_row, pad_tokens=pad, head_major=head_major, seed=seed)
