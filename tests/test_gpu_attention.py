@@ -349,6 +349,25 @@ def test_bf16_random_configurations(seed):
     _check(inp, out, lse, st)
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_fp32_random_configurations(seed):
+    rng = np.random.default_rng(9500 + seed)
+    B = int(rng.choice([1, 2, 5]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 3, 8]))
+    D = int(rng.choice([64, 128]))
+    layout = "interleaved" if rng.random() < 0.3 else "appended"
+    T = int(rng.integers(1, 61))
+    C = int(rng.integers(0, 5))
+    P = [int(x) for x in rng.integers(0, int(rng.choice([40, 300, 1200])) + 1, size=B)]
+    s_len = min(int(rng.integers(0, min(P) + 1)), 70) if rng.random() < 0.4 and min(P) > 0 else 0
+    inp = _case(9600 + seed, dtype="f32", Hq=G * Hkv, Hkv=Hkv, D=D, P=P if B > 1 else P[0], T=T, C=C, s=s_len,
+                layout=layout, B=B, max_depth=int(rng.integers(6, 13)), max_children=int(rng.integers(2, 9)))
+    print(f"[random] seed {seed}: B={B} Hq={G * Hkv} Hkv={Hkv} D={D} M={inp.M} P={P} s={s_len}", flush=True)
+    out, lse, st = H.run_attention(inp, max_prefix_len=max(P) * int(rng.choice([1, 4])) + 5)
+    _check(inp, out, lse, st)
+
+
 # ---- the named workloads at full size -----------------------------------------------------------------------
 @pytest.mark.parametrize("index,peaked", [(1, False), (1, True), (2, False), (2, True)])
 def test_full_size_single_sequence_workloads(index, peaked):
