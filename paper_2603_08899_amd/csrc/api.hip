@@ -94,15 +94,30 @@ int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
         const int64_t waves = (wgs + cus - 1) / cus;
         const int rounds = (n_tiles + n * streams - 1) / (n * streams);
         const double fixed = rb == 1 ? 6.5 : rb == 2 ? 11.6 : 15.5;
-        double per_round;
-        if (rb == 1) per_round = 1.60 + 0.25 * (rounds <= 17 ? 0.0 : rounds >= 33 ? 1.0 : (rounds - 17) / 16.0);
-        else if (rb == 2) per_round = 1.02 + 0.28 * (rounds <= 9 ? 0.0 : rounds >= 33 ? 1.0 : (rounds - 9) / 24.0);
-        else per_round = 1.20;
+        auto per_round = [&](double r) {
+            if (rb == 1) return 1.60 + 0.25 * (r <= 17 ? 0.0 : r >= 33 ? 1.0 : (r - 17) / 16.0);
+            if (rb == 2) return 1.02 + 0.28 * (r <= 9 ? 0.0 : r >= 33 ? 1.0 : (r - 9) / 24.0);
+            return 1.20;
+        };
+        auto wg_us = [&](double r) { return fixed + r * per_round(r); };
         const double combine = n > 1 ? 3.3 : 0.0;
-        const double longest = fixed + rounds * per_round;
-        const double spread = (double)wgs / cus * (fixed + kRaggedMean * rounds * per_round);
-        *t_uniform = (double)waves * longest + combine;
-        *t_ragged = (longest > spread ? longest : spread) + combine;
+        *t_uniform = (double)waves * wg_us(rounds) + combine;
+        // Ragged: workgroup times spread evenly from the longest sequence's down to the shortest's (lengths uniform
+        // on [2*mean - 1, 1] of the maximum), dispatched longest first.  The last workgroup ends no earlier than the
+        // longest one, than the sum over all CUs, and - with more workgroups than CUs - than a second workgroup
+        // started when the shortest of the first wave has finished.
+        const double w = (double)wgs / cus;
+        const double shortest = kRaggedMean > 0.5 ? 2.0 * kRaggedMean - 1.0 : 0.0;
+        const double t_max = wg_us(rounds), t_mean = wg_us(kRaggedMean * rounds), t_min = wg_us(shortest * rounds);
+        double t = t_max > w * t_mean ? t_max : w * t_mean;
+        if (w > 1.0 && w <= 2.0) {
+            const double two = 2.0 * (t_max - (t_max - t_min) / w);
+            if (two > t) t = two;
+        } else if (w > 2.0) {
+            const double more = w * t_mean + 0.5 * t_min;
+            if (more > t) t = more;
+        }
+        *t_ragged = t + combine;
     };
     auto allowed = [&](int rb, int n) {
         if (d.wg_row_blocks ? rb != d.wg_row_blocks : (rb_needed % rb != 0)) return false;
