@@ -226,3 +226,16 @@ def test_commit_random_configurations(seed):
     pad = 0 if head_major else int(rng.choice([0, 0, 3]))
     print(f"[random] seed {seed}: {dtype} L={L} B={B} T={T} M={M} Hkv={Hkv} D={D} head_major={head_major} pad={pad}", flush=True)
     _run_commit(dtype, L, B, T, M, Hkv, D, plen, path, n_acc, node_row, pad_tokens=pad, head_major=head_major, seed=seed)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_embed_random_configurations(seed):
+    rng = np.random.default_rng(5500 + seed)
+    dtype = str(rng.choice(["f32", "bf16"]))
+    B = int(rng.choice([1, 2, 5, 19]))
+    d_in = 8 * int(rng.integers(1, 200))
+    d_out = 8 * int(rng.integers(1, 200))
+    n_expert = int(rng.integers(1, 65))
+    k_expert = int(rng.integers(1, n_expert + 1))
+    print(f"[random] seed {seed}: {dtype} B={B} d_in={d_in} d_out={d_out} experts={n_expert} top={k_expert}", flush=True)
+    _run_embed(dtype, B, d_in, d_out, n_expert, k_expert, seed=5600 + seed)
