@@ -412,6 +412,34 @@ def test_full_size_ragged_batch_sampled_heads():
             assert np.abs(out[b, i, h] - r).max() <= REL_TOL_BF16 * np.abs(r).max() + 1e-4
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_bf16_random_large_configurations(seed):
+    """Random draws at sizes where the planner leaves the single-sequence, 64-row default: long contexts, batches
+    of unequal lengths, with and without the length hint.  Checked on two heads of every sequence."""
+    rng = np.random.default_rng(9800 + seed)
+    B = int(rng.choice([1, 2, 4, 12]))
+    Hkv, G = int(rng.choice([2, 8])), int(rng.choice([2, 4]))
+    top = int(rng.choice([9000, 20000, 45000])) if B <= 2 else int(rng.choice([3000, 9000]))
+    P = [int(x) for x in rng.integers(top // 16, top + 1, size=B)]
+    T = int(rng.integers(20, 61))
+    layout = "interleaved" if rng.random() < 0.3 else "appended"
+    inp = _case(9900 + seed, dtype="bf16", Hq=G * Hkv, Hkv=Hkv, D=128, P=P if B > 1 else P[0], T=T, C=4, layout=layout, B=B,
+                s=int(rng.choice([0, 16])), q_std=1.0, kv_std=1.0)
+    hint = sum(P) if rng.random() < 0.5 else 0
+    import paper_2603_08899_amd as tv
+    plan = tv.tv_attention_plan(tv.make_attn_desc(dtype=tv.TV_DTYPE_BF16, B=B, M=inp.M, Hq=G * Hkv, Hkv=Hkv, D=128,
+                                                  soft_len=inp.soft_len, max_prefix_len=max(P), softmax_scale=inp.scale,
+                                                  sum_prefix_len=hint))
+    print(f"[random] seed {seed}: B={B} Hq={G * Hkv} Hkv={Hkv} M={inp.M} P={P} s={inp.soft_len} hint={hint} plan={plan}", flush=True)
+    out, _, st = H.run_attention(inp, want_lse=False, sum_prefix_len=hint)
+    assert np.all(st == 0)
+    for b in range(B):
+        ref = H.oracle_attention_rows(inp, b, range(inp.M), heads=[(3 * b) % (G * Hkv), G * Hkv - 1])
+        for (i, h), r in ref.items():
+            assert np.abs(out[b, i, h] - r).max() <= 2e-2
+            assert np.abs(out[b, i, h] - r).max() <= REL_TOL_BF16 * np.abs(r).max() + 1e-4
+
+
 def test_layers_from_one_pool_back_to_back():
     """Several layers' K/V in one allocation, one launch per layer on one stream without host
     synchronisation in between (the 32-layer benchmark configuration, shortened)."""
