@@ -149,3 +149,44 @@ def test_attention_planner_choices_on_a_256_cu_device():
             rb, n = _plan(B=B, max_prefix_len=P)
             assert rb in (1, 2, 4) and 1 <= n <= 64
             assert 8 * (4 // rb) * n < 2 ** 31
+
+
+def test_a_plain_c_client_links_and_calls_the_host_entry_points(tmp_path):
+    """The boundary is a C ABI: a C99 translation unit that includes the header, links the library and calls the
+    host-only entry points (no device work) must build and agree with the Python binding."""
+    import os, shutil, subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "client.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "confu_verify.h"
+int main(void) {
+    tv_attn_desc d;
+    memset(&d, 0, sizeof d);
+    d.struct_size = sizeof d; d.dtype = TV_DTYPE_BF16; d.B = 1; d.M = 64; d.Hq = 32; d.Hkv = 8; d.D = 128;
+    d.max_prefix_len = 4096; d.softmax_scale = 0.088f;
+    size_t bytes = 0; int32_t rb = 0, n = 0;
+    int rc1 = tv_attention_workspace_bytes(&d, &bytes);
+    int rc2 = tv_attention_plan(&d, &rb, &n);
+    int32_t parent[3] = {-1, 0, 1}; uint8_t kind[3] = {0, 0, 1}; uint64_t bits[6];
+    int rc3 = tv_build_mask_host(parent, kind, 3, bits);
+    printf("%d %d %d %d %zu %d %d %llu %s\n", tv_version(), rc1, rc2, rc3, bytes, (int)rb, (int)n,
+           (unsigned long long)bits[4], tv_error_string(TV_ERR_WORKSPACE));
+    return 0;
+}
+''')
+    exe = tmp_path / "client"
+    libdir = os.path.dirname(tv.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(root, "include"), str(src), "-o", str(exe),
+                           "-L", libdir, "-l:" + os.path.basename(tv.LIB_PATH), "-Wl,-rpath," + libdir])
+    out = subprocess.check_output([str(exe)], text=True).split(None, 8)
+    d = tv.make_attn_desc(dtype=tv.TV_DTYPE_BF16, B=1, M=64, Hq=32, Hkv=8, D=128, soft_len=0, max_prefix_len=4096,
+                          softmax_scale=0.088)
+    assert int(out[0]) == tv.lib().tv_version() and out[1:4] == ["0", "0", "0"]
+    assert int(out[4]) == tv.tv_attention_workspace_bytes(d)
+    assert (int(out[5]), int(out[6])) == tv.tv_attention_plan(d)
+    assert int(out[7]) == 0b111                       # row 2 sees rows 0, 1 and itself
+    assert out[8].strip() == "workspace missing or too small"
