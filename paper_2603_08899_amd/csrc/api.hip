@@ -55,7 +55,28 @@ int check_attn_desc(const tv_attn_desc* d) {
 
 }  // namespace
 
+static int plan_attention_uncached(const tv_attn_desc& d, AttnPlan* plan);
+
+// The plan depends on the descriptor (and the device's CU count) only, and a serving loop hands over the same
+// descriptor layer after layer: each thread remembers the last one it planned (a few microseconds of host time per
+// call otherwise).  The descriptor is compared field by field as bytes; its padding-free layout makes that exact.
 int plan_attention(const tv_attn_desc& d, AttnPlan* plan) {
+    static_assert(sizeof(tv_attn_desc) == 72, "byte-wise comparison assumes a layout without padding");
+    struct Last { tv_attn_desc d; AttnPlan p; int rc; int cus; bool valid; };
+    thread_local Last last{};
+    const int cus = device_cu_count();
+    if (last.valid && last.cus == cus && std::memcmp(&last.d, &d, sizeof d) == 0) {
+        *plan = last.p;
+        return last.rc;
+    }
+    AttnPlan p{};
+    const int rc = plan_attention_uncached(d, &p);
+    last.d = d; last.p = p; last.rc = rc; last.cus = cus; last.valid = true;
+    *plan = p;
+    return rc;
+}
+
+static int plan_attention_uncached(const tv_attn_desc& d, AttnPlan* plan) {
     AttnPlan p{};
     p.G = d.Hq / d.Hkv;
     if (d.dtype == TV_DTYPE_F32) {
