@@ -88,6 +88,14 @@ def lib() -> ctypes.CDLL:
             raise ImportError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2603_08899_amd.build` "
                 "(hipcc, gfx950). There is no CPU fallback.")
+        # PyTorch ships its own copy of the HIP runtime.  If this library were loaded first it would bring in the
+        # system's copy, and the process would then hold two: a device initialised through one is not visible to
+        # the other ("No HIP GPUs are available" from torch after a host-only call such as tv_attention_plan).
+        # Importing torch first makes both use the one torch loads.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         l = ctypes.CDLL(LIB_PATH)
         vp, sz = ctypes.c_void_p, ctypes.c_size_t
         l.tv_version.restype = ctypes.c_int
