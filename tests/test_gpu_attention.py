@@ -471,3 +471,29 @@ def test_layers_from_one_pool_back_to_back():
         got = outs[l].float().cpu().numpy()[0].astype(np.float64)
         assert np.abs(got - ref).max() <= 2e-2
         assert np.abs(got - ref).max() <= REL_TOL_BF16 * np.abs(ref).max()
+
+
+def test_host_only_call_before_torch_leaves_the_gpu_usable():
+    """A fresh process that asks the library for a launch plan (a host-only call that reads the device's CU count)
+    before anything has imported torch must still get a working torch.cuda afterwards, and a correct result: the
+    binding has to make the library and PyTorch share one HIP runtime whichever is touched first."""
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = r'''
+import sys
+sys.path.insert(0, %r)
+import paper_2603_08899_amd as tv
+d = tv.make_attn_desc(dtype=tv.TV_DTYPE_F32, B=1, M=4, Hq=2, Hkv=1, D=64, soft_len=0, max_prefix_len=8, softmax_scale=0.125)
+print("plan", tv.tv_attention_plan(d), flush=True)
+import torch
+q = torch.ones((1, 4, 2, 64), device="cuda"); k = torch.ones((12, 1, 64), device="cuda"); v = 2 * torch.ones((12, 1, 64), device="cuda")
+out = torch.zeros_like(q); st = torch.zeros(1, dtype=torch.int32, device="cuda")
+tv.tree_verify_attention(d, q, k, v, torch.zeros(1, dtype=torch.int64, device="cuda"), torch.full((1,), 8, dtype=torch.int32, device="cuda"),
+                         torch.tensor([[-1, 0, 1, 2]], dtype=torch.int32, device="cuda"), torch.zeros((1, 4), dtype=torch.uint8, device="cuda"),
+                         out, None, st, None)
+torch.cuda.synchronize()
+print("status", int(st[0]), "out", float(out.min()), float(out.max()), flush=True)
+''' % root
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0, r.stderr[-800:]
+    assert "plan (1, 1)" in r.stdout and "status 0 out 2.0 2.0" in r.stdout, r.stdout
