@@ -99,8 +99,7 @@ static int plan_attention_uncached(const tv_attn_desc& d, AttnPlan* plan) {
     // long runs); one workgroup runs per CU at a time; the second kernel adds 3.3 when n > 1.
     // The lengths are on the device, so the model prices two batches: every sequence at max_prefix_len
     // (all workgroups alike: whole waves of them, waves * t), and a ragged one whose lengths average 0.55 of the
-    // longest, which is near max_prefix_len (the dispatcher evens out workgroups of unlike length, so what counts
-    // is the longest one or the sum over all CUs: U{512..8192} has that mean).  The choice is the candidate
+    // longest, which is near max_prefix_len (U{512..8192} has that mean; see t_ragged below).  The choice is the candidate
     // whose worse regret over the two is smallest; one sequence has only the first case.  With the caller's
     // sum_prefix_len the batch is known instead: equal lengths when the mean is within a tenth of the maximum,
     // else the ragged model with that mean.
@@ -108,7 +107,7 @@ static int plan_attention_uncached(const tv_attn_desc& d, AttnPlan* plan) {
     const int max_n = n_tiles / 8 > 1 ? (n_tiles / 8 < 64 ? n_tiles / 8 : 64) : 1;     // at least eight tiles per range
     const bool mean_known = d.B > 1 && d.sum_prefix_len > 0 && d.max_prefix_len > 0;
     const double known_mean = mean_known ? (double)d.sum_prefix_len / ((double)d.B * d.max_prefix_len) : 1.0;
-    const double kRaggedMean = mean_known ? known_mean : 0.55;
+    const double ragged_mean = mean_known ? known_mean : 0.55;
     auto model_us = [&](int rb, int n, double* t_uniform, double* t_ragged) {
         const int streams = 4 / rb;
         const int64_t wgs = (int64_t)d.B * d.Hkv * ((rb_needed + rb - 1) / rb) * n;
@@ -128,8 +127,8 @@ static int plan_attention_uncached(const tv_attn_desc& d, AttnPlan* plan) {
         // longest one, than the sum over all CUs, and - with more workgroups than CUs - than a second workgroup
         // started when the shortest of the first wave has finished.
         const double w = (double)wgs / cus;
-        const double shortest = kRaggedMean > 0.5 ? 2.0 * kRaggedMean - 1.0 : 0.0;
-        const double t_max = wg_us(rounds), t_mean = wg_us(kRaggedMean * rounds), t_min = wg_us(shortest * rounds);
+        const double shortest = ragged_mean > 0.5 ? 2.0 * ragged_mean - 1.0 : 0.0;
+        const double t_max = wg_us(rounds), t_mean = wg_us(ragged_mean * rounds), t_min = wg_us(shortest * rounds);
         double t = t_max > w * t_mean ? t_max : w * t_mean;
         if (w > 1.0 && w <= 2.0) {
             const double two = 2.0 * (t_max - (t_max - t_min) / w);
