@@ -116,7 +116,7 @@ static int plan_attention_uncached(const tv_attn_desc& d, AttnPlan* plan) {
         const double fixed = rb == 1 ? 6.5 : rb == 2 ? 11.6 : 15.5;
         auto per_round = [&](double r) {
             if (rb == 1) return 1.60 + 0.25 * (r <= 17 ? 0.0 : r >= 33 ? 1.0 : (r - 17) / 16.0);
-            if (rb == 2) return 1.02 + 0.28 * (r <= 9 ? 0.0 : r >= 33 ? 1.0 : (r - 9) / 24.0);
+            if (rb == 2) return 1.02 + 0.23 * (r <= 9 ? 0.0 : r >= 33 ? 1.0 : (r - 9) / 24.0);
             return 1.20;
         };
         auto wg_us = [&](double r) { return fixed + r * per_round(r); };

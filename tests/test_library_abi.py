@@ -134,7 +134,7 @@ def test_attention_planner_choices_on_a_256_cu_device():
     assert _plan(B=8, max_prefix_len=8192) == (2, 4)             # long batch: twice the CU count, for ragged lengths
     assert _plan(B=64, max_prefix_len=512)[1] == 1               # enough sequences: no split of the keys
     # the hint: the same batch shape sized for equal lengths, and for the ragged lengths of the batch-of-8 workload
-    assert _plan(B=16, max_prefix_len=2048) == (2, 2) and _plan(B=16, max_prefix_len=2048, sum_prefix_len=16 * 2048) == (2, 1)
+    assert _plan(B=16, max_prefix_len=4096) == (2, 2) and _plan(B=16, max_prefix_len=4096, sum_prefix_len=16 * 4096) == (2, 1)
     wgs = lambda plan: 8 * 8 * (4 // plan[0]) * plan[1]           # B * Hkv * row groups * ranges
     assert wgs(_plan(B=8, max_prefix_len=8192, sum_prefix_len=8 * 8192)) == 256      # equal lengths: one per CU
     assert wgs(_plan(B=8, max_prefix_len=8192, sum_prefix_len=34868)) > 256          # ragged: more, smaller ones
