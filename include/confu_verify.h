@@ -56,6 +56,7 @@ extern "C" {
 
 /* ---- limits -------------------------------------------------------------------- */
 #define TV_MAX_ROWS   128          /* M (attention) and T (acceptance) */
+#define TV_PREPARED_TREE_BYTES 2304 /* device bytes per sequence of a prepared tree (tv_prepare_tree) */
 
 /* ---- enums ---------------------------------------------------------------------- */
 #define TV_DTYPE_F32   0
@@ -127,6 +128,17 @@ int tv_attention_workspace_bytes(const tv_attn_desc* desc, size_t* out_bytes);
  * Returns TV_OK / TV_ERR_INVALID_ARG / TV_ERR_UNSUPPORTED. */
 int tv_attention_plan(const tv_attn_desc* desc, int32_t* wg_row_blocks, int32_t* key_ranges);
 
+/* Optional, once per verification step (paper: Section 3.1 / Figure 4 - the tree mask belongs to the step and
+ * is the same in every layer): checks the B trees and writes, per sequence, the ancestor mask of every row, the
+ * row kinds and the verdict (TV_STATUS_BAD_PARENT / TV_STATUS_BAD_KIND bits) into `prepared` (device, 16-byte
+ * aligned, B * TV_PREPARED_TREE_BYTES bytes, owned by the caller).  Layer calls of tree_verify_attention that
+ * are handed `prepared` skip their own checks and ancestor walks; results and status are the same either way.
+ * parent / kind: device [B, M] as for tree_verify_attention.  Enqueued on hip_stream, no synchronisation; the
+ * record must not be rewritten while calls that read it are in flight.
+ * Returns TV_OK / TV_ERR_INVALID_ARG / TV_ERR_LAUNCH. */
+int tv_prepare_tree(int32_t B, int32_t M, const int32_t* parent, const uint8_t* kind, void* prepared,
+                    size_t prepared_bytes, void* hip_stream);
+
 int tree_verify_attention(
     const tv_attn_desc* desc,      /* host */
     const void*    q,              /* device [B, M, Hq, D], dtype, contiguous */
@@ -136,6 +148,9 @@ int tree_verify_attention(
     const int32_t* prefix_len,     /* device [B]: P_b, soft-prompt slots included */
     const int32_t* parent,         /* device [B, M]: parent row, -1 for the root, parent[i] < i */
     const uint8_t* kind,           /* device [B, M]: TV_KIND_* */
+    const void*    prepared_tree,  /* device: what tv_prepare_tree wrote for these B trees (same parent / kind), or NULL:
+                                      the call then checks the trees and builds the masks itself.  Used by the bf16
+                                      path; the fp32 path always builds its own */
     void*          out,            /* device [B, M, Hq, D], dtype */
     float*         lse,            /* device [B, Hq, M] natural-log sum of exp of the scaled visible scores, or NULL */
     int32_t*       status,         /* device [B]: TV_STATUS_* bits, written by the call */

@@ -20,13 +20,14 @@ TV_STATUS_BAD_PARENT, TV_STATUS_BAD_KIND, TV_STATUS_BAD_PREFIX, TV_STATUS_BAD_TO
 TV_STATUS_INTERNAL = 16
 TV_STATUS_BAD_PATH = 32
 TV_MAX_ROWS = 128
+TV_PREPARED_TREE_BYTES = 2304
 TV_DTYPE_F32, TV_DTYPE_BF16 = 0, 1
 TV_KIND_NODE, TV_KIND_CONTEMPLATE = 0, 1
 TV_RULE_GREEDY, TV_RULE_DETERMINISTIC, TV_RULE_DRAFT_WOR, TV_RULE_DRAFT_WR, TV_RULE_SAMPLE_MATCH = 0, 1, 2, 3, 4
 TV_FINAL_BONUS, TV_FINAL_RESIDUAL = 0, 1
 
 EXPORTED_SYMBOLS = (
-    "tv_attention_workspace_bytes", "tv_attention_plan", "tree_verify_attention",
+    "tv_attention_workspace_bytes", "tv_attention_plan", "tv_prepare_tree", "tree_verify_attention",
     "tv_accept_workspace_bytes", "tree_accept",
     "tree_commit", "contemplate_embed", "tv_embed_workspace_bytes",
     "tv_build_mask_host", "tv_error_string", "tv_version", "tv_set_wait_limit",
@@ -111,7 +112,9 @@ def lib() -> ctypes.CDLL:
         l.tv_attention_plan.argtypes = [ctypes.POINTER(tv_attn_desc), ctypes.POINTER(ctypes.c_int32),
                                         ctypes.POINTER(ctypes.c_int32)]
         l.tree_verify_attention.restype = ctypes.c_int
-        l.tree_verify_attention.argtypes = [ctypes.POINTER(tv_attn_desc)] + [vp] * 11 + [sz, vp]
+        l.tree_verify_attention.argtypes = [ctypes.POINTER(tv_attn_desc)] + [vp] * 12 + [sz, vp]
+        l.tv_prepare_tree.restype = ctypes.c_int
+        l.tv_prepare_tree.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp, vp, sz, vp]
         l.tv_accept_workspace_bytes.restype = ctypes.c_int
         l.tv_accept_workspace_bytes.argtypes = [ctypes.POINTER(tv_accept_desc), ctypes.POINTER(sz)]
         l.tree_accept.restype = ctypes.c_int
@@ -192,13 +195,23 @@ def tv_build_mask_host(parent, kind):
     return bits
 
 
+def tv_prepare_tree(parent, kind, prepared, stream=None) -> None:
+    """parent int32 [B, M], kind uint8 [B, M], prepared uint8 [>= B * TV_PREPARED_TREE_BYTES] (torch CUDA tensors):
+    checks the trees and writes their ancestor masks once for all layers of a verification step."""
+    B, M = parent.shape
+    rc = lib().tv_prepare_tree(int(B), int(M), _ptr(parent), _ptr(kind), _ptr(prepared),
+                               prepared.numel() * prepared.element_size(), _stream_handle(stream))
+    if rc:
+        raise ConfuVerifyError(rc, "tv_prepare_tree")
+
+
 def tree_verify_attention(desc: tv_attn_desc, q, k_pool, v_pool, kv_offset, prefix_len, parent, kind,
-                          out, lse, status, workspace, stream=None) -> None:
-    """All tensor arguments are torch CUDA tensors (lse / workspace may be None); see
+                          out, lse, status, workspace, stream=None, prepared_tree=None) -> None:
+    """All tensor arguments are torch CUDA tensors (lse / workspace / prepared_tree may be None); see
     include/confu_verify.h for shapes.  Enqueues on `stream` (default: torch's current stream)."""
     rc = lib().tree_verify_attention(
         ctypes.byref(desc), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(kv_offset), _ptr(prefix_len),
-        _ptr(parent), _ptr(kind), _ptr(out), _ptr(lse), _ptr(status), _ptr(workspace),
+        _ptr(parent), _ptr(kind), _ptr(prepared_tree), _ptr(out), _ptr(lse), _ptr(status), _ptr(workspace),
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc:
         raise ConfuVerifyError(rc, "tree_verify_attention")

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libconfu_verify.so")
-SOURCES = ["api.hip", "attn_f32.hip", "attn_bf16.hip", "accept.hip", "bookkeeping.hip"]
+SOURCES = ["api.hip", "tree_prep.hip", "attn_f32.hip", "attn_bf16.hip", "accept.hip", "bookkeeping.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

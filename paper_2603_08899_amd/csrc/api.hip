@@ -194,7 +194,7 @@ using namespace tv;
 
 extern "C" {
 
-int tv_version(void) { return 101; }
+int tv_version(void) { return 200; }
 
 static std::atomic<int> g_wait_limit{0};
 
@@ -238,7 +238,8 @@ int tv_attention_workspace_bytes(const tv_attn_desc* desc, size_t* out_bytes) {
     const int rc = check_attn_desc(desc);
     if (rc != TV_OK) return rc;
     AttnPlan p;
-    plan_attention(*desc, &p);
+    const int prc = plan_attention(*desc, &p);
+    if (prc != TV_OK) return prc;
     *out_bytes = p.total_bytes;
     return TV_OK;
 }
@@ -255,24 +256,35 @@ int tv_attention_plan(const tv_attn_desc* desc, int32_t* wg_row_blocks, int32_t*
     return TV_OK;
 }
 
+int tv_prepare_tree(int32_t B, int32_t M, const int32_t* parent, const uint8_t* kind, void* prepared,
+                    size_t prepared_bytes, void* hip_stream) {
+    if (B < 1 || B > 65535 || M < 1 || M > TV_MAX_ROWS || !parent || !kind || !prepared) return TV_ERR_INVALID_ARG;
+    if (((uintptr_t)prepared & 15) || prepared_bytes < (size_t)B * TV_PREPARED_TREE_BYTES) return TV_ERR_INVALID_ARG;
+    const hipError_t e = launch_prepare_tree(parent, kind, B, M, static_cast<PreparedTree*>(prepared),
+                                             static_cast<hipStream_t>(hip_stream));
+    return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;
+}
+
 int tree_verify_attention(const tv_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
                           const int64_t* kv_offset, const int32_t* prefix_len, const int32_t* parent,
-                          const uint8_t* kind, void* out, float* lse, int32_t* status, void* workspace,
-                          size_t workspace_bytes, void* hip_stream) {
+                          const uint8_t* kind, const void* prepared_tree, void* out, float* lse, int32_t* status,
+                          void* workspace, size_t workspace_bytes, void* hip_stream) {
     const int rc = check_attn_desc(desc);
     if (rc != TV_OK) return rc;
     if (!q || !k_pool || !v_pool || !kv_offset || !prefix_len || !parent || !kind || !out || !status)
         return TV_ERR_INVALID_ARG;
-    const uintptr_t align_or = (uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)out;
+    const uintptr_t align_or = (uintptr_t)q | (uintptr_t)k_pool | (uintptr_t)v_pool | (uintptr_t)out | (uintptr_t)prepared_tree;
     if (align_or & 15) return TV_ERR_INVALID_ARG;
     AttnPlan p;
-    plan_attention(*desc, &p);
+    const int prc = plan_attention(*desc, &p);
+    if (prc != TV_OK) return prc;
     if (p.total_bytes > 0) {
         if (!workspace || workspace_bytes < p.total_bytes || ((uintptr_t)workspace & 255)) return TV_ERR_WORKSPACE;
     }
     AttnArgs a{};
     a.q = q; a.k = k_pool; a.v = v_pool;
     a.kv_offset = kv_offset; a.prefix_len = prefix_len; a.parent = parent; a.kind = kind;
+    a.prepared = static_cast<const unsigned char*>(prepared_tree);
     a.out = out; a.lse = lse; a.status = status;
     a.part_o = workspace;
     a.part_ml = p.total_bytes ? reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + p.part_o_bytes) : nullptr;

@@ -60,10 +60,16 @@ struct Bf16Smem {
     unsigned char big[kRingBytes];         // K/V stage ring, later the merge buffer [256 rows][32 float4]
     float ml[kWgRows][2];                  // (max, sum) of every wave's rows
     int parent[kMaxRows];
-    unsigned char kind[kMaxRows];
+    int kind[kMaxRows];                    // low byte = TV_KIND_* (a one-byte direct-to-LDS load fills one dword per row)
     unsigned long long bits[kMaxRows][2];  // ancestor mask of every row (only filled where masked tiles occur)
+    int prep_status[kWave];                // verdict of a prepared tree (entry 0; a direct-to-LDS load fills all)
     int flag;
 };
+// 64-row workgroups stage their query block behind the struct, in an area of its own: the whole stage ring then
+// takes K/V tiles from the first instruction on (160 KB of LDS hold 128 KB of ring, 16 KB of Q and the rest).
+constexpr int kQAreaOffset = (sizeof(Bf16Smem) + 1023) / 1024 * 1024;
+constexpr int kQAreaBytes = kQRows * kRowBytes;
+template <int RB> constexpr int smem_bytes() { return RB == 1 ? kQAreaOffset + kQAreaBytes : (int)sizeof(Bf16Smem); }
 
 __device__ __forceinline__ float cross_half_max(float x) {
     // permlane32_swap(a, b) returns {[a.lo, b.lo], [a.hi, b.hi]}: with a = b = x both halves see both values
@@ -96,6 +102,17 @@ __device__ __forceinline__ void dma16(unsigned lds_addr, unsigned long long sbas
     const unsigned long long sb = ((unsigned long long)hi << 32) | lo;
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(m), "v"(voff), "s"(sb) : "memory", "m0");
+}
+// The same with 4 bytes (or one zero-extended byte) per lane: lane l lands at lds_addr + 4*l.
+__device__ __forceinline__ void dma4(unsigned lds_addr, unsigned long long sbase, unsigned voff) {
+    const unsigned m = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :: "s"(m), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+__device__ __forceinline__ void dma1(unsigned lds_addr, unsigned long long sbase, unsigned voff) {
+    const unsigned m = __builtin_amdgcn_readfirstlane(lds_addr);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_ubyte %1, %2"
+                 :: "s"(m), "v"(voff), "s"(sbase) : "memory", "m0");
 }
 // A wave-uniform pointer as a scalar value the assembler operand above accepts (pins it to SGPRs even when
 // the compiler cannot prove uniformity).
@@ -195,15 +212,46 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
         kv_first_row = kv_offset[b];
     }
 
-    // ---- Q for this wave's rows: HBM -> LDS (the upper half of the stream's ring is free at this point) -
-    // The 32-row query block is laid out like a K tile, with the same segment swizzle.
+    // ---- tree rows (64-row workgroups): parent and kind - or, from a prepared tree, the ancestor masks, kinds and
+    //      verdict - go straight into LDS, requested by wave 0 ahead of everything else, so that the wait for the
+    //      query block below covers them and no register load makes the compiler wait for the tiles requested in
+    //      between -----------------------------------------------------------------------------------------
+    const PreparedTree* prep = a.prepared ? reinterpret_cast<const PreparedTree*>(a.prepared) + b : nullptr;
+    if (RB == 1 && wave == 0) {
+        if (prep) {
+            const unsigned long long prep_base = scalar_base(prep);
+            for (int j = 0; j < (M + kWave - 1) / kWave; ++j) {   // (the record holds kMaxRows rows, zeros past M)
+                const unsigned row = (unsigned)(j * kWave + lane);
+                dma16(lds_address(&sm.bits[j * kWave][0]), prep_base, (unsigned)offsetof(PreparedTree, bits) + row * 16u);
+                dma1(lds_address(&sm.kind[j * kWave]), prep_base, (unsigned)offsetof(PreparedTree, kind) + row);
+            }
+            dma4(lds_address(&sm.prep_status[0]), prep_base, (unsigned)offsetof(PreparedTree, status));
+        } else {
+            const unsigned long long par_base = scalar_base(a.parent + (int64_t)b * M);
+            const unsigned long long kind_base = scalar_base(a.kind + (int64_t)b * M);
+            for (int j = 0; j < (M + kWave - 1) / kWave; ++j) {   // rows past M repeat row M-1 (never looked at)
+                const unsigned row = (unsigned)min(j * kWave + lane, M - 1);
+                dma4(lds_address(&sm.parent[j * kWave]), par_base, row * 4u);
+                dma1(lds_address(&sm.kind[j * kWave]), kind_base, row);
+            }
+        }
+    }
+
+    // ---- Q for this wave's rows: HBM -> LDS -----------------------------------------------------------
+    // A 32-row slice of the query block is laid out like a K tile, with the same segment swizzle.  64-row
+    // workgroups keep the block (two slices) in its own area and every wave requests an eighth of it; the larger
+    // shapes stage each stream's slices in the upper half of its ring, which is free at this point.
     const int q_off = (S / 2) * kStageBytes + wsub * kTileBytes;
+    const unsigned q_slice_addr = (RB == 1) ? lds_address(smem_raw + kQAreaOffset) + wsub * kTileBytes
+                                            : ring_addr + q_off;
     {
-        const unsigned q_stage = __builtin_amdgcn_readfirstlane(ring_addr + q_off);
+        const unsigned q_stage = __builtin_amdgcn_readfirstlane(q_slice_addr);
         const unsigned long long q_sbase =
             scalar_base(static_cast<const unsigned char*>(a.q) + (int64_t)b * M * a.Hq * (kD * 2));
+        constexpr int kQLoads = (RB == 1) ? 2 : 8;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int jj = 0; jj < kQLoads; ++jj) {
+            const int j = (RB == 1) ? 2 * st + jj : jj;
             const int row = 4 * j + l_row;            // row inside the query block: selects the swizzle
             const int r = min(row0 + row, n_rows - 1);                 // padding rows re-read the last packed row
             const int hl = (int)(((float)r + 0.5f) * a.inv_M);         // r / M (exact for these sizes)
@@ -227,6 +275,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
     const int n_my = bad_prefix ? 0 : tiles_per_slot + (slot < extra ? 1 : 0);
     // the longest stream of the workgroup is its first one
     const int n_iter = bad_prefix ? 0 : tiles_per_slot + (slot0 < extra ? 1 : 0);
+    auto tile_of = [&](int it) { return t_begin + it; };
 
     const int64_t seq_base = (kv_first_row * a.tok_stride + (int64_t)g * a.head_stride) * 2;
     const unsigned char* kbase = static_cast<const unsigned char*>(a.k) + seq_base;
@@ -246,55 +295,71 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
     for (int pi = 0; pi < NP; ++pi)
         k_lane[pi] = (unsigned)l_row * tok_bytes + (unsigned)((l_seg ^ l_row ^ (4 * ((pi * WPS + wsub) & 3))) << 4);
     const unsigned v_lane = (unsigned)l_row * tok_bytes + (unsigned)((l_seg ^ (l_row << 2)) << 4);
-    auto issue_half = [&](int t, int stage, int half) {      // half 0: K rows, half 1: V rows
+    // piece jj (0 .. PER/2-1) of one half of a tile: one request instruction of this wave
+    auto issue_piece = [&](int t, int stage, int half, int jj) __attribute__((always_inline)) {      // half 0: K rows, half 1: V rows
         const int k0 = t * kTK;
         const unsigned dst = __builtin_amdgcn_readfirstlane(ring_addr + stage * kStageBytes + half * kTileBytes);
         const unsigned char* base = half ? vbase : kbase;
         if (k0 + kTK <= Lk) {
             const unsigned long long tile_base = scalar_base(base + (size_t)k0 * tok_bytes);
-#pragma unroll
-            for (int jj = 0; jj < PER / 2; ++jj) {
-                const int jb = (jj * WPS + wsub) & 7;        // 4-row block of this instruction
-                dma16(dst + jb * 1024, tile_base + (unsigned long long)(4 * jb) * tok_bytes,
-                      half ? v_lane : k_lane[jj % NP]);
-            }
+            const int jb = (jj * WPS + wsub) & 7;        // 4-row block of this instruction
+            dma16(dst + jb * 1024, tile_base + (unsigned long long)(4 * jb) * tok_bytes, half ? v_lane : k_lane[jj % NP]);
         } else {                                             // last tile: never read past the sequence's rows
-#pragma unroll
-            for (int jj = 0; jj < PER / 2; ++jj) {
-                const int j = (half * (PER / 2) + jj) * WPS + wsub;
-                const int row = 4 * (j & 7) + l_row;
-                const unsigned key = (unsigned)min(k0 + row, Lk - 1);
-                const int seg = half ? (l_seg ^ (l_row << 2)) : (l_seg ^ (row & 15));
-                dma16(dst + (j & 7) * 1024, scalar_base(base), key * tok_bytes + (unsigned)(seg * 16));
-            }
+            const int j = (half * (PER / 2) + jj) * WPS + wsub;
+            const int row = 4 * (j & 7) + l_row;
+            const unsigned key = (unsigned)min(k0 + row, Lk - 1);
+            const int seg = half ? (l_seg ^ (l_row << 2)) : (l_seg ^ (row & 15));
+            dma16(dst + (j & 7) * 1024, scalar_base(base), key * tok_bytes + (unsigned)(seg * 16));
         }
     };
-    auto issue_tile = [&](int t, int stage) { issue_half(t, stage, 0); issue_half(t, stage, 1); };
+    auto issue_half = [&](int t, int stage, int half) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < S / 2; ++i)
-        if (i < n_my) issue_tile(t_begin + i, i);
+        for (int jj = 0; jj < PER / 2; ++jj) issue_piece(t, stage, half, jj);
+    };
+    auto issue_tile = [&](int t, int stage) { issue_half(t, stage, 0); issue_half(t, stage, 1); };
+    // 64-row workgroups fill both stages of every stream here; the others the lower half of their rings
+    constexpr int kFirstTiles = (RB == 1) ? S : S / 2;
+#pragma unroll
+    for (int i = 0; i < kFirstTiles; ++i)
+        if (i < n_my) issue_tile(tile_of(i), i);
 
-    // ---- tree, validation (ordinary loads: the wait the compiler puts before the LDS writes also covers
-    //      everything requested above, which is needed next anyway) ---------------------------------------
-    int my_parent = -1, my_kind = TV_KIND_NODE;          // row tid (M <= 128 < kThreads)
-    if (tid < M) {
-        my_parent = a.parent[(int64_t)b * M + tid];
-        my_kind = a.kind[(int64_t)b * M + tid];
-        sm.parent[tid] = my_parent;
-        sm.kind[tid] = (unsigned char)my_kind;
+    // ---- tree, validation ------------------------------------------------------------------------------
+    if (RB == 1) {
+        // everything requested before the tiles (tree rows, query block) has landed once no more than the tile
+        // requests are outstanding
+        if (n_my >= 2) wait_vmcnt<2 * PER>();
+        else if (n_my == 1) wait_vmcnt<PER>();
+        else wait_vmcnt<0>();
+    } else {
+        // ordinary loads: the wait the compiler puts before the LDS writes also covers everything requested above
+        if (tid < M) {
+            if (prep) {
+                sm.bits[tid][0] = prep->bits[tid][0];
+                sm.bits[tid][1] = prep->bits[tid][1];
+                sm.kind[tid] = prep->kind[tid];
+            } else {
+                sm.parent[tid] = a.parent[(int64_t)b * M + tid];
+                sm.kind[tid] = a.kind[(int64_t)b * M + tid];
+            }
+        }
+        if (prep && tid == 0) sm.prep_status[0] = prep->status;
+        wait_vmcnt<0>();
     }
     if (tid == 0) sm.flag = 0;
-    wait_vmcnt<0>();
     __syncthreads();
     // Row tid checks itself; a workgroup whose key range meets masked tiles (soft-prompt slots, new rows, the
     // tail) also walks the row's ancestors once and leaves the two mask words in LDS.  The walk only follows
     // parents that are smaller than the row they belong to, so it ends whatever the other rows hold.
-    int bad = 0;
-    if (tid < M) {
+    // With a prepared tree all of this was done once for the step: only the verdict is taken over.
+    if (prep) {
+        if (tid == 0) sm.flag = sm.prep_status[0];
+    } else if (tid < M) {                                 // row tid (M <= 128 < kThreads)
+        const int my_parent = sm.parent[tid], my_kind = sm.kind[tid] & 0xff;
+        int bad = 0;
         if (my_parent < -1 || my_parent >= tid) bad |= TV_STATUS_BAD_PARENT;
         if (my_kind != TV_KIND_NODE && my_kind != TV_KIND_CONTEMPLATE) bad |= TV_STATUS_BAD_KIND;
         else if (my_parent >= 0 && my_parent < tid && my_kind == TV_KIND_NODE &&
-                 sm.kind[my_parent] == TV_KIND_CONTEMPLATE)
+                 (sm.kind[my_parent] & 0xff) == TV_KIND_CONTEMPLATE)
             bad |= TV_STATUS_BAD_KIND;
         const int wg_t_begin = slot0 * tiles_per_slot + min(slot0, extra);
         const int wg_t_end = (slot0 + NS) * tiles_per_slot + min(slot0 + NS, extra);
@@ -309,8 +374,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
             sm.bits[tid][0] = w0;
             sm.bits[tid][1] = w1;
         }
+        if (bad) atomicOr(&sm.flag, bad);     // looked at after the next barrier
     }
-    if (bad) atomicOr(&sm.flag, bad);     // looked at after the next barrier (the one that follows the Q reads)
 
     // per-lane LDS offsets of the MFMA operands inside a tile
     // K (A operand of S^T): row ln, logical segment 2*ks + hf, stored at segment (2*ks + hf) ^ (ln & 15): the
@@ -331,7 +396,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
     // ---- this lane's query (column ln of the query block): B operands of S^T, kept in registers ---------
     bf16x8 qreg[8];
     {
-        const unsigned q_it = ring_addr + q_off + k_base;
+        const unsigned q_it = q_slice_addr + k_base;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qreg[ks] = *(lds_b128_ptr)(q_it ^ (ks << 5));
     }
@@ -340,11 +405,12 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
         return r - (int)(((float)r + 0.5f) * a.inv_M) * M;             // r % M
     }();
     __syncthreads();         // the Q staging area goes back to the ring; every row's verdict is in sm.flag
-    bad = sm.flag;
+    int bad = sm.flag;
     if (bad_prefix) bad |= TV_STATUS_BAD_PREFIX;
     if (blockIdx.x == 0 && tid == 0) a.status[b] = bad;
     unsigned short* out16 = static_cast<unsigned short*>(a.out);
     if (bad) {
+        wait_vmcnt<0>();             // (tiles requested above land before the workgroup gives its LDS back)
         if (a.n_chunks == 1) {       // otherwise the combine kernel writes the zeros
             for (int idx = tid; idx < RB * kQRows * kD; idx += kThreads) {
                 const int r = rbg * RB * kQRows + idx / kD;
@@ -360,8 +426,8 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
     }
 
 #pragma unroll
-    for (int i = S / 2; i < (RB == 1 ? S - 1 : S); ++i)       // RB = 1 keeps one stage back for the tile in use
-        if (i < n_my) issue_tile(t_begin + i, i);
+    for (int i = kFirstTiles; i < (RB == 1 ? S - 1 : S); ++i)       // (64-row workgroups have filled their ring)
+        if (i < n_my) issue_tile(tile_of(i), i);
 
     const float c = a.scale * kLog2e;
     float m_run = -INFINITY, l_run = 0.f;       // running max in log2 units (score * c); this lane's share of the sum
@@ -408,10 +474,10 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
     // Mask of a tile that touches the soft-prompt slots, the new rows or the tail (a few tiles per sequence):
     // from the row's ancestor mask, left in LDS by the prologue
     auto mask_tile = [&](int it, f32x16& s) __attribute__((always_inline)) {
-        const int k0 = (t_begin + it) * kTK;
+        const int k0 = tile_of(it) * kTK;
         if ((k0 < a.soft_len) || (k0 + kTK > P)) {
             const unsigned long long bits0 = sm.bits[tree_row][0], bits1 = sm.bits[tree_row][1];
-            const bool is_con = (sm.kind[tree_row] == TV_KIND_CONTEMPLATE);
+            const bool is_con = ((sm.kind[tree_row] & 0xff) == TV_KIND_CONTEMPLATE);
             const unsigned vis = tile_visibility(k0, P, a.soft_len, is_con, bits0, bits1) >> (4 * hf);
 #pragma unroll
             for (int j = 0; j < 16; ++j) s[j] = (vis & (1u << (8 * (j >> 2) + (j & 3)))) ? s[j] : -INFINITY;
@@ -461,7 +527,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
         // refilled separately, each by the stream's own waves right after the barrier that follows its last
         // read: the K half with K(t+2) when the slot of phase B(t) opens, the V half with V(t+2) when the slot
         // of phase A(t+1) opens - three slots (a round and a half) ahead of their use.  Requests of a wave, in
-        // order: K0 V0 (prologue) K1 V1 | K2 | V2 | K3 | V3 ...  Both halves of the workgroup run their own copy
+        // order: K0 V0 K1 V1 (prologue) | K2 | V2 | K3 | V3 ...  Both halves of the workgroup run their own copy
         // of the loop (2*n_iter+1 barriers each): with the phase order fixed the accumulators stay in place.
         bf16x8 va[8], pb[2];     // V^T operands and probabilities of the previous tile
 #pragma unroll
@@ -475,15 +541,18 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
         f32x16 s;
 #pragma unroll
         for (int j = 0; j < 16; ++j) s[j] = 0.f;
-        if (1 < n_my) issue_tile(t_begin + 1, 1);      // K1, V1: the Q staging area is free
         // opens the slot of phase A(t): K(t) has landed (younger requests: V(t), K(t+1)); V(t+1) may be requested
         auto open_a = [&](int t) __attribute__((always_inline)) {
             if (t < n_my) {
-                if (t + 1 < n_my) wait_vmcnt<PER>();
-                else wait_vmcnt<PER / 2>();
+                if (t + 1 < n_my) {
+                    if (t == 0) wait_vmcnt<3 * PER / 2>();      // (V0, K1 and V1 were all requested in the prologue)
+                    else wait_vmcnt<PER>();
+                } else {
+                    wait_vmcnt<PER / 2>();
+                }
             }
             __syncthreads();
-            if (t >= 1 && t + 1 < n_my) issue_half(t_begin + t + 1, (t + 1) % S, 1);
+            if (t >= 1 && t + 1 < n_my) issue_half(tile_of(t + 1), (t + 1) % S, 1);
         };
         // opens the slot of phase B(t): V(t) has landed (younger requests: K(t+1), V(t+1)); K(t+2) may be requested
         auto open_b = [&](int t) __attribute__((always_inline)) {
@@ -492,7 +561,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
                 else wait_vmcnt<0>();
             }
             __syncthreads();
-            if (t >= 0 && t + 2 < n_my) issue_half(t_begin + t + 2, t % S, 0);
+            if (t >= 0 && t + 2 < n_my) issue_half(tile_of(t + 2), t % S, 0);
         };
         auto phase_a = [&](int t) __attribute__((always_inline)) {
             bf16x8 ka[8];        // all eight reads are requested before the first product (no read waits on a product)
@@ -564,7 +633,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
         // the barrier that opens slot 2t+1; the stage of tile t-1 is free from here on
         auto open_odd = [&](int t) __attribute__((always_inline)) {
             __syncthreads();
-            if (t >= 1 && t - 1 + S < n_my) issue_tile(t_begin + t - 1 + S, (t - 1) % S);
+            if (t >= 1 && t - 1 + S < n_my) issue_tile(tile_of(t - 1 + S), (t - 1) % S);
         };
         auto phase_a = [&](int t) __attribute__((always_inline)) {
             bf16x8 ka[8];
@@ -748,12 +817,12 @@ hipError_t launch_variant(const AttnArgs& a, hipStream_t s) {
     const unsigned bit = 1u << (dev & 31);
     if (!(attr_done.load(std::memory_order_acquire) & bit)) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bf16_kernel<RB>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Bf16Smem));
+                                hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes<RB>());
         if (e != hipSuccess) return e;
         attr_done.fetch_or(bit, std::memory_order_release);
     }
     const dim3 grid(a.Hkv * (a.row_blocks / RB) * a.n_chunks, a.B);
-    attn_bf16_kernel<RB><<<grid, 512, sizeof(Bf16Smem), s>>>(a.prefix_len, a.kv_offset, a.B, a);
+    attn_bf16_kernel<RB><<<grid, 512, smem_bytes<RB>(), s>>>(a.prefix_len, a.kv_offset, a.B, a);
     return hipGetLastError();
 }
 

@@ -34,6 +34,7 @@ struct AttnArgs {
     const int32_t* prefix_len;
     const int32_t* parent;
     const uint8_t* kind;
+    const unsigned char* prepared;     // [B] PreparedTree records written by tv_prepare_tree, or null
     void* out;
     float* lse;
     int32_t* status;
@@ -47,6 +48,17 @@ struct AttnArgs {
     int row_blocks, n_chunks, rb_per_wg;
 };
 
+// What tv_prepare_tree leaves per sequence: the ancestor mask of every row (Section 3.1 / Figure 4: one mask per
+// verification step, shared by all layers), the row kinds, and the verdict of the tree checks.
+struct PreparedTree {
+    unsigned long long bits[kMaxRows][2];   // zeros when the tree is malformed
+    unsigned char kind[kMaxRows];
+    int32_t status;                         // TV_STATUS_BAD_PARENT / TV_STATUS_BAD_KIND bits
+    unsigned char pad[TV_PREPARED_TREE_BYTES - kMaxRows * 16 - kMaxRows - 4];
+};
+static_assert(sizeof(PreparedTree) == TV_PREPARED_TREE_BYTES, "record size is part of the ABI");
+
+hipError_t launch_prepare_tree(const int32_t* parent, const uint8_t* kind, int B, int M, PreparedTree* out, hipStream_t s);
 hipError_t launch_attention_f32(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attention_bf16(const AttnArgs& a, hipStream_t s);
 

@@ -22,8 +22,9 @@ def to_device_storage(arr: np.ndarray, dtype: str):
 
 def run_attention(inp: AttnInputs, *, want_lse: bool = True, num_splits: int = 0, max_prefix_len=None,
                   device_inputs=None, wg_row_blocks: int = 0, sum_prefix_len: int = 0,
-                  kv_token_stride: int = 0, kv_head_stride: int = 0):
-    """Returns (out float64 [B,M,Hq,D], lse float64 [B,Hq,M] or None, status int32 [B])."""
+                  kv_token_stride: int = 0, kv_head_stride: int = 0, prepare: bool = False):
+    """Returns (out float64 [B,M,Hq,D], lse float64 [B,Hq,M] or None, status int32 [B]).
+    prepare=True: the trees go through tv_prepare_tree first and the call is handed the prepared record."""
     import paper_2603_08899_amd as tv
     torch = _torch()
     dt = tv.TV_DTYPE_BF16 if inp.dtype == "bf16" else tv.TV_DTYPE_F32
@@ -48,7 +49,11 @@ def run_attention(inp: AttnInputs, *, want_lse: bool = True, num_splits: int = 0
     status = torch.full((inp.B,), -7, device="cuda", dtype=torch.int32)
     wsb = tv.tv_attention_workspace_bytes(desc)
     ws = torch.empty(max(wsb, 256), device="cuda", dtype=torch.uint8)
-    tv.tree_verify_attention(desc, q, k, v, kv_off, plen, parent, kind, out, lse, status, ws)
+    prepared = None
+    if prepare:
+        prepared = torch.full((inp.B * tv.TV_PREPARED_TREE_BYTES,), 0xA5, device="cuda", dtype=torch.uint8)
+        tv.tv_prepare_tree(parent, kind, prepared)
+    tv.tree_verify_attention(desc, q, k, v, kv_off, plen, parent, kind, out, lse, status, ws, prepared_tree=prepared)
     torch.cuda.synchronize()
     o = out.float().cpu().numpy().astype(np.float64)
     l = None if lse is None else lse.cpu().numpy().astype(np.float64)

@@ -30,7 +30,9 @@ def _check(inp, out, lse, status, *, seqs=None, rel=True):
             assert err <= REL_TOL_BF16 * np.abs(ref).max(), f"seq {b}: {err:.3e} vs scale {np.abs(ref).max():.3e}"
         if lse is not None:
             lerr = np.abs(lse[b] - ref_lse).max()
-            assert lerr <= (1e-5 * max(1.0, np.abs(ref_lse).max()) if inp.dtype == "f32" else 2e-2), f"lse err {lerr:.3e}"
+            # bf16 path: scores come from exact bf16 inputs with fp32 accumulation and the row sums are kept in fp32
+            # (only the weights handed to the PV product are rounded), so the log-sum-exp is good to fp32 level
+            assert lerr <= (1e-5 * max(1.0, np.abs(ref_lse).max()) if inp.dtype == "f32" else 1e-3), f"lse err {lerr:.3e}"
         worst = max(worst, err)
     return worst
 
@@ -317,6 +319,76 @@ def test_malformed_sequences_are_flagged_and_zeroed(dtype, D):
         _check(inp, out, lse, st, seqs=[0])
 
 
+@pytest.mark.parametrize("dtype,D,Hq,Hkv,T,C,P,s,layout,wg,splits", [
+    ("bf16", 128, 8, 2, 60, 4, [700], 0, "appended", 1, 0),
+    ("bf16", 128, 8, 2, 60, 4, [700], 16, "appended", 1, 3),
+    ("bf16", 128, 8, 2, 60, 60, [300], 16, "interleaved", 0, 0),          # 120 rows: both mask words
+    ("bf16", 128, 6, 2, 37, 3, [0, 900, 64, 5], 0, "appended", 2, 2),
+    ("bf16", 128, 4, 1, 60, 4, [2000, 100], 8, "appended", 4, 0),
+    ("f32", 64, 8, 2, 20, 2, [90, 10], 4, "appended", 0, 0),               # the fp32 path builds its own masks
+])
+def test_prepared_tree_changes_nothing_bitwise(dtype, D, Hq, Hkv, T, C, P, s, layout, wg, splits):
+    """Section 3.1 / Figure 4: the mask belongs to the step.  Handing a layer call the record tv_prepare_tree wrote
+    for the same trees must give the same bits as letting the call check the trees and walk the ancestors itself."""
+    inp = _case(4100 + T + len(P), dtype=dtype, Hq=Hq, Hkv=Hkv, D=D, P=P if len(P) > 1 else P[0], T=T, C=C, s=s,
+                layout=layout, B=len(P))
+    a = H.run_attention(inp, wg_row_blocks=wg, num_splits=splits)
+    b = H.run_attention(inp, wg_row_blocks=wg, num_splits=splits, prepare=True)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+    _check(inp, *b)
+
+
+@pytest.mark.parametrize("splits", [1, 2])
+def test_prepared_malformed_trees_are_flagged_and_zeroed(splits):
+    import paper_2603_08899_amd as tv
+    inp = _case(23, dtype="bf16", Hq=4, Hkv=2, D=128, P=[50, 60, 70, 80], T=10, C=2, B=4)
+    inp.parent[1, 5] = 7                 # forward reference
+    inp.kind[2, 4] = 3                   # unknown kind
+    out, lse, st = H.run_attention(inp, num_splits=splits, max_prefix_len=75, prepare=True)   # sequence 3 exceeds the bound
+    assert st[0] == 0
+    assert st[1] == tv.TV_STATUS_BAD_PARENT and st[2] == tv.TV_STATUS_BAD_KIND and st[3] == tv.TV_STATUS_BAD_PREFIX
+    for b in (1, 2, 3):
+        assert np.all(out[b] == 0) and np.all(lse[b] == 0)
+    _check(inp, out, lse, st, seqs=[0])
+
+
+@pytest.mark.parametrize("wg,splits", [(1, 0), (2, 3), (4, 1)])
+def test_bf16_relabelling_rows_permutes_the_output(wg, splits):
+    """Outputs follow the rows: renumbering the rows of a tree (parents still before children; siblings swapped,
+    whole subtrees moved) only permutes the rows of the result.  Each row's keys are then met in another order and
+    in other tiles, so the match is to rounding, not bitwise."""
+    rng = np.random.default_rng(77)
+    inp = _case(78, dtype="bf16", Hq=8, Hkv=2, D=128, P=333, T=48, C=0)
+    M, P = inp.M, int(inp.prefix_len[0])
+    parent = inp.parent[0]
+    # a random relabelling that keeps every parent in front of its children: visit the tree with children in random order
+    kids = [[] for _ in range(M)]
+    for i in range(1, M):
+        kids[parent[i]].append(i)
+    order, stack = [], [0]
+    while stack:
+        x = stack.pop(int(rng.integers(0, len(stack))))       # any visited-parent-first order
+        order.append(x)
+        stack.extend(kids[x])
+    perm = np.array(order)                                     # new row r holds old row perm[r]
+    assert not np.array_equal(perm, np.arange(M))
+    inv = np.argsort(perm)
+    parent2 = np.array([-1 if parent[o] < 0 else inv[parent[o]] for o in perm], dtype=np.int32)
+    assert all(parent2[i] < i for i in range(M))
+    import dataclasses
+    k2, v2 = inp.k_pool.copy(), inp.v_pool.copy()
+    k2[P:P + M], v2[P:P + M] = inp.k_pool[P:P + M][perm], inp.v_pool[P:P + M][perm]
+    inp2 = dataclasses.replace(inp, q=inp.q[:, perm].copy(), k_pool=k2, v_pool=v2, parent=parent2[None].copy(),
+                               kind=inp.kind[:, perm].copy())
+    out1, lse1, st1 = H.run_attention(inp, wg_row_blocks=wg, num_splits=splits)
+    out2, lse2, st2 = H.run_attention(inp2, wg_row_blocks=wg, num_splits=splits)
+    assert st1[0] == 0 and st2[0] == 0
+    _check(inp2, out2, lse2, st2)
+    scale = np.abs(out1).max()
+    assert np.abs(out2[0] - out1[0][perm]).max() <= 2 ** -7 * scale          # two bf16 roundings apart at most
+    assert np.abs(lse2[0] - lse1[0][:, perm]).max() <= 1e-4
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_bf16_random_configurations(seed):
     """Seeded random draws over everything the launch depends on at once: batch size, head grouping, tree size
@@ -345,7 +417,7 @@ def test_bf16_random_configurations(seed):
                 max_children=int(rng.integers(2, 9)))
     print(f"[random] seed {seed}: B={B} Hq={G * Hkv} Hkv={Hkv} M={inp.M} P={P} s={s_len} bound={bound} wg={wg} splits={splits}",
           flush=True)
-    out, lse, st = H.run_attention(inp, max_prefix_len=bound, wg_row_blocks=wg, num_splits=splits)
+    out, lse, st = H.run_attention(inp, max_prefix_len=bound, wg_row_blocks=wg, num_splits=splits, prepare=bool(seed % 2))
     _check(inp, out, lse, st)
 
 
@@ -378,16 +450,11 @@ def test_full_size_single_sequence_workloads(index, peaked):
         _check(inp, out, lse, st)
 
 
-def test_full_size_long_context_sampled_heads():
-    """Qwen3-4B-shaped, P=16384: every row of four query heads (one per distinct KV head)."""
+def test_full_size_long_context_all_heads():
+    """Qwen3-4B-shaped, P=16384: every row of every head, in the launch shape the library picks."""
     inp = si.attention_case(4, peaked=True)
-    out, _, st = H.run_attention(inp, want_lse=False)
-    assert st[0] == 0
-    rows = range(inp.M)
-    ref = H.oracle_attention_rows(inp, 0, rows, heads=[0, 9, 18, 31])
-    for (i, h), r in ref.items():
-        assert np.abs(out[0, i, h] - r).max() <= 2e-2
-        assert np.abs(out[0, i, h] - r).max() <= REL_TOL_BF16 * np.abs(r).max() + 1e-4
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st)
 
 
 @pytest.mark.parametrize("peaked", [False, True])
@@ -400,16 +467,11 @@ def test_full_size_contemplate_row_per_node(peaked):
     _check(inp, out, lse, st)
 
 
-def test_full_size_ragged_batch_sampled_heads():
-    """Eight sequences, prefix lengths 512..8192, one pool: two heads of every sequence."""
+def test_full_size_ragged_batch_all_heads():
+    """Eight sequences, prefix lengths 512..8192, one pool: every row of every head of every sequence."""
     inp = si.attention_case(3, peaked=True)
-    out, _, st = H.run_attention(inp, want_lse=False)
-    assert np.all(st == 0)
-    for b in range(inp.B):
-        ref = H.oracle_attention_rows(inp, b, range(inp.M), heads=[(5 * b) % 32, 31 - b])
-        for (i, h), r in ref.items():
-            assert np.abs(out[b, i, h] - r).max() <= 2e-2
-            assert np.abs(out[b, i, h] - r).max() <= REL_TOL_BF16 * np.abs(r).max() + 1e-4
+    out, lse, st = H.run_attention(inp)
+    _check(inp, out, lse, st)
 
 
 @pytest.mark.parametrize("seed", range(8))

@@ -101,7 +101,7 @@ def test_null_pointers_are_rejected_before_any_launch():
     # no device work is enqueued: the checks run on host scalars and pointer values only
     d = tv.make_attn_desc(dtype=tv.TV_DTYPE_F32, B=1, M=4, Hq=2, Hkv=1, D=64, soft_len=0,
                           max_prefix_len=8, softmax_scale=0.1)
-    rc = tv.lib().tree_verify_attention(ctypes.byref(d), *([None] * 11), 0, None)
+    rc = tv.lib().tree_verify_attention(ctypes.byref(d), *([None] * 12), 0, None)
     assert rc == tv.TV_ERR_INVALID_ARG
     a = tv.make_accept_desc(B=1, T=4, V=10, C=0, rule=tv.TV_RULE_GREEDY, temperature=0.0)
     rc = tv.lib().tree_accept(ctypes.byref(a), *([None] * 14), 0, None)
