@@ -158,6 +158,21 @@ int tree_verify_attention(
     size_t         workspace_bytes,
     void*          hip_stream);
 
+/* For callers that cannot allocate device memory or pass a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The same operation, arguments, results and error behaviour as
+ * tree_verify_attention, with the partial results of the key ranges kept in a fixed array of
+ * TV_NOALLOC_SCRATCH_BYTES inside the library's device image (each GPU the library runs on holds one copy until
+ * the process ends) instead of a workspace.  The call allocates and frees nothing.  A launch shape that needs
+ * more than the array (tv_attention_workspace_bytes(desc) > TV_NOALLOC_SCRATCH_BYTES: very long contexts, large
+ * batches) is refused with TV_ERR_WORKSPACE before anything is enqueued.  All calls on one GPU share that GPU's
+ * array: calls that may overlap on one GPU (different streams) race; calls on one stream are safe.  The first
+ * call on a device looks the array's address up (do it once outside any graph capture). */
+#define TV_NOALLOC_SCRATCH_BYTES (16u << 20)
+int tree_verify_attention_noalloc(
+    const tv_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_offset,
+    const int32_t* prefix_len, const int32_t* parent, const uint8_t* kind, const void* prepared_tree, void* out,
+    float* lse, int32_t* status, void* hip_stream);
+
 /* =================================================================================
  * tree_accept
  *

@@ -28,6 +28,7 @@ TV_FINAL_BONUS, TV_FINAL_RESIDUAL = 0, 1
 
 EXPORTED_SYMBOLS = (
     "tv_attention_workspace_bytes", "tv_attention_plan", "tv_prepare_tree", "tree_verify_attention",
+    "tree_verify_attention_noalloc",
     "tv_accept_workspace_bytes", "tree_accept",
     "tree_commit", "contemplate_embed", "tv_embed_workspace_bytes",
     "tv_build_mask_host", "tv_error_string", "tv_version", "tv_set_wait_limit",
@@ -113,6 +114,8 @@ def lib() -> ctypes.CDLL:
                                         ctypes.POINTER(ctypes.c_int32)]
         l.tree_verify_attention.restype = ctypes.c_int
         l.tree_verify_attention.argtypes = [ctypes.POINTER(tv_attn_desc)] + [vp] * 12 + [sz, vp]
+        l.tree_verify_attention_noalloc.restype = ctypes.c_int
+        l.tree_verify_attention_noalloc.argtypes = [ctypes.POINTER(tv_attn_desc)] + [vp] * 12
         l.tv_prepare_tree.restype = ctypes.c_int
         l.tv_prepare_tree.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp, vp, sz, vp]
         l.tv_accept_workspace_bytes.restype = ctypes.c_int
@@ -215,6 +218,19 @@ def tree_verify_attention(desc: tv_attn_desc, q, k_pool, v_pool, kv_offset, pref
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream_handle(stream))
     if rc:
         raise ConfuVerifyError(rc, "tree_verify_attention")
+
+
+TV_NOALLOC_SCRATCH_BYTES = 16 << 20
+
+
+def tree_verify_attention_noalloc(desc: tv_attn_desc, q, k_pool, v_pool, kv_offset, prefix_len, parent, kind,
+                                  out, lse, status, stream=None, prepared_tree=None) -> None:
+    """tree_verify_attention without a workspace: partial results live in a fixed array inside the library."""
+    rc = lib().tree_verify_attention_noalloc(
+        ctypes.byref(desc), _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(kv_offset), _ptr(prefix_len),
+        _ptr(parent), _ptr(kind), _ptr(prepared_tree), _ptr(out), _ptr(lse), _ptr(status), _stream_handle(stream))
+    if rc:
+        raise ConfuVerifyError(rc, "tree_verify_attention_noalloc")
 
 
 def tree_accept(desc: tv_accept_desc, target_logits, draft_logits, token, parent, uniforms, con_anchor,

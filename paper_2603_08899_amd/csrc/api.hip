@@ -265,10 +265,11 @@ int tv_prepare_tree(int32_t B, int32_t M, const int32_t* parent, const uint8_t* 
     return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;
 }
 
-int tree_verify_attention(const tv_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
-                          const int64_t* kv_offset, const int32_t* prefix_len, const int32_t* parent,
-                          const uint8_t* kind, const void* prepared_tree, void* out, float* lse, int32_t* status,
-                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+// Checks, plan and launch shared by the two attention entry points.
+static int enqueue_attention(const tv_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
+                             const int64_t* kv_offset, const int32_t* prefix_len, const int32_t* parent,
+                             const uint8_t* kind, const void* prepared_tree, void* out, float* lse, int32_t* status,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
     const int rc = check_attn_desc(desc);
     if (rc != TV_OK) return rc;
     if (!q || !k_pool || !v_pool || !kv_offset || !prefix_len || !parent || !kind || !out || !status)
@@ -298,6 +299,52 @@ int tree_verify_attention(const tv_attn_desc* desc, const void* q, const void* k
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const hipError_t e = (desc->dtype == TV_DTYPE_F32) ? launch_attention_f32(a, s) : launch_attention_bf16(a, s);
     return e == hipSuccess ? TV_OK : TV_ERR_LAUNCH;
+}
+
+int tree_verify_attention(const tv_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
+                          const int64_t* kv_offset, const int32_t* prefix_len, const int32_t* parent,
+                          const uint8_t* kind, const void* prepared_tree, void* out, float* lse, int32_t* status,
+                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return enqueue_attention(desc, q, k_pool, v_pool, kv_offset, prefix_len, parent, kind, prepared_tree, out, lse,
+                             status, workspace, workspace_bytes, hip_stream);
+}
+
+// ---- the same call for callers that cannot allocate ------------------------------------------------------------
+// The partial results of the key ranges go to a fixed array in the library's own device image instead of a
+// caller's workspace.  Every GPU holds its own copy at its own address, looked up once per device (with that
+// device current) and remembered; host code only ever uses the looked-up address.
+static __device__ __align__(256) unsigned char scratch[TV_NOALLOC_SCRATCH_BYTES];
+
+static constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_addr[kMaxDevices];
+
+static int scratch_for_current_device(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TV_ERR_LAUNCH;
+    void* p = g_scratch_addr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return TV_ERR_LAUNCH;
+        g_scratch_addr[dev].store(p, std::memory_order_release);     // (two threads racing here store the same address)
+    }
+    *out = p;
+    return TV_OK;
+}
+
+int tree_verify_attention_noalloc(const tv_attn_desc* desc, const void* q, const void* k_pool, const void* v_pool,
+                                  const int64_t* kv_offset, const int32_t* prefix_len, const int32_t* parent,
+                                  const uint8_t* kind, const void* prepared_tree, void* out, float* lse,
+                                  int32_t* status, void* hip_stream) {
+    const int rc = check_attn_desc(desc);
+    if (rc != TV_OK) return rc;
+    AttnPlan p;
+    const int prc = plan_attention(*desc, &p);
+    if (prc != TV_OK) return prc;
+    if (p.total_bytes > (size_t)TV_NOALLOC_SCRATCH_BYTES) return TV_ERR_WORKSPACE;     // larger than the fixed array
+    void* ws = nullptr;
+    const int src = scratch_for_current_device(&ws);
+    if (src != TV_OK) return src;
+    return enqueue_attention(desc, q, k_pool, v_pool, kv_offset, prefix_len, parent, kind, prepared_tree, out, lse,
+                             status, ws, (size_t)TV_NOALLOC_SCRATCH_BYTES, hip_stream);
 }
 
 static int check_accept_desc(const tv_accept_desc* d) {

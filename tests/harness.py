@@ -22,7 +22,7 @@ def to_device_storage(arr: np.ndarray, dtype: str):
 
 def run_attention(inp: AttnInputs, *, want_lse: bool = True, num_splits: int = 0, max_prefix_len=None,
                   device_inputs=None, wg_row_blocks: int = 0, sum_prefix_len: int = 0,
-                  kv_token_stride: int = 0, kv_head_stride: int = 0, prepare: bool = False):
+                  kv_token_stride: int = 0, kv_head_stride: int = 0, prepare: bool = False, noalloc: bool = False):
     """Returns (out float64 [B,M,Hq,D], lse float64 [B,Hq,M] or None, status int32 [B]).
     prepare=True: the trees go through tv_prepare_tree first and the call is handed the prepared record."""
     import paper_2603_08899_amd as tv
@@ -53,7 +53,10 @@ def run_attention(inp: AttnInputs, *, want_lse: bool = True, num_splits: int = 0
     if prepare:
         prepared = torch.full((inp.B * tv.TV_PREPARED_TREE_BYTES,), 0xA5, device="cuda", dtype=torch.uint8)
         tv.tv_prepare_tree(parent, kind, prepared)
-    tv.tree_verify_attention(desc, q, k, v, kv_off, plen, parent, kind, out, lse, status, ws, prepared_tree=prepared)
+    if noalloc:      # the entry point that keeps its partial results in the library's own fixed array
+        tv.tree_verify_attention_noalloc(desc, q, k, v, kv_off, plen, parent, kind, out, lse, status, prepared_tree=prepared)
+    else:
+        tv.tree_verify_attention(desc, q, k, v, kv_off, plen, parent, kind, out, lse, status, ws, prepared_tree=prepared)
     torch.cuda.synchronize()
     o = out.float().cpu().numpy().astype(np.float64)
     l = None if lse is None else lse.cpu().numpy().astype(np.float64)
