@@ -25,8 +25,10 @@
  *     of range, a prefix length out of range) are reported per sequence in the
  *     device array `status`, and that sequence's outputs are then zeros
  *     (attention) or -1 (acceptance).
- *   - No global mutable state apart from a cached device-property query; calls are
- *     thread-safe for distinct streams and workspaces.
+ *   - Global state: cached device properties and launch attributes, the address of the
+ *     fixed scratch array of tree_verify_attention_noalloc, and the test hook
+ *     tv_set_wait_limit (an atomic integer read by tree_accept).  Calls are thread-safe
+ *     for distinct streams and workspaces.
  */
 #ifndef CONFU_VERIFY_H
 #define CONFU_VERIFY_H
@@ -51,7 +53,7 @@ extern "C" {
 #define TV_STATUS_BAD_KIND      2   /* kind not 0/1, or a draft node hangs off a contemplate row */
 #define TV_STATUS_BAD_PREFIX    4   /* prefix_len < soft_len, < 0 or > max_prefix_len */
 #define TV_STATUS_BAD_TOKEN     8   /* token id outside [0, V) */
-#define TV_STATUS_INTERNAL     16   /* a bounded wait between workgroups ran out (tree_accept, draft rules) */
+#define TV_STATUS_INTERNAL     16   /* reserved (earlier versions: a bounded wait between workgroups ran out); no longer raised */
 #define TV_STATUS_BAD_PATH     32   /* tree_commit: path not a strictly increasing list of nodes starting at the root */
 
 /* ---- limits -------------------------------------------------------------------- */
@@ -191,6 +193,11 @@ int tree_verify_attention_noalloc(
  *     an accepted child becomes the current node;
  *   when no child is accepted: final_token = first v whose running sum of p exceeds
  *   u[T + node] (GREEDY: the argmax), final_kind says whether p had been corrected.
+ *
+ * Logits may be -infinity (banned tokens, a padded tail): such entries have probability 0.  A row
+ * that is -infinity throughout has no law: every child of that node is rejected, and if the walk
+ * stops there final_token is -1 (GREEDY: 0, the lowest index of the tie).  NaN and +infinity are
+ * not allowed (undefined results).
  * ================================================================================= */
 typedef struct tv_accept_desc {
     uint32_t struct_size;        /* sizeof(tv_accept_desc), checked */
@@ -341,11 +348,11 @@ const char* tv_error_string(int code);
 /* host: library version, major*100 + minor. */
 int tv_version(void);
 
-/* host, for tests of the failure path: sets how many times a workgroup of tree_accept's sibling-chain
- * kernel (draft rules) polls for the other workgroups of its group before it gives up; a sequence whose
- * wait ran out gets TV_STATUS_INTERNAL and -1 outputs, and every kernel still ends normally.
- * 0 restores the default (about a million polls).  Applies to calls made after it; returns the
- * previous setting. */
+/* host, for tests: sets how many times a workgroup of tree_accept's sibling-chain kernel (draft rules) looks
+ * for a result of another workgroup of its group before it stops waiting and computes that result itself (the
+ * same bits, more work).  Results never depend on it; workgroups never wait without bound, whether or not the
+ * others are running.  0 restores the default (about a million looks).  Applies to calls made after it;
+ * returns the previous setting. */
 int tv_set_wait_limit(int polls);
 
 #ifdef __cplusplus

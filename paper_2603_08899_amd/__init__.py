@@ -182,7 +182,8 @@ def tv_accept_workspace_bytes(desc: tv_accept_desc) -> int:
 
 
 def tv_set_wait_limit(polls: int) -> int:
-    """Test hook: polls before a sibling-chain workgroup gives up (0 = default); returns the old value."""
+    """Test hook: looks at another workgroup's slot before a sibling-chain workgroup computes that share itself
+    (0 = default); returns the old value."""
     return int(lib().tv_set_wait_limit(int(polls)))
 
 

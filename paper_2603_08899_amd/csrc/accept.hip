@@ -9,17 +9,26 @@
 // Decomposition (all bandwidth-bound, plain ALUs, 64-wide wave reductions):
 //   1. accept_stats_kernel   every logits row is cut into ranges; one workgroup reduces one range
 //                            to (max, argmax, sum exp) with fp32 loads and fp64 accumulation.
+//                            The same workgroups pick every child's token logit out of its parent's row
+//                            while that row is passing through them.
 //   2. accept_chain_kernel   draft rules only.  A node's accept test depends only on its parent's two
 //                            rows and on its rank among its siblings (as if all earlier siblings were
-//                            rejected), so every parent is processed independently: one workgroup per
-//                            parent walks its children in order and needs one vocabulary-wide
-//                            reduction (the corrected law's normaliser) per child.
-//   3. accept_walk_kernel    a group of workgroups per sequence.  Each one repeats the (cheap, LDS-only)
-//                            walk from the root, then sums the final law over its own slice of the
-//                            vocabulary and publishes that mass; every workgroup reads all the masses,
-//                            and the one whose slice holds the crossing of the uniform finishes the
-//                            inverse-CDF search inside its slice and writes the results.
+//                            rejected), so every parent is processed independently: a group of workgroups
+//                            per parent walks its children in order and needs one vocabulary-wide
+//                            reduction (the corrected law's normaliser) per child; the per-slice shares of
+//                            every child's reduction stay in the workspace.
+//   3. accept_walk_kernel    one workgroup per sequence, no waiting on anybody: the (cheap, LDS-only) walk
+//                            from the root, then the final inverse-CDF draw.  The mass of the final law in
+//                            every piece of the vocabulary is already known - from the ranges of step 1
+//                            (minus the rejected tokens) or from the shares of step 2 - so only the piece that
+//                            holds the crossing of the uniform is read again.
+#include <atomic>
+
 #include "tv_internal.hpp"
+
+// No fused multiply-adds formed across expressions in this file: a share of a reduction rebuilt by another workgroup
+// (accept_chain_kernel) must come out with the owner's bits whatever shape the surrounding code has.
+#pragma clang fp contract(off)
 
 namespace tv {
 
@@ -28,16 +37,20 @@ namespace {
 constexpr int kStatThreads = 256;
 constexpr int kChainThreads = 256;
 constexpr int kChainWaves = kChainThreads / kWave;
-constexpr int kDrawThreads = 256;
+constexpr int kDrawThreads = 1024;
 constexpr int kDrawWaves = kDrawThreads / kWave;
 constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// exp((z - m) / temperature) as the kernels evaluate it everywhere: fp32 exponent, fp64 afterwards.
+// exp((z - m) / temperature) as the kernels evaluate it everywhere: fp32 exponent, fp64 afterwards.  A logit of
+// -infinity (a banned token, a padded tail) has no mass; so has every entry while the reference m itself is still
+// -infinity (nothing finite seen yet).
 __device__ __forceinline__ double unnorm_prob(float z, float m, float it_log2e) {
-    return (double)fast_exp2((z - m) * it_log2e);
+    return (m == -INFINITY) ? 0.0 : (double)fast_exp2((z - m) * it_log2e);
 }
+// 1 / s for a row (or law) sum; a row without any mass gives every entry probability 0
+__device__ __forceinline__ double inv_mass(double s) { return (s > 0.0) ? 1.0 / s : 0.0; }
 
 struct Red {          // (max, lowest argmax, sum exp relative to max)
     float m;
@@ -146,20 +159,26 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a
     const int mat = blockIdx.y / a.T;
     const int row = blockIdx.y % a.T;
     const int b = blockIdx.z;
-    // the kernels that follow on the stream count arriving workgroups from zero
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        if (a.n_mat == 2 && blockIdx.y == 0 && b == 0) *a.chain_fail = 0;
-    }
-    if (blockIdx.x == 0 && blockIdx.y == 0)                  // the draw kernel's slice slots: "not published yet"
-        for (int i = threadIdx.x; i < kMaxSlices; i += kStatThreads) a.slice_bits[(int64_t)b * kMaxSlices + i] = 3ull;
-    if (a.n_mat == 2 && mat == 0 && blockIdx.x == 0) {       // this node's share slots: a tag no early round expects
-        unsigned long long* parts = a.chain_parts + ((int64_t)b * a.T + row) * 2 * a.chain_slices;
-        for (int i = threadIdx.x; i < 2 * a.chain_slices; i += kStatThreads) parts[i] = 3ull;
+    // this node's share slots of the sibling-chain kernel: "not published yet"
+    if (a.n_mat == 2 && mat == 0 && blockIdx.x == 0) {
+        unsigned long long* parts = a.chain_parts + ((int64_t)b * a.T + row) * a.chain_slices;
+        for (int i = threadIdx.x; i < a.chain_slices; i += kStatThreads) parts[i] = 3ull;
     }
     const Row lrow = logits_row(a, mat == 0 ? a.target : a.draft, b, row);
     const int begin = split * a.split_len;
     const int end = min(a.V, begin + a.split_len);
     const float it = kGreedy ? 0.f : kLog2e / a.temperature;
+
+    // The logit of every child's token in this (its parent's) row, picked out by the workgroup whose range holds it:
+    // the walk then finds all of them in one small array instead of gathering them from the rows.  Thread c looks
+    // at node c, before the streaming starts, so that these few dependent loads run under it; a token outside the
+    // row is left alone (the walk flags the sequence).
+    if (!kGreedy && threadIdx.x >= 1 && (int)threadIdx.x < a.T) {
+        const int c = threadIdx.x;
+        const int tok = a.token[(int64_t)b * a.T + c];
+        if (a.parent[(int64_t)b * a.T + c] == row && tok >= begin && tok < end)
+            a.z_tok[((int64_t)b * a.n_mat + mat) * a.T + c] = lrow[tok];
+    }
 
     Red r{-INFINITY, 0x7fffffff, 0.0};
     int v = begin;
@@ -239,7 +258,7 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a
         for (int w = 1; w < kStatThreads / kWave; ++w) t = red_merge(t, wred[w], it);
         RowStat* out = a.stats + ((((int64_t)b * a.n_mat + mat) * a.T + row) * a.splits + split);
         out->max_logit = t.m;
-        out->argmax = t.am;
+        out->argmax = (t.am == 0x7fffffff) ? begin : t.am;      // nothing above -infinity: the range's first entry
         out->sum_exp = t.s;
     }
 }
@@ -346,22 +365,30 @@ __device__ __forceinline__ double block_sum(double x, double* scratch /* kWaves 
 }
 
 // ---- 2. sibling chains (draft rules) --------------------------------------------------------------------
-// The launch holds a whole number of groups of chain_slices workgroups, no more than fit on the device at
-// once.  A group takes the nodes that have children one after the other; each workgroup holds its slice of
-// the node's two laws in registers and the group steps through the children in order.  One child costs one
-// group-wide reduction (the normaliser of the corrected law): every workgroup publishes its partial sum and
-// waits until it has seen the partial sums of the whole group.
+// The launch holds a whole number of groups of chain_slices workgroups.  A group takes the nodes that have
+// children one after the other; each workgroup holds its slice of the node's two laws in registers and the
+// group steps through the children in order.  One child costs one group-wide reduction (the normaliser of the
+// corrected law): every workgroup publishes its slice's share - which stays in the workspace for the final draw -
+// and collects the shares of the whole group.
 //
-// Forward progress: a workgroup waits only for workgroups of its own launch, and the host sizes the grid so
-// that all of them are resident together.  The wait is bounded all the same: past wait_limit polls the
-// workgroup gives up, raises chain_fail (the walk kernel turns it into TV_STATUS_INTERNAL) and exits.
+// Forward progress does not hang on the other workgroups being resident: a workgroup polls a bounded number of
+// times (wait_limit); when that runs out it computes the missing shares itself, from the rows in memory, with
+// the same instruction sequence and summation order the owning workgroup uses - the same bits - and goes on.
 constexpr int kChainPer = 16;                                  // vocabulary entries per lane
 constexpr int kChainQuads = kChainPer / 4;
+constexpr int kChainSlice = kChainThreads * kChainPer;         // vocabulary entries per workgroup
 
 // What workgroups hand to each other inside a kernel goes through agent-scope atomic stores and loads, which
 // pass by the caches that are not coherent across the device (a device-wide release fence would write back
-// the whole L2); every published value carries its own "ready" tag, so no second store has to be ordered
-// behind it.
+// the whole L2); every published value carries its own "ready" tag in its two lowest mantissa bits (0 = ready,
+// 3 = not yet, left there by the statistics kernel), so no second store has to be ordered behind it.  Readers
+// use the value with those two bits cleared, everywhere.
+__device__ __forceinline__ unsigned long long share_bits(double x) {
+    return (unsigned long long)__double_as_longlong(x) & ~3ull;
+}
+__device__ __forceinline__ double share_value(unsigned long long bits) {
+    return __longlong_as_double((long long)(bits & ~3ull));
+}
 
 // Four consecutive logits of a row (entries past the end of the row read as -infinity, which the
 // laws map to zero mass).
@@ -380,6 +407,93 @@ __device__ __forceinline__ void load_quad(const Row& row, bool vec_ok, int v, in
     }
 }
 
+// This lane's kChainPer entries of the two laws at a node, for vocabulary slice `slice`: quad qd covers
+// v = slice * kChainSlice + (qd * threads + tid) * 4 ...
+__device__ __forceinline__ void chain_load_slice(const Row& prow, const Row& qrow, bool vec_ok, int slice, int V,
+                                                 const Red& sp, const Red& sq, float it, double (&p)[kChainPer],
+                                                 double (&q)[kChainPer]) {
+    const double inv_sp = inv_mass(sp.s), inv_sq = inv_mass(sq.s);
+    const int slice_base = slice * kChainSlice;
+#pragma unroll
+    for (int qd = 0; qd < kChainQuads; ++qd) {
+        const int v = slice_base + (qd * kChainThreads + (int)threadIdx.x) * 4;
+        float zp[4], zq[4];
+        if (v < V) {
+            load_quad(prow, vec_ok, v, V, zp);
+            load_quad(qrow, vec_ok, v, V, zq);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { zp[e] = -INFINITY; zq[e] = -INFINITY; }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            p[4 * qd + e] = unnorm_prob(zp[e], sp.m, it) * inv_sp;
+            q[4 * qd + e] = unnorm_prob(zq[e], sq.m, it) * inv_sq;
+        }
+    }
+}
+template <int kRule>
+__device__ __forceinline__ void chain_step_slice(int slice, const ChainStep& st, double (&p)[kChainPer], double (&q)[kChainPer]) {
+    const int slice_base = slice * kChainSlice;
+#pragma unroll
+    for (int qd = 0; qd < kChainQuads; ++qd) {
+        const int v = slice_base + (qd * kChainThreads + (int)threadIdx.x) * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) law_step<kRule>(v + e, st, p[4 * qd + e], q[4 * qd + e]);
+    }
+}
+// the slice's share of the normaliser of max(p - q, 0): lanes in entry order, then the workgroup's fixed tree
+__device__ __forceinline__ double chain_share(const double (&p)[kChainPer], const double (&q)[kChainPer], double* red) {
+    double part = 0.0;
+#pragma unroll
+    for (int e = 0; e < kChainPer; ++e) part += fmax(p[e] - q[e], 0.0);
+    return block_sum<kChainWaves>(part, red);
+}
+
+// Every share of the j-th reduction at a node that is still missing in `shares` (tag bits set), rebuilt entry by
+// entry as its owner forms it - the slice's laws from the rows, the j steps so far, the same sums in the same order,
+// hence the same bits - one quad of entries at a time, so that this rarely taken path needs few registers next to
+// the caller's own slice.  Called by all threads of the workgroup.
+template <int kRule>
+__device__ __forceinline__ void rebuild_missing_shares(const Row& prow, const Row& qrow, bool vec_ok, int V, int S,
+                                                       const Red& sp, const Red& sq, float it, const ChainStep* steps,
+                                                       int j, unsigned long long* shares, double* red) {
+    const double inv_sp = inv_mass(sp.s), inv_sq = inv_mass(sq.s);
+    for (int s = 0; s < S; ++s) {
+        if ((shares[s] & 3ull) == 0ull) continue;             // (uniform: read after a barrier)
+        double part = 0.0;
+#pragma unroll 1
+        for (int qd = 0; qd < kChainQuads; ++qd) {
+            const int v = s * kChainSlice + (qd * kChainThreads + (int)threadIdx.x) * 4;
+            float zp[4], zq[4];
+            if (v < V) {
+                load_quad(prow, vec_ok, v, V, zp);
+                load_quad(qrow, vec_ok, v, V, zq);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { zp[e] = -INFINITY; zq[e] = -INFINITY; }
+            }
+            double p[4], q[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                p[e] = unnorm_prob(zp[e], sp.m, it) * inv_sp;
+                q[e] = unnorm_prob(zq[e], sq.m, it) * inv_sq;
+            }
+            for (int i = 0; i < j; ++i) {
+                const ChainStep st = steps[i];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) law_step<kRule>(v + e, st, p[e], q[e]);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) part += fmax(p[e] - q[e], 0.0);
+        }
+        const double theirs = block_sum<kChainWaves>(part, red);
+        __syncthreads();
+        if (threadIdx.x == 0) shares[s] = share_bits(theirs);
+    }
+    __syncthreads();
+}
+
 template <int kRule>
 __global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs a) {
     const int T = a.T, V = a.V, S = a.chain_slices;
@@ -392,7 +506,9 @@ __global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs 
     __shared__ Red s_stat[2];
     __shared__ int s_internal[kMaxRows];
     __shared__ int s_has[kMaxRows];
-    __shared__ int s_flag, s_k, s_fail, s_nint;
+    __shared__ int s_flag, s_k, s_missing, s_nint;
+    __shared__ float s_zp[kMaxRows], s_zq[kMaxRows], s_u[kMaxRows];      // per child: its token's logits, its uniform
+    extern __shared__ unsigned long long s_share[];                        // [S]: the shares of one reduction
     const int n_groups = gridDim.x / S;
     const int group = blockIdx.x / S, slice = blockIdx.x % S;
     if (group >= n_groups) return;
@@ -436,10 +552,7 @@ __global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs 
                         while (hi) { s_internal[n++] = kWave + __ffsll((long long)hi) - 1; hi &= hi - 1; }
                     }
                 }
-                if (lane == 0) {
-                    s_nint = bad ? 0 : n;       // malformed input: nothing to do (the walk kernel reports it)
-                    s_fail = 0;
-                }
+                if (lane == 0) s_nint = bad ? 0 : n;       // malformed input: nothing to do (the walk kernel reports it)
             }
             __syncthreads();
         }
@@ -470,40 +583,20 @@ __global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs 
             const Red r = group_row_stat(a, b, wave, u, true, lane, kWave, it, true);
             if (lane == 0) s_stat[wave] = r;
         }
-        __syncthreads();
-        const Red sp = s_stat[0], sq = s_stat[1];
-        const double inv_sp = 1.0 / sp.s, inv_sq = 1.0 / sq.s;
-        const Row prow = logits_row(a, a.target, b, u), qrow = logits_row(a, a.draft, b, u);
-        const bool vec_ok = prow.quad_aligned() && qrow.quad_aligned();
-        __shared__ float s_zp[kMaxRows], s_zq[kMaxRows], s_u[kMaxRows];      // per child: its token's logits, its uniform
-        if (tid < k) {
+        if (tid < k) {          // what the statistics kernel picked out of the two rows for this child
             const int c = s_child[tid];
-            s_zp[tid] = prow[s_token[c]];
-            s_zq[tid] = qrow[s_token[c]];
+            s_zp[tid] = a.z_tok[((int64_t)b * 2 + 0) * T + c];
+            s_zq[tid] = a.z_tok[((int64_t)b * 2 + 1) * T + c];
             s_u[tid] = a.uniforms[(int64_t)b * 2 * T + c];
         }
         __syncthreads();
+        const Red sp = s_stat[0], sq = s_stat[1];
+        const double inv_sp = inv_mass(sp.s), inv_sq = inv_mass(sq.s);
+        const Row prow = logits_row(a, a.target, b, u), qrow = logits_row(a, a.draft, b, u);
+        const bool vec_ok = prow.quad_aligned() && qrow.quad_aligned();
 
-        // this lane's entries of the two laws: quad qd covers v = slice_base + (qd * threads + tid) * 4 ...
-        const int slice_base = slice * (kChainThreads * kChainPer);
         double p[kChainPer], q[kChainPer];
-#pragma unroll
-        for (int qd = 0; qd < kChainQuads; ++qd) {
-            const int v = slice_base + (qd * kChainThreads + tid) * 4;
-            float zp[4], zq[4];
-            if (v < V) {
-                load_quad(prow, vec_ok, v, V, zp);
-                load_quad(qrow, vec_ok, v, V, zq);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) { zp[e] = -INFINITY; zq[e] = -INFINITY; }
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                p[4 * qd + e] = unnorm_prob(zp[e], sp.m, it) * inv_sp;
-                q[4 * qd + e] = unnorm_prob(zq[e], sq.m, it) * inv_sq;
-            }
-        }
+        chain_load_slice(prow, qrow, vec_ok, slice, V, sp, sq, it, p, q);
 
         for (int j = 0; j < k; ++j) {
             const int c = s_child[j];
@@ -521,190 +614,59 @@ __global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs 
                 const double qs = 1.0 - qx;      // mass of q left once x is removed
                 st.inv_qs = (kRule == TV_RULE_DRAFT_WOR && qs > 0.0) ? 1.0 / qs : 0.0;
                 s_steps[j] = st;
+                s_missing = 0;
             }
-            // normaliser of the corrected law after rejecting child j: this slice's share ...
-            double part = 0.0;
-#pragma unroll
-            for (int e = 0; e < kChainPer; ++e) part += fmax(p[e] - q[e], 0.0);
-            const double mine = block_sum<kChainWaves>(part, s_red);
-            // ... published with the round number (mod 4) in the two lowest mantissa bits, which tells a reader that
-            // the slot holds this round's share: no counter, no second round trip.  Two buffers, by parity of j;
-            // the statistics kernel left tag 3 in both, which neither of the first two rounds expects.
-            unsigned long long* parts = a.chain_parts + ((((int64_t)b * T + u) * 2) + (j & 1)) * S;
-            const unsigned long long tag = (unsigned long long)(j & 3);
+            // normaliser of the corrected law after rejecting child j: this slice's share, published in child c's
+            // slot of this slice (where it also stays for the final draw) ...
+            const double mine = chain_share(p, q, s_red);
+            unsigned long long* parts = a.chain_parts + ((int64_t)b * T + c) * S;
             if (tid == 0)
-                __hip_atomic_store(parts + slice, ((unsigned long long)__double_as_longlong(mine) & ~3ull) | tag,
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            // ... and the whole: every workgroup of the group adds the shares in the same order
+                __hip_atomic_store(parts + slice, share_bits(mine), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // ... and the others': a bounded number of looks at every slot
             if (wave == 0) {
-                double z = 0.0;
-                int fail = 0;
+                int missing = 0;
                 unsigned polls = 0;
                 for (int s = lane; s < S; s += kWave) {
-                    unsigned long long bits = 0;
-                    for (;;) {
-                        bits = __hip_atomic_load(parts + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        if ((bits & 3ull) == tag) break;
-                        __builtin_amdgcn_s_sleep(1);
-                        if (++polls > a.wait_limit) { fail = 1; break; }
+                    unsigned long long bits = share_bits(mine);
+                    if (s != slice) {
+                        for (;;) {
+                            bits = __hip_atomic_load(parts + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            if ((bits & 3ull) == 0ull) break;
+                            if (++polls > a.wait_limit) { bits = 3ull; break; }
+                            __builtin_amdgcn_s_sleep(1);
+                        }
                     }
-                    z += __longlong_as_double((long long)(bits & ~3ull));
+                    s_share[s] = bits;
+                    if ((bits & 3ull) != 0ull) missing = 1;
                 }
-                fail = __any(fail);
+                if (__any(missing) && lane == 0) s_missing = 1;
+            }
+            __syncthreads();
+            if (s_missing) {
+                // Some workgroup of the group has not been heard from (it may not even be running yet): its share
+                // is rebuilt here (a call, so that this rarely taken path costs the loop above no registers).
+                rebuild_missing_shares<kRule>(prow, qrow, vec_ok, V, S, sp, sq, it, s_steps, j, s_share, s_red);
+            }
+            // the whole: every workgroup of the group adds the shares in the same order
+            if (wave == 0) {
+                double z = 0.0;
+                for (int s = lane; s < S; s += kWave) z += share_value(s_share[s]);
                 z = wave_sum(z);
                 if (lane == 0) {
-                    s_fail = fail;
                     s_steps[j].inv_z = (z > 0.0) ? 1.0 / z : 0.0;
                     if (slice == 0) a.chain_z[(int64_t)b * T + c] = z;
                 }
             }
             __syncthreads();
-            if (s_fail) {
-                if (tid == 0) *a.chain_fail = 1;
-                return;
-            }
-            if (j + 1 < k) {
-                const ChainStep st = s_steps[j];
-#pragma unroll
-                for (int qd = 0; qd < kChainQuads; ++qd) {
-                    const int v = slice_base + (qd * kChainThreads + tid) * 4;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) law_step<kRule>(v + e, st, p[4 * qd + e], q[4 * qd + e]);
-                }
-            }
+            if (j + 1 < k) chain_step_slice<kRule>(slice, s_steps[j], p, q);
         }
     }   // next node of this group
 }
 
-// ---- 2b. inverse CDF at one node from the row's reduced ranges ------------------------------------------------
-constexpr int kDrawQuads = 8;     // quads of entries a lane of range_draw requests at once: 8192 entries per workgroup
-struct DrawScratch {              // shared memory of range_draw
-    double wave_tot[kDrawWaves];
-    double base, inv_total;
-    float row_max;
-    int split, hit, last, tok;
-};
+// ---- 2b. the inverse-CDF draw from a law whose mass per piece of the vocabulary is known -------------------------
+constexpr int kDrawQuads = 8;     // quads of entries a lane requests at once: 8192 entries per workgroup and batch
+constexpr int kMaxPieces = 256;   // pieces a draw can choose among (four per lane of one wave)
 
-// The first v whose running sum of softmax(target row / temperature) at `node` exceeds u.  The sums of the row's
-// ranges, left by the statistics kernel, locate the range that holds the crossing, and only that range is read
-// again - by one workgroup, without any hand-off between workgroups.  Every thread of the workgroup calls this
-// and gets the token (-1: the law has no mass at all).
-__device__ __forceinline__ int range_draw(const AcceptArgs& a, DrawScratch& ds, int b, int node, double u, float it) {
-    const int T = a.T, V = a.V;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const RowStat* st = a.stats + (((int64_t)b * a.n_mat) * T + node) * a.splits;
-    if (wave == 0) {
-        // mass of every range relative to the row's maximum (there are at most 64 ranges: one per lane)
-        const bool live = lane < a.splits;
-        const float ms = live ? st[lane].max_logit : -INFINITY;
-        const float m = wave_max(ms);
-        double mass = live ? ((ms == m) ? st[lane].sum_exp : st[lane].sum_exp * unnorm_prob(ms, m, it)) : 0.0;
-        const double inv_total = 1.0 / wave_sum(mass);
-        mass *= inv_total;
-        // prefix sum in range order, first range whose running sum exceeds u
-        double inc = mass;
-#pragma unroll
-        for (int o = 1; o < kWave; o <<= 1) {
-            const double t = __shfl_up(inc, o, kWave);
-            if (lane >= o) inc += t;
-        }
-        const unsigned long long cross = __ballot(live && inc > u);
-        const unsigned long long has = __ballot(live && mass > 0.0);
-        // (if rounding leaves the total at or below u: the last range that carries mass)
-        const int split = cross ? __ffsll((long long)cross) - 1 : (has ? 63 - __builtin_clzll(has) : 0);
-        const double before = __shfl(inc - mass, split, kWave);
-        if (lane == 0) {
-            ds.split = split;
-            ds.base = before;
-            ds.inv_total = inv_total;
-            ds.row_max = m;
-            ds.hit = kDrawThreads;
-            ds.last = -1;
-            ds.tok = -1;
-        }
-    }
-    __syncthreads();
-
-    // the chosen range, a contiguous run of quads per lane in vocabulary order.  A lane requests kDrawQuads quads
-    // before it uses the first; ranges are planned so that this is the whole run (plan_accept), longer ones
-    // (vocabularies beyond 64 x 8192 entries) take several such batches.
-    const Row row = logits_row(a, a.target, b, node);
-    const bool vec_ok = row.quad_aligned();
-    const int begin = ds.split * a.split_len, end = min(V, begin + a.split_len);
-    const int quads = (end - begin + 4 * kDrawThreads - 1) / (4 * kDrawThreads);
-    const int v0 = begin + tid * 4 * quads;
-    const float m = ds.row_max;
-    const double inv_total = ds.inv_total;
-    // find = false: mass of the lane's run and its last entry with mass; true: first entry at which `run` exceeds u
-    auto scan = [&](bool find, double run, int* last_out) {
-        int lst = -1, fnd = -1;
-        for (int g0 = 0; g0 < quads; g0 += kDrawQuads) {
-            float z[kDrawQuads][4];
-#pragma unroll
-            for (int g = 0; g < kDrawQuads; ++g) {
-                const int v = v0 + 4 * (g0 + g);
-                if (g0 + g < quads && v < end) {
-                    load_quad(row, vec_ok, v, end, z[g]);       // entries past the range read as -infinity: no mass
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) z[g][e] = -INFINITY;
-                }
-            }
-#pragma unroll
-            for (int g = 0; g < kDrawQuads; ++g) {
-                const int v = v0 + 4 * (g0 + g);
-                double pv[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) pv[e] = unnorm_prob(z[g][e], m, it) * inv_total;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    run += pv[e];
-                    if (pv[e] > 0.0) lst = v + e;
-                    if (find && fnd < 0 && run > u) fnd = v + e;
-                }
-            }
-        }
-        *last_out = find ? ((fnd >= 0) ? fnd : lst) : lst;
-        return run;
-    };
-    int last;
-    const double mine = scan(false, 0.0, &last);
-    if (last >= 0) atomicMax(&ds.last, last);
-    double inc = mine;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        const double t = __shfl_up(inc, o, kWave);
-        if (lane >= o) inc += t;
-    }
-    if (lane == kWave - 1) ds.wave_tot[wave] = inc;
-    __syncthreads();
-    double before = ds.base;
-    for (int w = 0; w < wave; ++w) before += ds.wave_tot[w];
-    if (before + inc > u) atomicMin(&ds.hit, tid);
-    __syncthreads();
-    if (tid == ds.hit) {
-        int tok;
-        scan(true, before + (inc - mine), &tok);
-        ds.tok = tok;
-    }
-    __syncthreads();
-    // (no lane's running sum exceeds u: the range sums put the crossing here, the in-order sums round just below
-    //  it, or the total itself rounds to u or less - the last entry that carries mass)
-    return (ds.hit == kDrawThreads) ? ds.last : ds.tok;
-}
-
-// The target's own token at every node (sample-and-match rule).  Grid (T, B): one workgroup draws, for one node,
-// the token that plain sampling of the target would emit there: inverse CDF of softmax(target row /
-// temperature) at the node's uniform u[T + node].
-__global__ __launch_bounds__(kDrawThreads) void accept_sample_kernel(AcceptArgs a) {
-    const int i = blockIdx.x, b = blockIdx.y;
-    __shared__ DrawScratch ds;
-    const double u = (double)a.uniforms[(int64_t)b * 2 * a.T + a.T + i];
-    const int tok = range_draw(a, ds, b, i, u, kLog2e / a.temperature);
-    if (threadIdx.x == 0) a.sampled[(int64_t)b * a.T + i] = tok;
-}
-
-// ---- 3. walk + final draw ---------------------------------------------------------------------------------
 struct WalkShared {
     int parent[kMaxRows];
     int token[kMaxRows];
@@ -719,60 +681,243 @@ struct WalkShared {
     float z_tok_q[kMaxRows];      // draft logit of the same entry
     int abit[kMaxRows];           // draft rules: the chain kernel's accept bit of node c
     double chain_z[kMaxRows];     // draft rules: normaliser of the corrected law after rejecting node c
-    ChainStep steps[kMaxRows];
+    ChainStep steps[kMaxRows];    // the rejections at the stop node, in order
+    int rej_child[kMaxRows];      // ... the child each of them turned down
+    double rej_p0[kMaxRows];      // ... and the target's own probability of its token
     int con_anchor[kMaxRows];     // node of each contemplate row (the first kMaxRows of them)
     double red[kDrawWaves];
     double wave_tot[kDrawWaves];
-    double base;                  // mass of the final law in the slices before the chosen one
+    int wave_last[kDrawWaves];
+    double base;                  // mass of the final law in the pieces before the chosen one
     int flag, cur, n_steps, rejected_any, len, tok_out;
-    int slice_last, s_star, hit, fallback;
+    int piece;
 };
 
-// One lane's contiguous run of vocabulary entries [v0, v0 + 4*quads).  kFind = false: the mass of the
-// final law over the run and the last entry that carries mass.  kFind = true: the running sum starts at
-// *mass and the first entry at which it exceeds u is returned in *found (-1 if none).
+// One lane's contiguous run of vocabulary entries [v0, v0 + 4*quads) of the law at `node` after sh.n_steps
+// rejections, entries at or past `end` carrying no mass.  kFind = false: returns the mass of the run and, in *out,
+// its last entry that carries mass.  kFind = true: the running sum starts at `run`; *out is the first entry at
+// which it exceeds u, or - if none does - the last entry with mass.
 template <int kRule, bool kFind>
-__device__ __forceinline__ void segment_scan(const WalkShared& sh, const Row& prow, const Row& qrow,
-                                             bool vec_ok, int node, int v0, int quads, int V, float it,
-                                             double u, double* mass, int* last, int* found) {
+__device__ __forceinline__ double run_scan(const WalkShared& sh, const Row& prow, const Row& qrow, bool vec_ok,
+                                           int node, int v0, int quads, int end, float it, double u, double run,
+                                           int* out) {
     constexpr bool kDraft = (kRule == TV_RULE_DRAFT_WOR || kRule == TV_RULE_DRAFT_WR);
-    double acc = kFind ? *mass : 0.0;
     int lst = -1, fnd = -1;
     const float m_p = sh.m_p[node], m_q = kDraft ? sh.m_q[node] : 0.f;
     const double inv_s_p = sh.inv_s_p[node], inv_s_q = kDraft ? sh.inv_s_q[node] : 0.0;
     const int n = sh.n_steps;
-    for (int g = 0; g < quads; ++g) {
-        const int v = v0 + 4 * g;
-        if (v >= V) break;
-        float zp[4], zq[4];
-        load_quad(prow, vec_ok, v, V, zp);
-        if (kDraft) load_quad(qrow, vec_ok, v, V, zq);
-        double p[4], q[4];
+    for (int g0 = 0; g0 < quads; g0 += kDrawQuads) {
+        // all loads of a batch are requested before the first is used
+        float zp[kDrawQuads][4], zq[kDraft ? kDrawQuads : 1][4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            p[e] = unnorm_prob(zp[e], m_p, it) * inv_s_p;
-            q[e] = kDraft ? unnorm_prob(zq[e], m_q, it) * inv_s_q : 0.0;
+        for (int g = 0; g < kDrawQuads; ++g) {
+            const int v = v0 + 4 * (g0 + g);
+            if (g0 + g < quads && v < end) {
+                load_quad(prow, vec_ok, v, end, zp[g]);       // entries past the piece read as -infinity: no mass
+                if (kDraft) load_quad(qrow, vec_ok, v, end, zq[g]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    zp[g][e] = -INFINITY;
+                    if (kDraft) zq[g][e] = -INFINITY;
+                }
+            }
         }
-        for (int i = 0; i < n; ++i) {              // one LDS read per rejection, four independent chains
-            const ChainStep st = sh.steps[i];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) law_step<kRule>(v + e, st, p[e], q[e]);
-        }
+        for (int g = 0; g < kDrawQuads; ++g) {
+            if (g0 + g >= quads) break;                 // (uniform: a short run costs no more than it holds)
+            const int v = v0 + 4 * (g0 + g);
+            double p[4], q[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            acc += p[e];
-            if (p[e] > 0.0) lst = v + e;
-            if (kFind && fnd < 0 && acc > u) fnd = v + e;
+            for (int e = 0; e < 4; ++e) {
+                p[e] = unnorm_prob(zp[g][e], m_p, it) * inv_s_p;
+                q[e] = kDraft ? unnorm_prob(zq[g][e], m_q, it) * inv_s_q : 0.0;
+            }
+            for (int i = 0; i < n; ++i) {              // one LDS read per rejection, four independent chains
+                const ChainStep st = sh.steps[i];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) law_step<kRule>(v + e, st, p[e], q[e]);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                run += p[e];
+                if (p[e] > 0.0) lst = v + e;
+                if (kFind && fnd < 0 && run > u) fnd = v + e;
+            }
         }
     }
-    *mass = acc;
-    *last = lst;
-    if (kFind) *found = fnd;
+    *out = kFind ? ((fnd >= 0) ? fnd : lst) : lst;
+    return run;
 }
 
-// One sequence, one vocabulary slice.
+// The first v at which the running sum of the law at `node` (after sh.n_steps rejections) exceeds u.  The law's
+// mass in each of n_pieces consecutive pieces of piece_len entries comes from mass_of(piece) - no pass over the
+// vocabulary - so only the piece that holds the crossing is read, by this one workgroup.  Every thread calls
+// this and gets the token (-1: the law has no mass at all).
+template <int kRule, typename MassFn>
+__device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared& sh, int b, int node, double u, float it,
+                                                int n_pieces, int piece_len, MassFn mass_of) {
+    constexpr bool kDraft = (kRule == TV_RULE_DRAFT_WOR || kRule == TV_RULE_DRAFT_WR);
+    const int V = a.V;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    if (wave == 0) {
+        // prefix sum over the pieces in vocabulary order (a lane holds kPer consecutive ones), first piece at which
+        // the running sum exceeds u; if rounding leaves the total at or below u, the last piece that carries mass
+        constexpr int kPer = kMaxPieces / kWave;
+        const int per = (n_pieces + kWave - 1) / kWave;        // (one piece per lane up to 64 pieces: all fetched at once)
+        double pm[kPer], mine = 0.0;
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            const int s = lane * per + k;
+            pm[k] = (k < per && s < n_pieces) ? mass_of(s) : 0.0;
+            mine += pm[k];
+        }
+        double inc = mine;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const double t = __shfl_up(inc, o, kWave);
+            if (lane >= o) inc += t;
+        }
+        double run = inc - mine, base_c = 0.0;
+        int cand = -1, has_mass = -1;
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            if (cand < 0 && k < per && lane * per + k < n_pieces && run + pm[k] > u) { cand = lane * per + k; base_c = run; }
+            if (pm[k] > 0.0) has_mass = lane * per + k;
+            run += pm[k];
+        }
+        const unsigned long long hit = __ballot(cand >= 0);
+        int piece;
+        double base = 0.0;
+        if (hit) {
+            const int first = __ffsll((long long)hit) - 1;
+            piece = __shfl(cand, first, kWave);
+            base = __shfl(base_c, first, kWave);
+        } else {
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) has_mass = max(has_mass, __shfl_xor(has_mass, o, kWave));
+            piece = has_mass;               // (-1: no mass anywhere)
+            base = -4.0;                    // no running sum inside it exceeds u: its last entry with mass is taken
+        }
+        if (lane == 0) {
+            sh.piece = piece;
+            sh.base = base;
+            sh.tok_out = -1;
+        }
+    }
+    __syncthreads();
+    const int piece = sh.piece;
+    if (piece < 0) return -1;
+
+    // the chosen piece, a contiguous run of quads per lane in vocabulary order
+    const Row prow = logits_row(a, a.target, b, node);
+    const Row qrow = kDraft ? logits_row(a, a.draft, b, node) : prow;
+    const bool vec_ok = prow.quad_aligned() && qrow.quad_aligned();
+    const int begin = piece * piece_len, end = min(V, begin + piece_len);
+    const int quads = (end - begin + 4 * kDrawThreads - 1) / (4 * kDrawThreads);
+    const int v0 = begin + tid * 4 * quads;
+    int last;
+    const double mine = run_scan<kRule, false>(sh, prow, qrow, vec_ok, node, v0, quads, end, it, u, 0.0, &last);
+    // the last entry of the piece that carries mass, and every wave's total (one LDS word per wave, no atomics)
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) last = max(last, __shfl_xor(last, o, kWave));
+    double inc = mine;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const double t = __shfl_up(inc, o, kWave);
+        if (lane >= o) inc += t;
+    }
+    if (lane == kWave - 1) {
+        sh.wave_tot[wave] = inc;
+        sh.wave_last[wave] = last;
+    }
+    __syncthreads();
+    // the wave in which the running sum crosses u (every thread finds the same one), the lane inside it
+    double tot[kDrawWaves];
+    int lasts[kDrawWaves];
+#pragma unroll
+    for (int w = 0; w < kDrawWaves; ++w) { tot[w] = sh.wave_tot[w]; lasts[w] = sh.wave_last[w]; }
+    double before = sh.base;
+    int w_star = -1, piece_last = -1;
+#pragma unroll
+    for (int w = 0; w < kDrawWaves; ++w) {
+        piece_last = max(piece_last, lasts[w]);
+        const bool crosses = (w_star < 0) && (before + tot[w] > u);
+        if (crosses) w_star = w;
+        if (w_star < 0) before += tot[w];
+    }
+    // (no wave's running sum exceeds u: the piece sums put the crossing here, the in-order sums round just below
+    //  it, or the total itself rounds to u or less - the last entry that carries mass)
+    if (w_star < 0) return piece_last;
+    if (wave == w_star) {
+        const unsigned long long over = __ballot(before + inc > u);       // not empty: the wave's total exceeds u
+        const int l_star = __ffsll((long long)over) - 1;
+        double run0 = before + __shfl(inc - mine, l_star, kWave);          // running sum in front of that lane's run
+        const int r0 = __shfl(v0, l_star, kWave), n_run = 4 * quads;
+        // that lane's entries, one per lane of this wave, in vocabulary order (64 at a time)
+        int tok = -1, lst = -1;
+        for (int e0 = 0; e0 < n_run && tok < 0; e0 += kWave) {
+            const int v = r0 + e0 + lane;
+            double p = 0.0, q = 0.0;
+            if (e0 + lane < n_run && v < end) {
+                p = unnorm_prob(prow[v], sh.m_p[node], it) * sh.inv_s_p[node];
+                if (kDraft) q = unnorm_prob(qrow[v], sh.m_q[node], it) * sh.inv_s_q[node];
+                for (int i = 0; i < sh.n_steps; ++i) law_step<kRule>(v, sh.steps[i], p, q);
+            }
+            double pre = p;
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const double t = __shfl_up(pre, o, kWave);
+                if (lane >= o) pre += t;
+            }
+            const unsigned long long cross = __ballot(run0 + pre > u);
+            const unsigned long long mass = __ballot(p > 0.0);
+            if (cross) tok = r0 + e0 + __ffsll((long long)cross) - 1;
+            if (mass) lst = r0 + e0 + 63 - __builtin_clzll(mass);
+            run0 += __shfl(pre, kWave - 1, kWave);
+        }
+        // (the lane's own sum exceeded u but the sums formed here round just below it: its last entry with mass)
+        if (lane == 0) sh.tok_out = (tok >= 0) ? tok : lst;
+    }
+    __syncthreads();
+    return sh.tok_out;
+}
+
+// mass of range `s` of the target row at `node`, as a share of the row (statistics kernel's ranges)
+__device__ __forceinline__ double range_mass(const AcceptArgs& a, const WalkShared& sh, int b, int node, int s, float it) {
+    const RowStat st = a.stats[(((int64_t)b * a.n_mat) * a.T + node) * a.splits + s];
+    const float m = sh.m_p[node];
+    return ((st.max_logit == m) ? st.sum_exp : st.sum_exp * unnorm_prob(st.max_logit, m, it)) * sh.inv_s_p[node];
+}
+
+// The target's own token at every node (sample-and-match rule).  Grid (T, B): one workgroup draws, for one node,
+// the token that plain sampling of the target would emit there: inverse CDF of softmax(target row /
+// temperature) at the node's uniform u[T + node].
+__global__ __launch_bounds__(kDrawThreads) void accept_sample_kernel(AcceptArgs a) {
+    const int i = blockIdx.x, b = blockIdx.y;
+    __shared__ WalkShared sh;
+    const float it = kLog2e / a.temperature;
+    if (threadIdx.x < kWave) {
+        const Red st = group_row_stat(a, b, 0, i, true, threadIdx.x, kWave, it, true);
+        if (threadIdx.x == 0) {
+            sh.m_p[i] = st.m;
+            sh.inv_s_p[i] = inv_mass(st.s);
+            sh.n_steps = 0;
+        }
+    }
+    __syncthreads();
+    const double u = (double)a.uniforms[(int64_t)b * 2 * a.T + a.T + i];
+    const int tok = draw_from_pieces<TV_RULE_SAMPLE_MATCH>(a, sh, b, i, u, it, a.splits, a.split_len,
+                                                           [&](int s) { return range_mass(a, sh, b, i, s, it); });
+    if (threadIdx.x == 0) a.sampled[(int64_t)b * a.T + i] = tok;
+}
+
+// ---- 3. walk + final draw ---------------------------------------------------------------------------------
+// One workgroup per sequence.
 template <int kRule>
-__device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared& sh, int b, int sl) {
+__global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a) {
+    __shared__ WalkShared sh;
+    const int b = blockIdx.x;
     const int T = a.T, V = a.V;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     // sample-and-match walks like greedy, with the node's sampled token in the place of the row's argmax
@@ -781,51 +926,32 @@ __device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared&
     constexpr bool kDraft = (kRule == TV_RULE_DRAFT_WOR || kRule == TV_RULE_DRAFT_WR);
     const float it = kGreedy ? 0.f : kLog2e / a.temperature;
 
-    for (int i = tid; i < T; i += kDrawThreads) {
+    // everything the walk needs is requested in one go: the tree, the uniforms, what the earlier kernels left per
+    // node - by the workgroup's last waves - and (below, by its first waves) the reduced ranges of every row, so that
+    // the two sets of loads share one memory round trip
+    for (int i = kDrawThreads - 1 - tid; i < T; i += kDrawThreads) {
         sh.parent[i] = a.parent[(int64_t)b * T + i];
         sh.token[i] = a.token[(int64_t)b * T + i];
         if (!kGreedy) {
             sh.unif[i] = a.uniforms[(int64_t)b * 2 * T + i];
             sh.unif[T + i] = a.uniforms[(int64_t)b * 2 * T + T + i];
+            sh.z_tok_p[i] = a.z_tok[((int64_t)b * a.n_mat) * T + i];             // (entry 0, the root's, is never read)
+            if (kDraft) {
+                sh.z_tok_q[i] = a.z_tok[((int64_t)b * a.n_mat + 1) * T + i];
+                sh.abit[i] = a.accept_bit[(int64_t)b * T + i];
+                sh.chain_z[i] = a.chain_z[(int64_t)b * T + i];
+            }
         }
+        if (kMatch) sh.argmax[i] = a.sampled[(int64_t)b * T + i];
     }
     // the contemplate rows' anchors (needed at the very end: fetched now, with everything else)
     const int n_con = (a.selected_con && a.con_anchor) ? min(a.C, kMaxRows) : 0;
-    for (int i = tid; i < n_con; i += kDrawThreads) sh.con_anchor[i] = a.con_anchor[(int64_t)b * a.C + i];
-    __syncthreads();
-    int bad = validate_tree(sh.parent, nullptr, T, &sh.flag);
-    {
-        int tok_bad = 0;
-        for (int i = tid; i < T; i += kDrawThreads)
-            if (sh.token[i] < 0 || sh.token[i] >= V) tok_bad = 1;
-        if (tok_bad) atomicOr(&sh.flag, TV_STATUS_BAD_TOKEN);
-        __syncthreads();
-        bad = sh.flag;
-    }
-    if (kDraft && !bad && *a.chain_fail) bad = TV_STATUS_INTERNAL;
-    int32_t* path = a.path + (int64_t)b * T;
-    if (bad) {                     // every workgroup of the sequence sees the same verdict; one reports it
-        if (sl == 0) {
-            for (int i = tid; i < T; i += kDrawThreads) path[i] = -1;
-            if (tid == 0) {
-                a.status[b] = bad;
-                a.n_accepted[b] = -1;
-                a.final_token[b] = -1;
-                a.final_kind[b] = -1;
-                a.last_node[b] = -1;
-                if (a.selected_con) a.selected_con[b] = -1;
-            }
-        }
-        return;
-    }
-
-    // per-row statistics and each node's token logit in its parent's row
-    if (kMatch) {
-        for (int i = tid; i < T; i += kDrawThreads) sh.argmax[i] = a.sampled[(int64_t)b * T + i];
-    } else {
+    for (int i = kDrawThreads - 1 - tid; i < n_con; i += kDrawThreads) sh.con_anchor[i] = a.con_anchor[(int64_t)b * a.C + i];
+    if (!kMatch) {
         const int n_rows = T * (kDraft ? 2 : 1);
-        int g = 1;                                   // lanes that share one row's ranges
-        while (2 * g * n_rows <= kDrawThreads && g < kWave) g *= 2;
+        int g = 1;                                   // lanes that share one row's ranges: one batch of loads per lane,
+        while ((a.splits + g - 1) / g > 8 && g < kWave) g *= 2;                      // more lanes while there are spare ones
+        while (2 * g * n_rows <= kDrawThreads && a.splits / (2 * g) >= 3 && g < kWave) g *= 2;
         const int per_pass = kDrawThreads / g;
         for (int r0 = 0; r0 < n_rows; r0 += per_pass) {
             const int r = r0 + tid / g;
@@ -836,24 +962,37 @@ __device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared&
                 if (mat == 0) {
                     sh.m_p[i] = st.m;
                     sh.argmax[i] = st.am;
-                    sh.inv_s_p[i] = kGreedy ? 0.0 : 1.0 / st.s;
+                    sh.inv_s_p[i] = kGreedy ? 0.0 : inv_mass(st.s);
                 } else {
                     sh.m_q[i] = st.m;
-                    sh.inv_s_q[i] = 1.0 / st.s;
+                    sh.inv_s_q[i] = inv_mass(st.s);
                 }
             }
         }
-        if (!kGreedy)
-            for (int i = 1 + tid; i < T; i += kDrawThreads) {
-                sh.z_tok_p[i] = logits_row(a, a.target, b, sh.parent[i])[sh.token[i]];
-                if (kDraft) {                          // what the chain kernel left for this node
-                    sh.z_tok_q[i] = logits_row(a, a.draft, b, sh.parent[i])[sh.token[i]];
-                    sh.abit[i] = a.accept_bit[(int64_t)b * T + i];
-                    sh.chain_z[i] = a.chain_z[(int64_t)b * T + i];
-                }
-            }
     }
     __syncthreads();
+    int bad = validate_tree(sh.parent, nullptr, T, &sh.flag);
+    {
+        int tok_bad = 0;
+        for (int i = tid; i < T; i += kDrawThreads)
+            if (sh.token[i] < 0 || sh.token[i] >= V) tok_bad = 1;
+        if (tok_bad) atomicOr(&sh.flag, TV_STATUS_BAD_TOKEN);
+        __syncthreads();
+        bad = sh.flag;
+    }
+    int32_t* path = a.path + (int64_t)b * T;
+    if (bad) {
+        for (int i = tid; i < T; i += kDrawThreads) path[i] = -1;
+        if (tid == 0) {
+            a.status[b] = bad;
+            a.n_accepted[b] = -1;
+            a.final_token[b] = -1;
+            a.final_kind[b] = -1;
+            a.last_node[b] = -1;
+            if (a.selected_con) a.selected_con[b] = -1;
+        }
+        return;
+    }
 
     // the walk: wave 0, LDS only.  Every lane follows the same path (the tests are wave-uniform); the
     // lanes only share the search for a node's children, which a ballot over the parent array gives in
@@ -876,13 +1015,15 @@ __device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared&
                 if (kGreedy) {
                     acc = (x == sh.argmax[cur]);
                 } else if (kRule == TV_RULE_DETERMINISTIC) {
+                    const double p0 = unnorm_prob(sh.z_tok_p[c], sh.m_p[cur], it) * sh.inv_s_p[cur];
                     double p, q;
-                    law_after<kRule>(x, unnorm_prob(sh.z_tok_p[c], sh.m_p[cur], it) * sh.inv_s_p[cur], 0.0,
-                                     sh.steps, nrej, &p, &q);
+                    law_after<kRule>(x, p0, 0.0, sh.steps, nrej, &p, &q);
                     acc = ((double)sh.unif[c] < p);
                     if (!acc) {
                         const double ps = 1.0 - p;       // mass of p left once x is removed
                         sh.steps[nrej] = ChainStep{x, 0.0, 0.0, (ps > 0.0) ? 1.0 / ps : 0.0};
+                        sh.rej_child[nrej] = c;
+                        sh.rej_p0[nrej] = p0;
                     }
                 } else {
                     acc = (sh.abit[c] != 0);
@@ -896,6 +1037,7 @@ __device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared&
                         const double qs = 1.0 - q;
                         sh.steps[nrej] = ChainStep{x, (z > 0.0) ? 1.0 / z : 0.0,
                                                    (kRule == TV_RULE_DRAFT_WOR && qs > 0.0) ? 1.0 / qs : 0.0, 1.0};
+                        sh.rej_child[nrej] = c;
                     }
                 }
                 if (acc) { next = c; break; }
@@ -910,145 +1052,57 @@ __device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared&
         sh.len = len;
         sh.n_steps = nrej;
         sh.rejected_any = (nrej > 0);
-        sh.tok_out = -1;
-        sh.slice_last = -1;
-        sh.hit = kDrawThreads;
     }
     __syncthreads();
     const int cur = sh.cur;
 
+    int tok;
     if (kGreedy) {
-        if (tid == 0) sh.tok_out = sh.argmax[cur];       // launched with one workgroup per sequence
+        tok = sh.argmax[cur];
     } else {
-        // ---- inverse CDF at the stop node: first v whose running sum of the law exceeds u --------
-        const Row prow = logits_row(a, a.target, b, cur);
-        const Row qrow = kDraft ? logits_row(a, a.draft, b, cur) : prow;
-        const bool vec_ok = prow.quad_aligned() && qrow.quad_aligned();
+        // ---- inverse CDF at the stop node: first v whose running sum of the final law exceeds u ---------------
         const double u = (double)sh.unif[T + cur];
-        const int quads = a.slice_len / (4 * kDrawThreads);     // quads of entries per lane, contiguous
-        unsigned long long* slots = a.slice_bits + (int64_t)b * kMaxSlices;
-
-        // (a) mass of the law inside this workgroup's slice, published with tag 0 in the two lowest mantissa bits
-        //     (the statistics kernel left tag 3 in every slot)
-        double mass;
-        int last;
-        const int v0 = sl * a.slice_len + tid * 4 * quads;
-        segment_scan<kRule, false>(sh, prow, qrow, vec_ok, cur, v0, quads, V, it, u, &mass, &last, nullptr);
-        if (last >= 0) atomicMax(&sh.slice_last, last);
-        const double tot = block_sum<kDrawWaves>(mass, sh.red);
-        if (tid == 0)
-            __hip_atomic_store(slots + sl, (unsigned long long)__double_as_longlong(tot) & ~3ull, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-
-        // (b) every workgroup of the sequence reads every slice's mass (they are all resident: the host sizes
-        //     the launch for that) and finds the slice in which the running sum crosses u; if rounding leaves the
-        //     total at or below u, the last slice that carries mass takes over
-        if (wave == 0) {
-            constexpr int kPer = kMaxSlices / kWave;
-            double sm[kPer], mine = 0.0;
-            int fail = 0;
-            unsigned polls = 0;
-#pragma unroll
-            for (int k = 0; k < kPer; ++k) {
-                const int s = lane * kPer + k;
-                sm[k] = 0.0;
-                if (s < a.n_slices) {
-                    unsigned long long bits;
-                    for (;;) {
-                        bits = __hip_atomic_load(slots + s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        if ((bits & 3ull) == 0ull) break;
-                        __builtin_amdgcn_s_sleep(1);
-                        if (++polls > a.wait_limit) { fail = 1; break; }
+        const int n = sh.n_steps;
+        // the last rejection that changed the target's law (draft rules: one whose corrected law had mass)
+        int eff = -1;
+        if (kDraft)
+            for (int i = 0; i < n; ++i)
+                if (sh.steps[i].inv_z > 0.0) eff = i;
+        if (kDraft && eff >= 0) {
+            // the corrected law after that rejection: its mass per slice of the sibling-chain kernel is that
+            // kernel's share of the normaliser, over the normaliser
+            const unsigned long long* parts = a.chain_parts + ((int64_t)b * T + sh.rej_child[eff]) * a.chain_slices;
+            const double inv_z = sh.steps[eff].inv_z;
+            tok = draw_from_pieces<kRule>(a, sh, b, cur, u, it, a.chain_slices, kChainSlice,
+                                          [&](int s) { return share_value(parts[s]) * inv_z; });
+        } else {
+            // the target's own law with the rejected tokens taken out (deterministic rule), scaled up accordingly:
+            // per range of the statistics kernel, the range's share minus the rejected tokens that lie in it
+            double scale = 1.0;
+            if (kRule == TV_RULE_DETERMINISTIC)
+                for (int i = 0; i < n; ++i)
+                    if (sh.steps[i].inv_ps > 0.0) scale *= sh.steps[i].inv_ps;
+            tok = draw_from_pieces<kRule>(a, sh, b, cur, u, it, a.splits, a.split_len, [&](int s) {
+                double m = range_mass(a, sh, b, cur, s, it);
+                if (kRule == TV_RULE_DETERMINISTIC) {
+                    const int lo = s * a.split_len, hi = lo + a.split_len;
+                    for (int i = 0; i < n; ++i) {
+                        const int x = sh.steps[i].tok;
+                        bool first = (x >= lo && x < hi);
+                        for (int k = 0; k < i; ++k) first = first && (sh.steps[k].tok != x);     // (a token proposed twice)
+                        if (first) m -= sh.rej_p0[i];
                     }
-                    sm[k] = __longlong_as_double((long long)(bits & ~3ull));
+                    m = fmax(m, 0.0) * scale;
                 }
-                mine += sm[k];
-            }
-            fail = __any(fail);
-            double inc = mine;
-#pragma unroll
-            for (int o = 1; o < kWave; o <<= 1) {
-                const double t = __shfl_up(inc, o, kWave);
-                if (lane >= o) inc += t;
-            }
-            double run = inc - mine, base_c = 0.0;
-            int cand = -1, has_mass = -1;
-#pragma unroll
-            for (int k = 0; k < kPer; ++k) {
-                if (cand < 0 && lane * kPer + k < a.n_slices && run + sm[k] > u) { cand = lane * kPer + k; base_c = run; }
-                if (sm[k] > 0.0) has_mass = lane * kPer + k;
-                run += sm[k];
-            }
-            const unsigned long long hit = __ballot(cand >= 0);
-            int s_star;
-            double base = 0.0;
-            if (hit) {
-                const int first = __ffsll((long long)hit) - 1;
-                s_star = __shfl(cand, first, kWave);
-                base = __shfl(base_c, first, kWave);
-            } else {
-#pragma unroll
-                for (int o = 32; o > 0; o >>= 1) has_mass = max(has_mass, __shfl_xor(has_mass, o, kWave));
-                s_star = has_mass;
-            }
-            if (lane == 0) {
-                sh.s_star = fail ? -2 : s_star;
-                sh.fallback = hit ? 0 : 1;
-                sh.base = base;
-            }
-        }
-        __syncthreads();
-        const int s_star = sh.s_star;
-        if (s_star == -2) {                       // the bounded wait ran out: report instead of hanging
-            if (sl == 0) {
-                for (int i = tid; i < T; i += kDrawThreads) path[i] = -1;
-                if (tid == 0) {
-                    a.status[b] = TV_STATUS_INTERNAL;
-                    a.n_accepted[b] = -1;
-                    a.final_token[b] = -1;
-                    a.final_kind[b] = -1;
-                    a.last_node[b] = -1;
-                    if (a.selected_con) a.selected_con[b] = -1;
-                }
-            }
-            return;
-        }
-        if (s_star != sl && !(s_star < 0 && sl == 0)) return;        // another slice finishes (slice 0 if no mass at all)
-        if (s_star >= 0 && !sh.fallback) {
-            // (c) the crossing is in this slice: a prefix sum over the lanes' masses in vocabulary order, then the
-            //     lane that holds the crossing walks its own entries one by one
-            double inc = mass;
-#pragma unroll
-            for (int o = 1; o < kWave; o <<= 1) {
-                const double t = __shfl_up(inc, o, kWave);
-                if (lane >= o) inc += t;
-            }
-            if (lane == kWave - 1) sh.wave_tot[wave] = inc;
-            __syncthreads();
-            double before = sh.base;
-            for (int w = 0; w < wave; ++w) before += sh.wave_tot[w];
-            const double excl = before + (inc - mass);
-            if (before + inc > u) atomicMin(&sh.hit, tid);
-            __syncthreads();
-            if (sh.hit == kDrawThreads) {
-                // the slice sums put the crossing here, the in-order sums round just below it
-                if (tid == 0) sh.tok_out = sh.slice_last;
-            } else if (tid == sh.hit) {
-                double run = excl;
-                int found = -1, seg_last = -1;
-                segment_scan<kRule, true>(sh, prow, qrow, vec_ok, cur, v0, quads, V, it, u, &run, &seg_last, &found);
-                sh.tok_out = (found >= 0) ? found : seg_last;
-            }
-        } else if (tid == 0) {
-            sh.tok_out = sh.slice_last;           // the last entry that carries mass (-1 if there is none)
+                return m;
+            });
         }
     }
-    __syncthreads();
     for (int i = tid; i < T; i += kDrawThreads) path[i] = sh.path[i];
     if (tid == 0) {
         a.status[b] = TV_STATUS_OK;
         a.n_accepted[b] = sh.len;
-        a.final_token[b] = sh.tok_out;
+        a.final_token[b] = tok;
         a.final_kind[b] = sh.rejected_any ? TV_FINAL_RESIDUAL : TV_FINAL_BONUS;
         a.last_node[b] = cur;
         if (a.selected_con) {
@@ -1063,26 +1117,13 @@ __device__ __forceinline__ void accept_walk_one(const AcceptArgs& a, WalkShared&
     }
 }
 
-// The launch holds a whole number of groups of n_slices workgroups, all resident together (the workgroups of a
-// group wait for each other's slice masses); a group takes sequences one after the other.
-template <int kRule>
-__global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a) {
-    __shared__ WalkShared sh;
-    const int n_groups = gridDim.x / a.n_slices;
-    const int group = blockIdx.x / a.n_slices, sl = blockIdx.x % a.n_slices;
-    for (int b = group; b < a.B; b += n_groups) {
-        __syncthreads();
-        accept_walk_one<kRule>(a, sh, b, sl);
-    }
-}
-
 }  // namespace
 
 int plan_accept(const tv_accept_desc& d, AcceptPlan* plan) {
     AcceptPlan p{};
     p.n_mat = (d.rule == TV_RULE_DRAFT_WOR || d.rule == TV_RULE_DRAFT_WR) ? 2 : 1;
     // about a thousand workgroups (four per CU), ranges no shorter than 4096 entries and - so that a workgroup can
-    // hold one in registers when it looks for the crossing of a draw (range_draw) - no longer than 8192
+    // hold one in registers when it looks for the crossing of a draw - no longer than 8192 where 64 ranges suffice
     const int rows = d.B * d.T * p.n_mat;
     int splits = (1024 + rows - 1) / rows;
     const int max_splits = (d.V + 4095) / 4096;
@@ -1095,67 +1136,39 @@ int plan_accept(const tv_accept_desc& d, AcceptPlan* plan) {
     len = (len + 7) / 8 * 8;          // ranges start on a 16-byte boundary of an aligned row (fp32 and bf16)
     p.splits = (d.V + len - 1) / len;
     p.split_len = len;
-    // the final draw: at most kMaxSlices slices, each a whole number of quads per lane
-    constexpr int kGrain = 4 * kDrawThreads;
-    int ns = (d.V + kGrain - 1) / kGrain;
-    if (ns > kMaxSlices) ns = kMaxSlices;
-    int slen = (d.V + ns - 1) / ns;
-    slen = (slen + kGrain - 1) / kGrain * kGrain;
-    p.slice_len = slen;
-    p.n_slices = (d.rule == TV_RULE_GREEDY || d.rule == TV_RULE_SAMPLE_MATCH) ? 1 : (d.V + slen - 1) / slen;
     auto up = [](size_t x) { return (x + 255) / 256 * 256; };
     p.stats_bytes = up((size_t)rows * p.splits * sizeof(RowStat));
+    p.ztok_bytes = up((size_t)rows * sizeof(float));
     p.chain_bytes = up((size_t)d.B * d.T * sizeof(double));
     p.bits_bytes = up((size_t)d.B * d.T * sizeof(int32_t));
-    p.slice_bytes = up((size_t)d.B * kMaxSlices * sizeof(unsigned long long));
-    // the sibling chains: one group of workgroups per node, one slice of kChainThreads * kChainPer entries each
-    constexpr int kChainSlice = kChainThreads * kChainPer;
+    // the sibling chains: one group of workgroups per node, one slice of kChainSlice entries each; every child
+    // keeps the shares of its reduction
     p.chain_slices = (d.V + kChainSlice - 1) / kChainSlice;
-    p.chain_parts_bytes = (p.n_mat == 2) ? up((size_t)d.B * d.T * 2 * p.chain_slices * sizeof(double)) : 0;
-    p.chain_ctl_bytes = (p.n_mat == 2) ? up(sizeof(int32_t)) : 0;
-    p.total_bytes = p.stats_bytes + p.chain_bytes + p.bits_bytes + p.slice_bytes + p.chain_parts_bytes +
-                    p.chain_ctl_bytes;
+    if (p.n_mat == 2 && p.chain_slices > kMaxPieces) return TV_ERR_UNSUPPORTED;
+    p.chain_parts_bytes = (p.n_mat == 2) ? up((size_t)d.B * d.T * p.chain_slices * sizeof(double)) : 0;
+    p.total_bytes = p.stats_bytes + p.ztok_bytes + p.chain_bytes + p.bits_bytes + p.chain_parts_bytes;
     *plan = p;
     return TV_OK;
 }
 
-// Workgroups of the chain kernel that are resident together on the current device (0 if unknown).
-static int chain_resident_workgroups(int rule) {
-    static int cache[2][64];
+// Workgroups of the chain kernel that fit on the current device at once (0 if unknown): the launch is sized to
+// that, so that the groups' workgroups usually meet each other running (nothing breaks when they do not).
+static int chain_resident_workgroups(int rule, size_t dyn_smem) {
+    static std::atomic<int> cache[2][64];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-    int& c = cache[rule == TV_RULE_DRAFT_WOR ? 0 : 1][dev];
-    if (c == 0) {
+    std::atomic<int>& c = cache[rule == TV_RULE_DRAFT_WOR ? 0 : 1][dev];
+    int v = c.load(std::memory_order_relaxed);
+    if (v == 0) {
         int per_cu = 0, cus = 0;
         const hipError_t e1 = (rule == TV_RULE_DRAFT_WOR)
-            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_chain_kernel<TV_RULE_DRAFT_WOR>, kChainThreads, 0)
-            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_chain_kernel<TV_RULE_DRAFT_WR>, kChainThreads, 0);
+            ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_chain_kernel<TV_RULE_DRAFT_WOR>, kChainThreads, dyn_smem)
+            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_chain_kernel<TV_RULE_DRAFT_WR>, kChainThreads, dyn_smem);
         const hipError_t e2 = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e1 == hipSuccess && e2 == hipSuccess && per_cu > 0 && cus > 0) c = per_cu * cus;
+        if (e1 == hipSuccess && e2 == hipSuccess && per_cu > 0 && cus > 0) v = per_cu * cus;
+        c.store(v, std::memory_order_relaxed);
     }
-    return c;
-}
-
-// Workgroups of the walk kernel that are resident together on the current device (0 if unknown).
-static int walk_resident_workgroups(int rule) {
-    static int cache[5][64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64 || rule < 0 || rule > 4) return 0;
-    int& c = cache[rule][dev];
-    if (c == 0) {
-        int per_cu = 0, cus = 0;
-        hipError_t e1;
-        switch (rule) {
-            case TV_RULE_GREEDY: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_GREEDY>, kDrawThreads, 0); break;
-            case TV_RULE_DETERMINISTIC: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_DETERMINISTIC>, kDrawThreads, 0); break;
-            case TV_RULE_DRAFT_WOR: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_DRAFT_WOR>, kDrawThreads, 0); break;
-            case TV_RULE_SAMPLE_MATCH: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_SAMPLE_MATCH>, kDrawThreads, 0); break;
-            default: e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, accept_walk_kernel<TV_RULE_DRAFT_WR>, kDrawThreads, 0); break;
-        }
-        const hipError_t e2 = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e1 == hipSuccess && e2 == hipSuccess && per_cu > 0 && cus > 0) c = per_cu * cus;
-    }
-    return c;
+    return v;
 }
 
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t s) {
@@ -1163,21 +1176,18 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t s) {
     if (a.rule == TV_RULE_GREEDY) accept_stats_kernel<true><<<gs, kStatThreads, 0, s>>>(a);
     else accept_stats_kernel<false><<<gs, kStatThreads, 0, s>>>(a);
     if (a.rule == TV_RULE_DRAFT_WOR || a.rule == TV_RULE_DRAFT_WR) {
-        // whole groups only, and no more workgroups than the device holds at once (they wait for each other)
-        const int cap = chain_resident_workgroups(a.rule);
+        // whole groups only; as many as the device holds at once (fewer when that is unknown: one group)
+        const size_t dyn = (size_t)a.chain_slices * sizeof(unsigned long long);
+        const int cap = chain_resident_workgroups(a.rule, dyn);
         int groups = cap / a.chain_slices;
-        if (groups < 1) return hipErrorLaunchOutOfResources;
+        if (groups < 1) groups = 1;
         if (groups > a.B * a.T) groups = a.B * a.T;
         const unsigned gc = (unsigned)groups * (unsigned)a.chain_slices;
-        if (a.rule == TV_RULE_DRAFT_WOR) accept_chain_kernel<TV_RULE_DRAFT_WOR><<<gc, kChainThreads, 0, s>>>(a);
-        else accept_chain_kernel<TV_RULE_DRAFT_WR><<<gc, kChainThreads, 0, s>>>(a);
+        if (a.rule == TV_RULE_DRAFT_WOR) accept_chain_kernel<TV_RULE_DRAFT_WOR><<<gc, kChainThreads, dyn, s>>>(a);
+        else accept_chain_kernel<TV_RULE_DRAFT_WR><<<gc, kChainThreads, dyn, s>>>(a);
     }
     if (a.rule == TV_RULE_SAMPLE_MATCH) accept_sample_kernel<<<dim3(a.T, a.B), kDrawThreads, 0, s>>>(a);
-    // whole groups of n_slices workgroups, no more than are resident at once
-    int walk_groups = walk_resident_workgroups(a.rule) / a.n_slices;
-    if (walk_groups < 1) return hipErrorLaunchOutOfResources;
-    if (walk_groups > a.B) walk_groups = a.B;
-    const dim3 gw((unsigned)walk_groups * (unsigned)a.n_slices);
+    const dim3 gw((unsigned)a.B);
     switch (a.rule) {
         case TV_RULE_GREEDY: accept_walk_kernel<TV_RULE_GREEDY><<<gw, kDrawThreads, 0, s>>>(a); break;
         case TV_RULE_SAMPLE_MATCH: accept_walk_kernel<TV_RULE_SAMPLE_MATCH><<<gw, kDrawThreads, 0, s>>>(a); break;

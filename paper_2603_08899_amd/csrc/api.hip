@@ -364,7 +364,8 @@ int tv_accept_workspace_bytes(const tv_accept_desc* desc, size_t* out_bytes) {
     const int rc = check_accept_desc(desc);
     if (rc != TV_OK) return rc;
     AcceptPlan p;
-    plan_accept(*desc, &p);
+    const int prc = plan_accept(*desc, &p);
+    if (prc != TV_OK) return prc;
     *out_bytes = p.total_bytes;
     return TV_OK;
 }
@@ -384,7 +385,8 @@ int tree_accept(const tv_accept_desc* desc, const void* target_logits, const voi
     if (desc->rule != TV_RULE_GREEDY && !uniforms) return TV_ERR_INVALID_ARG;
     if (desc->C > 0 && !con_anchor) return TV_ERR_INVALID_ARG;
     AcceptPlan p;
-    plan_accept(*desc, &p);
+    const int prc = plan_accept(*desc, &p);
+    if (prc != TV_OK) return prc;
     if (!workspace || workspace_bytes < p.total_bytes || ((uintptr_t)workspace & 255)) return TV_ERR_WORKSPACE;
     AcceptArgs a{};
     a.target = target_logits; a.draft = draft_rule ? draft_logits : nullptr;
@@ -394,19 +396,20 @@ int tree_accept(const tv_accept_desc* desc, const void* target_logits, const voi
     a.last_node = last_node; a.selected_con = selected_con; a.status = status;
     unsigned char* w = static_cast<unsigned char*>(workspace);
     a.stats = reinterpret_cast<RowStat*>(w);
-    a.chain_z = reinterpret_cast<double*>(w + p.stats_bytes);
-    a.accept_bit = reinterpret_cast<int32_t*>(w + p.stats_bytes + p.chain_bytes);
+    w += p.stats_bytes;
+    a.z_tok = reinterpret_cast<float*>(w);
+    w += p.ztok_bytes;
+    a.chain_z = reinterpret_cast<double*>(w);
+    w += p.chain_bytes;
+    a.accept_bit = reinterpret_cast<int32_t*>(w);
     a.sampled = a.accept_bit;
-    unsigned char* w2 = w + p.stats_bytes + p.chain_bytes + p.bits_bytes;
-    a.slice_bits = reinterpret_cast<unsigned long long*>(w2);
-    unsigned char* w3 = w2 + p.slice_bytes;
-    a.chain_parts = reinterpret_cast<unsigned long long*>(w3);
-    a.chain_fail = reinterpret_cast<int32_t*>(w3 + p.chain_parts_bytes);
+    w += p.bits_bytes;
+    a.chain_parts = reinterpret_cast<unsigned long long*>(w);
     a.B = desc->B; a.T = desc->T; a.V = desc->V; a.C = con_anchor ? desc->C : 0; a.rule = desc->rule;
     a.temperature = desc->temperature;
     a.row_stride = desc->logits_row_stride ? desc->logits_row_stride : desc->V;
     a.splits = p.splits; a.split_len = p.split_len; a.n_mat = p.n_mat;
-    a.n_slices = p.n_slices; a.slice_len = p.slice_len; a.chain_slices = p.chain_slices;
+    a.chain_slices = p.chain_slices;
     const int wl = g_wait_limit.load();
     a.wait_limit = wl > 0 ? (unsigned)wl : (1u << 20);
     const hipError_t e = launch_accept(a, static_cast<hipStream_t>(hip_stream));

@@ -70,16 +70,12 @@ struct RowStat {          // softmax statistics of one range of one logits row
 };
 
 struct AcceptPlan {
-    int splits;           // ranges a logits row is cut into for the statistics pass
-    int split_len;        // elements per range (multiple of 4)
+    int splits;           // ranges a logits row is cut into for the statistics pass (<= 64)
+    int split_len;        // elements per range (multiple of 8)
     int n_mat;            // 1 (target only) or 2 (target and draft)
-    int n_slices;         // workgroups per sequence that share the final draw (<= kMaxSlices)
-    int slice_len;        // vocabulary entries per slice (multiple of 4 * 256)
     int chain_slices;     // draft rules: workgroups per node in the sibling-chain kernel
-    size_t stats_bytes, chain_bytes, bits_bytes, slice_bytes, chain_parts_bytes, chain_ctl_bytes, total_bytes;
+    size_t stats_bytes, ztok_bytes, chain_bytes, bits_bytes, chain_parts_bytes, total_bytes;
 };
-
-constexpr int kMaxSlices = 128;      // a multiple of the wave size
 
 int plan_accept(const tv_accept_desc& d, AcceptPlan* plan);
 
@@ -99,21 +95,18 @@ struct AcceptArgs {
     int32_t* selected_con;
     int32_t* status;
     RowStat* stats;       // [B][n_mat][T][splits]
+    float*   z_tok;       // [B][n_mat][T]: logit of node c's token in its parent's row
     double*  chain_z;     // [B][T]: normaliser of the corrected law after rejecting child c
     int32_t* accept_bit;  // [B][T] (draft rules)
     int32_t* sampled;     // [B][T] (sample-and-match rule; same storage as accept_bit): the target's token at each node
-    unsigned long long* slice_bits;   // [B][kMaxSlices]: mass of the final law inside one vocabulary slice (fp64
-                             // bits; the two lowest are a tag: 0 = published, 3 = not yet)
-    unsigned long long* chain_parts;  // [B][T][2][chain_slices]: shares of a chain normaliser (fp64 bits, the two
-                             // lowest carrying a round tag), two buffers per node
-    int32_t* chain_fail;     // [1]: set when a bounded wait ran out
+    unsigned long long* chain_parts;  // [B][T][chain_slices]: per child, every slice's share of its chain normaliser
+                             // (fp64 bits; the two lowest are a tag: 0 = published, 3 = not yet)
     int B, T, V, C, rule;
     float temperature;
     int64_t row_stride;
     int splits, split_len, n_mat;
-    int n_slices, slice_len;
     int chain_slices;
-    unsigned wait_limit;     // polls before a workgroup gives up waiting for the others of its group
+    unsigned wait_limit;     // looks at another workgroup's slot before a workgroup computes that share itself
 };
 
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t s);

@@ -502,3 +502,29 @@ def test_sample_and_match_first_token_law_is_the_target_law():
         first = token[r["path"][1]] if r["n_accepted"] >= 1 else r["final_token"]
         counts[first] += 1
     assert np.abs(counts / n - _softmax64(tl[0], 1.0)).max() <= 2.0 / n
+
+
+@pytest.mark.parametrize("rule", [DET, WOR, WR])
+def test_banned_tokens_equal_a_smaller_vocabulary(rule):
+    """Logits of -infinity carry no mass: the walk over a vocabulary with banned entries is the walk over the
+    vocabulary without them (entries renumbered), for the same uniforms - textbook softmax over the finite
+    entries.  Pins what the oracle does with -infinity, which the HIP path is then held to."""
+    rng = np.random.default_rng(91)
+    V, T = 40, 9
+    parent = trees.random_tree(rng, T, 4, 3)
+    keep = np.sort(rng.choice(V, size=25, replace=False))            # the entries that stay finite
+    new_of = -np.ones(V, dtype=np.int64)
+    new_of[keep] = np.arange(len(keep))
+    for trial in range(40):
+        tl = rng.normal(0, 2, size=(T, V)).astype(np.float32)
+        dl = (0.8 * tl + rng.normal(0, 1, size=(T, V))).astype(np.float32)
+        tl[:, np.setdiff1d(np.arange(V), keep)] = -np.inf
+        dl[:, np.setdiff1d(np.arange(V), keep)] = -np.inf
+        token = rng.choice(keep, size=T).astype(np.int32)
+        un = rng.random(2 * T, dtype=np.float32)
+        draft = None if rule == DET else dl
+        full = oracle.tree_accept(tl, draft, token, parent, un, temperature=0.9, rule=rule)
+        small = oracle.tree_accept(np.ascontiguousarray(tl[:, keep]), None if draft is None else np.ascontiguousarray(dl[:, keep]),
+                                   new_of[token].astype(np.int32), parent, un, temperature=0.9, rule=rule)
+        assert np.array_equal(full["path"], small["path"]) and full["final_kind"] == small["final_kind"]
+        assert new_of[full["final_token"]] == small["final_token"]
