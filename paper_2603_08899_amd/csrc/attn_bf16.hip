@@ -283,38 +283,37 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
     const unsigned tok_bytes = (unsigned)(a.tok_stride * 2);
 
     // One tile: instruction j (0..7 K, 8..15 V) moves rows 4j..4j+3; lane l lands at byte 16*l of that 1 KB
-    // block and fetches the logical segment that the swizzle stores there.  This wave issues the
-    // instructions j = jj*WPS + wsub: the first PER/2 of them are K rows, the rest V rows.  The per-lane part
-    // of the address is constant; the tile only moves the (scalar) base.
-    // Row 4*jb + l_row of a tile: the 4-row block jb goes into the scalar base, the lane keeps l_row rows plus its
-    // swizzled segment.  The V swizzle does not depend on the block; the K swizzle depends on jb & 3, of which a
-    // wave meets NP values (jb = jj*WPS + wsub).
-    constexpr int NP = (WPS >= 4) ? 1 : 4 / WPS;
-    unsigned k_lane[NP];
+    // block and fetches the logical segment that the swizzle stores there (K: segment ^ (row & 15); V: segment ^
+    // 4 * (row & 3)).  This wave issues the instructions j = jj*WPS + wsub of each half.
+    // What differs between the PER/2 request instructions of a half tile is kept per lane (the row block's offset
+    // next to the lane's row and swizzled segment), so that one scalar base per half tile serves all of them and an
+    // instruction costs a couple of scalar operations.
+    constexpr int HP = PER / 2;                    // request instructions of this wave per half tile
+    unsigned k_voff[HP], v_voff[HP];
 #pragma unroll
-    for (int pi = 0; pi < NP; ++pi)
-        k_lane[pi] = (unsigned)l_row * tok_bytes + (unsigned)((l_seg ^ l_row ^ (4 * ((pi * WPS + wsub) & 3))) << 4);
-    const unsigned v_lane = (unsigned)l_row * tok_bytes + (unsigned)((l_seg ^ (l_row << 2)) << 4);
-    // piece jj (0 .. PER/2-1) of one half of a tile: one request instruction of this wave
-    auto issue_piece = [&](int t, int stage, int half, int jj) __attribute__((always_inline)) {      // half 0: K rows, half 1: V rows
+    for (int jj = 0; jj < HP; ++jj) {
+        const int jb = jj * WPS + wsub;            // 4-row block of the tile (0 .. 7)
+        k_voff[jj] = (unsigned)(4 * jb + l_row) * tok_bytes + (unsigned)((l_seg ^ l_row ^ (4 * (jb & 3))) << 4);
+        v_voff[jj] = (unsigned)(4 * jb + l_row) * tok_bytes + (unsigned)((l_seg ^ (l_row << 2)) << 4);
+    }
+    auto issue_half = [&](int t, int stage, int half) __attribute__((always_inline)) {      // half 0: K rows, half 1: V rows
         const int k0 = t * kTK;
-        const unsigned dst = __builtin_amdgcn_readfirstlane(ring_addr + stage * kStageBytes + half * kTileBytes);
+        const unsigned dst = __builtin_amdgcn_readfirstlane(ring_addr + stage * kStageBytes + half * kTileBytes + wsub * 1024);
         const unsigned char* base = half ? vbase : kbase;
         if (k0 + kTK <= Lk) {
             const unsigned long long tile_base = scalar_base(base + (size_t)k0 * tok_bytes);
-            const int jb = (jj * WPS + wsub) & 7;        // 4-row block of this instruction
-            dma16(dst + jb * 1024, tile_base + (unsigned long long)(4 * jb) * tok_bytes, half ? v_lane : k_lane[jj % NP]);
-        } else {                                             // last tile: never read past the sequence's rows
-            const int j = (half * (PER / 2) + jj) * WPS + wsub;
-            const int row = 4 * (j & 7) + l_row;
-            const unsigned key = (unsigned)min(k0 + row, Lk - 1);
-            const int seg = half ? (l_seg ^ (l_row << 2)) : (l_seg ^ (row & 15));
-            dma16(dst + (j & 7) * 1024, scalar_base(base), key * tok_bytes + (unsigned)(seg * 16));
-        }
-    };
-    auto issue_half = [&](int t, int stage, int half) __attribute__((always_inline)) {
 #pragma unroll
-        for (int jj = 0; jj < PER / 2; ++jj) issue_piece(t, stage, half, jj);
+            for (int jj = 0; jj < HP; ++jj) dma16(dst + jj * (WPS * 1024), tile_base, half ? v_voff[jj] : k_voff[jj]);
+        } else {                                             // last tile: never read past the sequence's rows
+#pragma unroll
+            for (int jj = 0; jj < HP; ++jj) {
+                const int jb = jj * WPS + wsub;
+                const int row = 4 * jb + l_row;
+                const unsigned key = (unsigned)min(k0 + row, Lk - 1);
+                const int seg = half ? (l_seg ^ (l_row << 2)) : (l_seg ^ (row & 15));
+                dma16(dst + jj * (WPS * 1024), scalar_base(base), key * tok_bytes + (unsigned)(seg * 16));
+            }
+        }
     };
     auto issue_tile = [&](int t, int stage) { issue_half(t, stage, 0); issue_half(t, stage, 1); };
     // 64-row workgroups fill both stages of every stream here; the others the lower half of their rings
@@ -517,9 +516,9 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
     // reach 2^kTau, harmless in fp32/bf16), so the rescale of O is rare.
 
     if (RB == 1) {
-        // Four streams of two stages.  A tile takes two barrier slots: phase A = K operands and the score products;
-        // phase B = mask, softmax next to the PREVIOUS tile's O^T += V^T P^T (issued one tile late so that the
-        // matrix pipe and the vector ALU work at the same time inside one wave), then the tile's V^T operands.
+        // Four streams of two stages.  A tile takes two barrier slots: phase A = matrix work only - K operands, the
+        // PREVIOUS tile's O^T += V^T P^T (its operands are in registers, so it runs while the K operands land) and
+        // the score products; phase B = vector work only - the tile's V^T operands (requested first), mask, softmax.
         // The two waves of a SIMD (w and w+4, i.e. streams 0-1 and streams 2-3) are one phase apart:
         //   slot 2t   : waves 0-3 phase A of tile t,  waves 4-7 phase B of tile t-1
         //   slot 2t+1 : waves 0-3 phase B of tile t,  waves 4-7 phase A of tile t
@@ -529,7 +528,7 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
         // of phase A(t+1) opens - three slots (a round and a half) ahead of their use.  Requests of a wave, in
         // order: K0 V0 K1 V1 (prologue) | K2 | V2 | K3 | V3 ...  Both halves of the workgroup run their own copy
         // of the loop (2*n_iter+1 barriers each): with the phase order fixed the accumulators stay in place.
-        bf16x8 va[8], pb[2];     // V^T operands and probabilities of the previous tile
+        bf16x8 va[8], pb[2];     // V^T operands and probabilities of the tile whose product is still to be issued
 #pragma unroll
         for (int e = 0; e < 8; ++e)
 #pragma unroll
@@ -561,31 +560,24 @@ __global__ __launch_bounds__(512, 1) void attn_bf16_kernel(const int32_t* prefix
                 else wait_vmcnt<0>();
             }
             __syncthreads();
-            if (t >= 0 && t + 2 < n_my) issue_half(tile_of(t + 2), t % S, 0);
         };
         auto phase_a = [&](int t) __attribute__((always_inline)) {
-            bf16x8 ka[8];        // all eight reads are requested before the first product (no read waits on a product)
+            bf16x8 ka[8];        // all eight reads are requested first; the previous tile's product runs while they land
             read_k(t, ka);
             __builtin_amdgcn_sched_barrier(0);
+            pv_mfma(va, pb);
             score_tile(ka, s);
         };
         auto phase_b = [&](int t) __attribute__((always_inline)) {
+            read_v(t, va);                             // requested first: the LDS latency runs under the softmax
+            __builtin_amdgcn_sched_barrier(0);
             mask_tile(t, s);
             const float tmax = tile_max(s);
-            if (t == 0) {
-                m_run = tmax;                          // nothing accumulated yet: adopt the tile's max as the reference
-            } else if (__any(tmax > m_run + kTau)) {
-                // rare: bring O up to date with the pending product, then rescale it to the new reference
-                pv_mfma(va, pb);
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                    for (int x = 0; x < 8; ++x) pb[ks][x] = (__bf16)0.f;
-                rescale(tmax > m_run + kTau, tmax);
-            }
-            pv_mfma(va, pb);                           // previous tile's product (matrix pipe) ...
-            probabilities(s, pb);                      // ... next to this tile's exponentials (vector ALU)
-            read_v(t, va);                             // this tile's V^T operands, used one tile later
+            if (t == 0) m_run = tmax;                  // nothing accumulated yet: adopt the tile's max as the reference
+            else if (__any(tmax > m_run + kTau)) rescale(tmax > m_run + kTau, tmax);      // rare
+            probabilities(s, pb);
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + 2 < n_my) issue_half(tile_of(t + 2), t % S, 0);
         };
         if ((wave >> 2) == 0) {
             for (int t = 0; t < n_iter; ++t) {
