@@ -267,7 +267,7 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a
 // of two, groups aligned to g; `sub` is the lane's index in its group).  Every lane of the wave calls
 // this; lanes whose group has no row pass active = false.  All lanes of a group return the result.
 __device__ __forceinline__ Red group_row_stat(const AcceptArgs& a, int b, int mat, int row, bool active,
-                                              int sub, int g, float it, bool want_sum) {
+                                              int sub, int g, float it, bool want_sum, uint4* keep = nullptr) {
     const RowStat* st = a.stats + ((((int64_t)b * a.n_mat + mat) * a.T + (active ? row : 0)) * a.splits);
     // A lane's ranges are sub, sub + g, ...  They are fetched kStatBatch at a time, 16 bytes each, all requested
     // before the first is looked at (a loop of single loads would pay one memory round trip per range).
@@ -278,6 +278,7 @@ __device__ __forceinline__ Red group_row_stat(const AcceptArgs& a, int b, int ma
             const int s = s0 + k * g;
             const uint4 w = *reinterpret_cast<const uint4*>(st + ((active && s < a.splits) ? s : 0));
             const bool live = active && s < a.splits;     // (an entry that is not there: never the max, no mass)
+            if (keep && live) keep[s] = w;                // (the caller's copy of the row's ranges, in LDS)
             x[k].max_logit = live ? __uint_as_float(w.x) : -INFINITY;
             x[k].argmax = live ? (int)w.y : 0x7fffffff;
             x[k].sum_exp = live ? __longlong_as_double((long long)(((unsigned long long)w.w << 32) | w.z)) : 0.0;
@@ -664,8 +665,9 @@ __global__ __launch_bounds__(kChainThreads) void accept_chain_kernel(AcceptArgs 
 }
 
 // ---- 2b. the inverse-CDF draw from a law whose mass per piece of the vocabulary is known -------------------------
-constexpr int kDrawQuads = 8;     // quads of entries a lane requests at once: 8192 entries per workgroup and batch
+constexpr int kDrawQuads = 2;     // quads of entries a lane holds: a piece has at most 8192 entries
 constexpr int kMaxPieces = 256;   // pieces a draw can choose among (four per lane of one wave)
+constexpr int kKeptRanges = 2048; // reduced ranges of the target rows a walk workgroup keeps in LDS (32 KB)
 
 struct WalkShared {
     int parent[kMaxRows];
@@ -691,59 +693,44 @@ struct WalkShared {
     double base;                  // mass of the final law in the pieces before the chosen one
     int flag, cur, n_steps, rejected_any, len, tok_out;
     int piece;
+    int ranges_kept;              // the target rows' reduced ranges are in `ranges` (T * splits <= kKeptRanges)
+    uint4 ranges[kKeptRanges];    // [node][range], as the statistics kernel wrote them
 };
 
 // One lane's contiguous run of vocabulary entries [v0, v0 + 4*quads) of the law at `node` after sh.n_steps
-// rejections, entries at or past `end` carrying no mass.  kFind = false: returns the mass of the run and, in *out,
-// its last entry that carries mass.  kFind = true: the running sum starts at `run`; *out is the first entry at
-// which it exceeds u, or - if none does - the last entry with mass.
+// rejections, from the logits zp / zq the lane holds (entries past the piece hold -infinity: no mass; quads <=
+// kDrawQuads).  kFind = false: returns the mass of the run and, in *out, its last entry that carries mass.
+// kFind = true: the running sum starts at `run`; *out is the first entry at which it exceeds u, or - if none
+// does - the last entry with mass.
 template <int kRule, bool kFind>
-__device__ __forceinline__ double run_scan(const WalkShared& sh, const Row& prow, const Row& qrow, bool vec_ok,
-                                           int node, int v0, int quads, int end, float it, double u, double run,
-                                           int* out) {
+__device__ __forceinline__ double run_scan(const WalkShared& sh, const float (&zp)[kDrawQuads][4],
+                                           const float (&zq)[kDrawQuads][4], int node, int v0, int quads, float it,
+                                           double u, double run, int* out) {
     constexpr bool kDraft = (kRule == TV_RULE_DRAFT_WOR || kRule == TV_RULE_DRAFT_WR);
     int lst = -1, fnd = -1;
     const float m_p = sh.m_p[node], m_q = kDraft ? sh.m_q[node] : 0.f;
     const double inv_s_p = sh.inv_s_p[node], inv_s_q = kDraft ? sh.inv_s_q[node] : 0.0;
     const int n = sh.n_steps;
-    for (int g0 = 0; g0 < quads; g0 += kDrawQuads) {
-        // all loads of a batch are requested before the first is used
-        float zp[kDrawQuads][4], zq[kDraft ? kDrawQuads : 1][4];
 #pragma unroll
-        for (int g = 0; g < kDrawQuads; ++g) {
-            const int v = v0 + 4 * (g0 + g);
-            if (g0 + g < quads && v < end) {
-                load_quad(prow, vec_ok, v, end, zp[g]);       // entries past the piece read as -infinity: no mass
-                if (kDraft) load_quad(qrow, vec_ok, v, end, zq[g]);
-            } else {
+    for (int g = 0; g < kDrawQuads; ++g) {
+        if (g >= quads) break;                      // (uniform: a short run costs no more than it holds)
+        const int v = v0 + 4 * g;
+        double p[4], q[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    zp[g][e] = -INFINITY;
-                    if (kDraft) zq[g][e] = -INFINITY;
-                }
-            }
+        for (int e = 0; e < 4; ++e) {
+            p[e] = unnorm_prob(zp[g][e], m_p, it) * inv_s_p;
+            q[e] = kDraft ? unnorm_prob(zq[g][e], m_q, it) * inv_s_q : 0.0;
+        }
+        for (int i = 0; i < n; ++i) {               // one LDS read per rejection, four independent chains
+            const ChainStep st = sh.steps[i];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) law_step<kRule>(v + e, st, p[e], q[e]);
         }
 #pragma unroll
-        for (int g = 0; g < kDrawQuads; ++g) {
-            if (g0 + g >= quads) break;                 // (uniform: a short run costs no more than it holds)
-            const int v = v0 + 4 * (g0 + g);
-            double p[4], q[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                p[e] = unnorm_prob(zp[g][e], m_p, it) * inv_s_p;
-                q[e] = kDraft ? unnorm_prob(zq[g][e], m_q, it) * inv_s_q : 0.0;
-            }
-            for (int i = 0; i < n; ++i) {              // one LDS read per rejection, four independent chains
-                const ChainStep st = sh.steps[i];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) law_step<kRule>(v + e, st, p[e], q[e]);
-            }
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                run += p[e];
-                if (p[e] > 0.0) lst = v + e;
-                if (kFind && fnd < 0 && run > u) fnd = v + e;
-            }
+        for (int e = 0; e < 4; ++e) {
+            run += p[e];
+            if (p[e] > 0.0) lst = v + e;
+            if (kFind && fnd < 0 && run > u) fnd = v + e;
         }
     }
     *out = kFind ? ((fnd >= 0) ? fnd : lst) : lst;
@@ -814,10 +801,27 @@ __device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared&
     const Row qrow = kDraft ? logits_row(a, a.draft, b, node) : prow;
     const bool vec_ok = prow.quad_aligned() && qrow.quad_aligned();
     const int begin = piece * piece_len, end = min(V, begin + piece_len);
-    const int quads = (end - begin + 4 * kDrawThreads - 1) / (4 * kDrawThreads);
+    const int quads = (end - begin + 4 * kDrawThreads - 1) / (4 * kDrawThreads);      // <= kDrawQuads (plan_accept)
     const int v0 = begin + tid * 4 * quads;
+    // the lane's logits, all requested before the first is used; they stay in registers for the second pass
+    float zp[kDrawQuads][4], zq[kDrawQuads][4];
+#pragma unroll
+    for (int g = 0; g < kDrawQuads; ++g) {
+        const int v = v0 + 4 * g;
+        if (g < quads && v < end) {
+            load_quad(prow, vec_ok, v, end, zp[g]);       // entries past the piece read as -infinity: no mass
+            if (kDraft) load_quad(qrow, vec_ok, v, end, zq[g]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) zp[g][e] = -INFINITY;
+        }
+        if (!kDraft || !(g < quads && v < end)) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) zq[g][e] = -INFINITY;
+        }
+    }
     int last;
-    const double mine = run_scan<kRule, false>(sh, prow, qrow, vec_ok, node, v0, quads, end, it, u, 0.0, &last);
+    const double mine = run_scan<kRule, false>(sh, zp, zq, node, v0, quads, it, u, 0.0, &last);
     // the last entry of the piece that carries mass, and every wave's total (one LDS word per wave, no atomics)
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) last = max(last, __shfl_xor(last, o, kWave));
@@ -852,32 +856,13 @@ __device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared&
     if (wave == w_star) {
         const unsigned long long over = __ballot(before + inc > u);       // not empty: the wave's total exceeds u
         const int l_star = __ffsll((long long)over) - 1;
-        double run0 = before + __shfl(inc - mine, l_star, kWave);          // running sum in front of that lane's run
-        const int r0 = __shfl(v0, l_star, kWave), n_run = 4 * quads;
-        // that lane's entries, one per lane of this wave, in vocabulary order (64 at a time)
-        int tok = -1, lst = -1;
-        for (int e0 = 0; e0 < n_run && tok < 0; e0 += kWave) {
-            const int v = r0 + e0 + lane;
-            double p = 0.0, q = 0.0;
-            if (e0 + lane < n_run && v < end) {
-                p = unnorm_prob(prow[v], sh.m_p[node], it) * sh.inv_s_p[node];
-                if (kDraft) q = unnorm_prob(qrow[v], sh.m_q[node], it) * sh.inv_s_q[node];
-                for (int i = 0; i < sh.n_steps; ++i) law_step<kRule>(v, sh.steps[i], p, q);
-            }
-            double pre = p;
-#pragma unroll
-            for (int o = 1; o < kWave; o <<= 1) {
-                const double t = __shfl_up(pre, o, kWave);
-                if (lane >= o) pre += t;
-            }
-            const unsigned long long cross = __ballot(run0 + pre > u);
-            const unsigned long long mass = __ballot(p > 0.0);
-            if (cross) tok = r0 + e0 + __ffsll((long long)cross) - 1;
-            if (mass) lst = r0 + e0 + 63 - __builtin_clzll(mass);
-            run0 += __shfl(pre, kWave - 1, kWave);
+        if (lane == l_star) {
+            // this lane's run holds the crossing: the same entries again, in order, from the running sum in front of
+            // them (if the sums formed here round just below u, the run's last entry with mass)
+            int tok;
+            run_scan<kRule, true>(sh, zp, zq, node, v0, quads, it, u, before + (inc - mine), &tok);
+            sh.tok_out = tok;
         }
-        // (the lane's own sum exceeded u but the sums formed here round just below it: its last entry with mass)
-        if (lane == 0) sh.tok_out = (tok >= 0) ? tok : lst;
     }
     __syncthreads();
     return sh.tok_out;
@@ -885,7 +870,14 @@ __device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared&
 
 // mass of range `s` of the target row at `node`, as a share of the row (statistics kernel's ranges)
 __device__ __forceinline__ double range_mass(const AcceptArgs& a, const WalkShared& sh, int b, int node, int s, float it) {
-    const RowStat st = a.stats[(((int64_t)b * a.n_mat) * a.T + node) * a.splits + s];
+    RowStat st;
+    if (sh.ranges_kept) {
+        const uint4 w = sh.ranges[node * a.splits + s];
+        st.max_logit = __uint_as_float(w.x);
+        st.sum_exp = __longlong_as_double((long long)(((unsigned long long)w.w << 32) | w.z));
+    } else {
+        st = a.stats[(((int64_t)b * a.n_mat) * a.T + node) * a.splits + s];
+    }
     const float m = sh.m_p[node];
     return ((st.max_logit == m) ? st.sum_exp : st.sum_exp * unnorm_prob(st.max_logit, m, it)) * sh.inv_s_p[node];
 }
@@ -903,6 +895,7 @@ __global__ __launch_bounds__(kDrawThreads) void accept_sample_kernel(AcceptArgs 
             sh.m_p[i] = st.m;
             sh.inv_s_p[i] = inv_mass(st.s);
             sh.n_steps = 0;
+            sh.ranges_kept = 0;
         }
     }
     __syncthreads();
@@ -913,9 +906,21 @@ __global__ __launch_bounds__(kDrawThreads) void accept_sample_kernel(AcceptArgs 
 }
 
 // ---- 3. walk + final draw ---------------------------------------------------------------------------------
-// One workgroup per sequence.
+// One workgroup per sequence.  What its first loads hang on comes as leading arguments of their own, which are in
+// registers when a wave starts (kernel-argument preload, see the build flags): the argument block itself costs a
+// memory round trip.
 template <int kRule>
-__global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a) {
+__global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat* stats, const float* z_tok,
+                                                                   const int32_t* parent, const int32_t* token,
+                                                                   const float* uniforms, int n_nodes, int n_splits,
+                                                                   AcceptArgs a) {
+    a.stats = const_cast<RowStat*>(stats);
+    a.z_tok = const_cast<float*>(z_tok);
+    a.parent = parent;
+    a.token = token;
+    a.uniforms = uniforms;
+    a.T = n_nodes;
+    a.splits = n_splits;
     __shared__ WalkShared sh;
     const int b = blockIdx.x;
     const int T = a.T, V = a.V;
@@ -947,6 +952,8 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a)
     // the contemplate rows' anchors (needed at the very end: fetched now, with everything else)
     const int n_con = (a.selected_con && a.con_anchor) ? min(a.C, kMaxRows) : 0;
     for (int i = kDrawThreads - 1 - tid; i < n_con; i += kDrawThreads) sh.con_anchor[i] = a.con_anchor[(int64_t)b * a.C + i];
+    const bool keep_ranges = !kGreedy && !kMatch && T * a.splits <= kKeptRanges;
+    if (tid == 0) sh.ranges_kept = keep_ranges ? 1 : 0;
     if (!kMatch) {
         const int n_rows = T * (kDraft ? 2 : 1);
         int g = 1;                                   // lanes that share one row's ranges: one batch of loads per lane,
@@ -957,7 +964,8 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(AcceptArgs a)
             const int r = r0 + tid / g;
             const bool active = r < n_rows;
             const int mat = (active && r >= T) ? 1 : 0, i = active ? r - mat * T : 0;
-            const Red st = group_row_stat(a, b, mat, i, active, tid % g, g, it, !kGreedy);
+            const Red st = group_row_stat(a, b, mat, i, active, tid % g, g, it, !kGreedy,
+                                          (keep_ranges && active && mat == 0) ? sh.ranges + i * a.splits : nullptr);
             if (active && tid % g == 0) {
                 if (mat == 0) {
                     sh.m_p[i] = st.m;
@@ -1131,7 +1139,7 @@ int plan_accept(const tv_accept_desc& d, AcceptPlan* plan) {
     if (splits > max_splits) splits = max_splits;
     if (splits < min_splits) splits = min_splits;
     if (splits < 1) splits = 1;
-    if (splits > 64) splits = 64;
+    if (splits > kMaxPieces) splits = kMaxPieces;
     int len = (d.V + splits - 1) / splits;
     len = (len + 7) / 8 * 8;          // ranges start on a 16-byte boundary of an aligned row (fp32 and bf16)
     p.splits = (d.V + len - 1) / len;
@@ -1145,6 +1153,7 @@ int plan_accept(const tv_accept_desc& d, AcceptPlan* plan) {
     // keeps the shares of its reduction
     p.chain_slices = (d.V + kChainSlice - 1) / kChainSlice;
     if (p.n_mat == 2 && p.chain_slices > kMaxPieces) return TV_ERR_UNSUPPORTED;
+    if (p.split_len > kDrawQuads * 4 * kDrawThreads) return TV_ERR_UNSUPPORTED;      // (a vocabulary beyond two million entries)
     p.chain_parts_bytes = (p.n_mat == 2) ? up((size_t)d.B * d.T * p.chain_slices * sizeof(double)) : 0;
     p.total_bytes = p.stats_bytes + p.ztok_bytes + p.chain_bytes + p.bits_bytes + p.chain_parts_bytes;
     *plan = p;
@@ -1189,11 +1198,11 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t s) {
     if (a.rule == TV_RULE_SAMPLE_MATCH) accept_sample_kernel<<<dim3(a.T, a.B), kDrawThreads, 0, s>>>(a);
     const dim3 gw((unsigned)a.B);
     switch (a.rule) {
-        case TV_RULE_GREEDY: accept_walk_kernel<TV_RULE_GREEDY><<<gw, kDrawThreads, 0, s>>>(a); break;
-        case TV_RULE_SAMPLE_MATCH: accept_walk_kernel<TV_RULE_SAMPLE_MATCH><<<gw, kDrawThreads, 0, s>>>(a); break;
-        case TV_RULE_DETERMINISTIC: accept_walk_kernel<TV_RULE_DETERMINISTIC><<<gw, kDrawThreads, 0, s>>>(a); break;
-        case TV_RULE_DRAFT_WOR: accept_walk_kernel<TV_RULE_DRAFT_WOR><<<gw, kDrawThreads, 0, s>>>(a); break;
-        default: accept_walk_kernel<TV_RULE_DRAFT_WR><<<gw, kDrawThreads, 0, s>>>(a); break;
+        case TV_RULE_GREEDY: accept_walk_kernel<TV_RULE_GREEDY><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, a.T, a.splits, a); break;
+        case TV_RULE_SAMPLE_MATCH: accept_walk_kernel<TV_RULE_SAMPLE_MATCH><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, a.T, a.splits, a); break;
+        case TV_RULE_DETERMINISTIC: accept_walk_kernel<TV_RULE_DETERMINISTIC><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, a.T, a.splits, a); break;
+        case TV_RULE_DRAFT_WOR: accept_walk_kernel<TV_RULE_DRAFT_WOR><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, a.T, a.splits, a); break;
+        default: accept_walk_kernel<TV_RULE_DRAFT_WR><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, a.T, a.splits, a); break;
     }
     return hipGetLastError();
 }

@@ -70,7 +70,7 @@ struct RowStat {          // softmax statistics of one range of one logits row
 };
 
 struct AcceptPlan {
-    int splits;           // ranges a logits row is cut into for the statistics pass (<= 64)
+    int splits;           // ranges a logits row is cut into for the statistics pass (<= 256)
     int split_len;        // elements per range (multiple of 8)
     int n_mat;            // 1 (target only) or 2 (target and draft)
     int chain_slices;     // draft rules: workgroups per node in the sibling-chain kernel
