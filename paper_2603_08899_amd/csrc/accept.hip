@@ -52,27 +52,23 @@ __device__ __forceinline__ double unnorm_prob(float z, float m, float it_log2e) 
 // 1 / s for a row (or law) sum; a row without any mass gives every entry probability 0
 __device__ __forceinline__ double inv_mass(double s) { return (s > 0.0) ? 1.0 / s : 0.0; }
 
+// exp((m_old - m_new) / temperature), m_new >= m_old: the factor that carries a sum over to a higher reference.  The
+// fp32 exponential (relative error ~1e-7, like every entry's own term) - the fp64 library routine is a long
+// instruction sequence that would sit at the end of every workgroup of the statistics pass.
+__device__ __forceinline__ double rescale_factor(float m_old, float m_new, float it_log2e) {
+    return (double)fast_exp2((m_old - m_new) * it_log2e);
+}
+
 struct Red {          // (max, lowest argmax, sum exp relative to max)
     float m;
     int am;
     double s;
 };
 
-__device__ __forceinline__ Red red_merge(const Red& a, const Red& b, float it_log2e) {
-    Red r;
-    if (a.m > b.m || (a.m == b.m && a.am <= b.am)) { r.m = a.m; r.am = a.am; }
-    else { r.m = b.m; r.am = b.am; }
-    // rescaling happens once per merge of already reduced values: use the fp64 exponential
-    const double sa = (a.s == 0.0) ? 0.0 : a.s * exp2((double)(a.m - r.m) * (double)it_log2e);
-    const double sb = (b.s == 0.0) ? 0.0 : b.s * exp2((double)(b.m - r.m) * (double)it_log2e);
-    r.s = sa + sb;
-    return r;
-}
-
 template <bool kGreedy>
 __device__ __forceinline__ void red_push(Red& r, float z, int v, float it_log2e) {
     if (z > r.m) {
-        if (!kGreedy && r.s != 0.0) r.s *= exp2((double)(r.m - z) * (double)it_log2e);
+        if (!kGreedy && r.s != 0.0) r.s *= rescale_factor(r.m, z, it_log2e);
         r.m = z;
         r.am = v;
     }
@@ -83,7 +79,7 @@ template <bool kGreedy>
 __device__ __forceinline__ void red_push4(Red& r, const float4 x, int v0, float it) {
     const float mx = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
     if (mx > r.m) {
-        if (!kGreedy && r.s != 0.0) r.s *= exp2((double)(r.m - mx) * (double)it);
+        if (!kGreedy && r.s != 0.0) r.s *= rescale_factor(r.m, mx, it);
         r.m = mx;
         r.am = (x.x == mx) ? v0 : (x.y == mx) ? v0 + 1 : (x.z == mx) ? v0 + 2 : v0 + 3;
     }
@@ -113,7 +109,7 @@ __device__ __forceinline__ void red_push_batch(Red& r, const float4 (&x)[N], con
         }
     }
     if (bm > r.m) {
-        if (!kGreedy && r.s != 0.0) r.s *= exp2((double)(r.m - bm) * (double)it);
+        if (!kGreedy && r.s != 0.0) r.s *= rescale_factor(r.m, bm, it);
         r.m = bm;
         r.am = bam;
     }
@@ -184,7 +180,7 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a
     int v = begin;
     // Vector part: every lane requests a batch of 16-byte pieces before it uses the first (a range of the usual
     // size is one or two batches, so the workgroup pays few memory round trips).
-    constexpr int kInFlight = 4;
+    constexpr int kInFlight = 8;
     if (!lrow.bf16) {
         const float* base = static_cast<const float*>(lrow.p);
         if (aligned16(base + begin)) {
@@ -247,19 +243,36 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a
     double ws = 0.0;
     if (!kGreedy) {
         double s = r.s;
-        if (s != 0.0 && r.m != wm) s *= exp2((double)(r.m - wm) * (double)it);
+        if (s != 0.0 && r.m != wm) s *= rescale_factor(r.m, wm, it);
         ws = wave_sum(s);
     }
-    __shared__ Red wred[kStatThreads / kWave];
-    if ((threadIdx.x & (kWave - 1)) == 0) wred[threadIdx.x / kWave] = Red{wm, wam, ws};
+    constexpr int kStatWaves = kStatThreads / kWave;
+    __shared__ float wred_m[kStatWaves];
+    __shared__ int wred_am[kStatWaves];
+    __shared__ double wred_s[kStatWaves];
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        wred_m[threadIdx.x / kWave] = wm;
+        wred_am[threadIdx.x / kWave] = wam;
+        wred_s[threadIdx.x / kWave] = ws;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
-        Red t = wred[0];
-        for (int w = 1; w < kStatThreads / kWave; ++w) t = red_merge(t, wred[w], it);
+        // the waves' results: the maximum (lowest index on ties) first, then every wave's sum carried over to it
+        float m = wred_m[0];
+        int am = wred_am[0];
+#pragma unroll
+        for (int w = 1; w < kStatWaves; ++w)
+            if (wred_m[w] > m || (wred_m[w] == m && wred_am[w] < am)) { m = wred_m[w]; am = wred_am[w]; }
+        double sum = 0.0;
+#pragma unroll
+        for (int w = 0; w < kStatWaves; ++w) {
+            const double sw = wred_s[w];
+            sum += (sw == 0.0 || wred_m[w] == m) ? sw : sw * rescale_factor(wred_m[w], m, it);
+        }
         RowStat* out = a.stats + ((((int64_t)b * a.n_mat + mat) * a.T + row) * a.splits + split);
-        out->max_logit = t.m;
-        out->argmax = (t.am == 0x7fffffff) ? begin : t.am;      // nothing above -infinity: the range's first entry
-        out->sum_exp = t.s;
+        out->max_logit = m;
+        out->argmax = (am == 0x7fffffff) ? begin : am;      // nothing above -infinity: the range's first entry
+        out->sum_exp = sum;
     }
 }
 
@@ -699,41 +712,41 @@ struct WalkShared {
 
 // One lane's contiguous run of vocabulary entries [v0, v0 + 4*quads) of the law at `node` after sh.n_steps
 // rejections, from the logits zp / zq the lane holds (entries past the piece hold -infinity: no mass; quads <=
-// kDrawQuads).  kFind = false: returns the mass of the run and, in *out, its last entry that carries mass.
-// kFind = true: the running sum starts at `run`; *out is the first entry at which it exceeds u, or - if none
-// does - the last entry with mass.
-template <int kRule, bool kFind>
-__device__ __forceinline__ double run_scan(const WalkShared& sh, const float (&zp)[kDrawQuads][4],
-                                           const float (&zq)[kDrawQuads][4], int node, int v0, int quads, float it,
-                                           double u, double run, int* out) {
+// kDrawQuads).  Leaves the entries' probabilities in pv, returns their sum (added in vocabulary order) and, in
+// *last, the run's last entry that carries mass.
+template <int kRule>
+__device__ __forceinline__ double run_probs(const WalkShared& sh, const float (&zp)[kDrawQuads][4],
+                                            const float (&zq)[kDrawQuads][4], int node, int v0, int quads, float it,
+                                            double (&pv)[kDrawQuads * 4], int* last) {
     constexpr bool kDraft = (kRule == TV_RULE_DRAFT_WOR || kRule == TV_RULE_DRAFT_WR);
-    int lst = -1, fnd = -1;
+    int lst = -1;
+    double run = 0.0;
     const float m_p = sh.m_p[node], m_q = kDraft ? sh.m_q[node] : 0.f;
     const double inv_s_p = sh.inv_s_p[node], inv_s_q = kDraft ? sh.inv_s_q[node] : 0.0;
     const int n = sh.n_steps;
 #pragma unroll
     for (int g = 0; g < kDrawQuads; ++g) {
-        if (g >= quads) break;                      // (uniform: a short run costs no more than it holds)
         const int v = v0 + 4 * g;
         double p[4], q[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            p[e] = unnorm_prob(zp[g][e], m_p, it) * inv_s_p;
-            q[e] = kDraft ? unnorm_prob(zq[g][e], m_q, it) * inv_s_q : 0.0;
+            p[e] = (g < quads) ? unnorm_prob(zp[g][e], m_p, it) * inv_s_p : 0.0;
+            q[e] = (kDraft && g < quads) ? unnorm_prob(zq[g][e], m_q, it) * inv_s_q : 0.0;
         }
-        for (int i = 0; i < n; ++i) {               // one LDS read per rejection, four independent chains
-            const ChainStep st = sh.steps[i];
+        if (g < quads)                              // (uniform: a short run costs no more than it holds)
+            for (int i = 0; i < n; ++i) {           // one LDS read per rejection, four independent chains
+                const ChainStep st = sh.steps[i];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) law_step<kRule>(v + e, st, p[e], q[e]);
-        }
+                for (int e = 0; e < 4; ++e) law_step<kRule>(v + e, st, p[e], q[e]);
+            }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
+            pv[4 * g + e] = p[e];
             run += p[e];
             if (p[e] > 0.0) lst = v + e;
-            if (kFind && fnd < 0 && run > u) fnd = v + e;
         }
     }
-    *out = kFind ? ((fnd >= 0) ? fnd : lst) : lst;
+    *last = lst;
     return run;
 }
 
@@ -821,7 +834,8 @@ __device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared&
         }
     }
     int last;
-    const double mine = run_scan<kRule, false>(sh, zp, zq, node, v0, quads, it, u, 0.0, &last);
+    double pv[kDrawQuads * 4];
+    const double mine = run_probs<kRule>(sh, zp, zq, node, v0, quads, it, pv, &last);
     // the last entry of the piece that carries mass, and every wave's total (one LDS word per wave, no atomics)
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) last = max(last, __shfl_xor(last, o, kWave));
@@ -836,32 +850,38 @@ __device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared&
         sh.wave_last[wave] = last;
     }
     __syncthreads();
-    // the wave in which the running sum crosses u (every thread finds the same one), the lane inside it
-    double tot[kDrawWaves];
-    int lasts[kDrawWaves];
+    // the wave in which the running sum crosses u (every wave finds the same one: lane w looks at wave w)
+    static_assert(kDrawWaves <= kWave, "one lane per wave");
+    const double w_tot = (lane < kDrawWaves) ? sh.wave_tot[lane] : 0.0;
+    int piece_last = (lane < kDrawWaves) ? sh.wave_last[lane] : -1;
+    double w_inc = w_tot;
 #pragma unroll
-    for (int w = 0; w < kDrawWaves; ++w) { tot[w] = sh.wave_tot[w]; lasts[w] = sh.wave_last[w]; }
-    double before = sh.base;
-    int w_star = -1, piece_last = -1;
-#pragma unroll
-    for (int w = 0; w < kDrawWaves; ++w) {
-        piece_last = max(piece_last, lasts[w]);
-        const bool crosses = (w_star < 0) && (before + tot[w] > u);
-        if (crosses) w_star = w;
-        if (w_star < 0) before += tot[w];
+    for (int o = 1; o < kDrawWaves; o <<= 1) {
+        const double t = __shfl_up(w_inc, o, kWave);
+        if (lane >= o) w_inc += t;
+        piece_last = max(piece_last, __shfl_xor(piece_last, o, kWave));
     }
+    const unsigned long long w_over = __ballot(lane < kDrawWaves && sh.base + w_inc > u);
     // (no wave's running sum exceeds u: the piece sums put the crossing here, the in-order sums round just below
     //  it, or the total itself rounds to u or less - the last entry that carries mass)
-    if (w_star < 0) return piece_last;
+    if (!w_over) return __shfl(piece_last, 0, kWave);
+    const int w_star = __ffsll((long long)w_over) - 1;
+    const double before = sh.base + __shfl(w_inc - w_tot, w_star, kWave);
     if (wave == w_star) {
         const unsigned long long over = __ballot(before + inc > u);       // not empty: the wave's total exceeds u
         const int l_star = __ffsll((long long)over) - 1;
         if (lane == l_star) {
-            // this lane's run holds the crossing: the same entries again, in order, from the running sum in front of
-            // them (if the sums formed here round just below u, the run's last entry with mass)
-            int tok;
-            run_scan<kRule, true>(sh, zp, zq, node, v0, quads, it, u, before + (inc - mine), &tok);
-            sh.tok_out = tok;
+            // this lane's run holds the crossing: its entries again, in order, from the running sum in front of them
+            // (if the sums formed here round just below u, the run's last entry with mass)
+            double run = before + (inc - mine);
+            int fnd = -1, lst = -1;
+#pragma unroll
+            for (int e = 0; e < kDrawQuads * 4; ++e) {
+                run += pv[e];
+                if (pv[e] > 0.0) lst = v0 + e;
+                if (fnd < 0 && run > u) fnd = v0 + e;
+            }
+            sh.tok_out = (fnd >= 0) ? fnd : lst;
         }
     }
     __syncthreads();
