@@ -22,10 +22,12 @@ STATUS_BAD_PATH = 32
 
 def path_is_valid(path_row, n_accepted: int, node_row_row, T: int, M: int) -> bool:
     """A path is the root followed by strictly increasing node indices (a child's index exceeds its
-    parent's); every node must map to one of this step's M rows."""
+    parent's); every node must map to one of this step's M rows, and these rows increase along the
+    path too: the rows are the ones the tree attention of the step ran over, where a row comes after
+    its parent's row (Section 2, tree attention), and consecutive path entries are parent and child."""
     if n_accepted + 1 > T:
         return False
-    prev = -1
+    prev = prev_row = -1
     for j in range(n_accepted + 1):
         node = int(path_row[j])
         if node < 0 or node >= T or node <= prev:
@@ -33,9 +35,9 @@ def path_is_valid(path_row, n_accepted: int, node_row_row, T: int, M: int) -> bo
         if j == 0 and node != 0:
             return False
         row = node if node_row_row is None else int(node_row_row[node])
-        if row < 0 or row >= M:
+        if row < 0 or row >= M or row <= prev_row:
             return False
-        prev = node
+        prev, prev_row = node, row
     return True
 
 

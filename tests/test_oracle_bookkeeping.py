@@ -70,6 +70,19 @@ def test_commit_rejects_malformed_paths_and_skips_failed_sequences():
     assert np.array_equal(nk, k) and list(nl) == [P, P, P]
 
 
+def test_commit_rejects_a_row_map_that_puts_a_child_before_its_parent():
+    """The rows of a path are parent and child rows of the tree the attention ran over, so they increase along it;
+    a map that swaps two of them is flagged and nothing moves, the identity and the interleaved map pass."""
+    T, P, M = 4, 3, 8
+    k, v = _labelled_pool(1, P + M, 1, 2)
+    path = np.array([[0, 1, 3, -1]], dtype=np.int32)
+    for rows, ok in (([0, 2, 4, 6], True), ([0, 1, 2, 3], True), ([0, 6, 4, 2], False), ([0, 2, 4, 2], False)):
+        nk, _, nl, st = bk.commit_kv(k, v, [0], [P], path, [2], np.array([rows], dtype=np.int32), M)
+        assert (st[0] == 0) == ok and nl[0] == (P + 3 if ok else P)
+        if not ok:
+            assert np.array_equal(nk, k)
+
+
 def test_committed_cache_reproduces_the_accepted_nodes_attention():
     """Ties the commit to the attention oracle: the last accepted node attended to the prefix and to its own
     path under the tree mask; plain causal attention of the same query over the committed cache (prefix +
