@@ -24,21 +24,29 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 WORKLOAD_INDEX = 2              # llama3.1-8b-32layers
 PAPER_LAYOUT_INDEX = 5          # the same model shape with one contemplate row per draft node
+OTHER_WORKLOADS = (0, 1, 3, 4)  # the other named configurations: parity cases, timed for information
+DEEP_WALK_BOOST = 7.5           # child_boost of the acceptance inputs whose walk accepts about four nodes
 
 
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "attn_bf16_kernel_llama8b_hbm_traffic.txt")
 
 
-def measured_traffic_bytes():
-    """HBM bytes per attention launch from the committed counter summary (a line
-    `traffic_bytes_per_launch = N`), or None when the summary is absent."""
+def measured_traffic(library_version):
+    """(HBM bytes per attention launch, stamp) from the committed counter summary: the lines
+    `traffic_bytes_per_launch = N` and `library_version = V`.  The bytes are None when the summary is absent or
+    was taken with another version of the library than the one that is running."""
+    traffic, stamp = None, None
     try:
         for line in open(TRAFFIC_FILE):
             if line.startswith("traffic_bytes_per_launch"):
-                return int(float(line.split("=")[1]))
+                traffic = int(float(line.split("=")[1]))
+            elif line.startswith("library_version"):
+                stamp = int(line.split("=")[1])
     except OSError:
         pass
-    return None
+    if stamp != library_version:
+        traffic = None
+    return traffic, stamp
 
 
 def main() -> int:
@@ -78,47 +86,61 @@ def main() -> int:
 
     # ---- inputs, resident in HBM -------------------------------------------------------------------
     t0 = time.time()
-    def attention_setup(index, soft_len=0, head_major=False):
-        """All layers of workload `index` in one KV pool on the device, and a function that launches them.
-        The pool is [L, tokens, Hkv, D] (the workload's layout); head_major=True holds the same rows as
-        [L, Hkv, tokens, D] and hands the strides over in the descriptor."""
+    def attention_setup(index, soft_len=0, head_major=False, n_layers=None):
+        """n_layers layers of workload `index` (all of the benchmark's by default) in one KV pool on the device, and
+        a function that launches them.  The pool is [L, tokens, Hkv, D] (the workload's layout: the sequences of a
+        batch one after the other); head_major=True holds the same rows as [L, Hkv, tokens, D] and hands the strides
+        over in the descriptor."""
         wk = si.WORKLOADS[index]
+        n_layers = n_layers or L
         first = si.attention_case(index, layer=0, soft_len=soft_len)
-        m, p = first.M, int(first.prefix_len[0])
-        kp = torch.empty((L, p + m, wk.Hkv, wk.D), device="cuda", dtype=torch.bfloat16)
+        bf16 = first.dtype == "bf16"
+        tdt = torch.bfloat16 if bf16 else torch.float32
+        to_dev = to_device_bf16 if bf16 else (lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda())
+        B, m, p = first.B, first.M, int(first.prefix_len.max())
+        tokens = first.k_pool.shape[0]
+        kp = torch.empty((n_layers, tokens, wk.Hkv, wk.D), device="cuda", dtype=tdt)
         vp = torch.empty_like(kp)
-        q = torch.empty((L, 1, m, wk.Hq, wk.D), device="cuda", dtype=torch.bfloat16)
-        for l in range(L):
+        q = torch.empty((n_layers, B, m, wk.Hq, wk.D), device="cuda", dtype=tdt)
+        for l in range(n_layers):
             x = first if l == 0 else si.attention_case(index, layer=l, soft_len=soft_len)
-            kp[l].copy_(to_device_bf16(x.k_pool))
-            vp[l].copy_(to_device_bf16(x.v_pool))
-            q[l].copy_(to_device_bf16(x.q))
+            kp[l].copy_(to_dev(x.k_pool).reshape(tokens, wk.Hkv, wk.D))
+            vp[l].copy_(to_dev(x.v_pool).reshape(tokens, wk.Hkv, wk.D))
+            q[l].copy_(to_dev(x.q).reshape(B, m, wk.Hq, wk.D))
         strides = {}
         if head_major:
             kp = kp.permute(0, 2, 1, 3).contiguous()
             vp = vp.permute(0, 2, 1, 3).contiguous()
-            strides = dict(kv_token_stride=wk.D, kv_head_stride=(p + m) * wk.D)
+            strides = dict(kv_token_stride=wk.D, kv_head_stride=tokens * wk.D)
         o = torch.empty_like(q)
-        off = torch.zeros(1, dtype=torch.int64, device="cuda")
-        pl = torch.from_numpy(first.prefix_len).cuda()
-        par = torch.from_numpy(first.parent).cuda()
-        kin = torch.from_numpy(first.kind).cuda()
-        st = torch.zeros(1, dtype=torch.int32, device="cuda")
-        desc = tv.make_attn_desc(dtype=tv.TV_DTYPE_BF16, B=1, M=m, Hq=wk.Hq, Hkv=wk.Hkv, D=wk.D, soft_len=soft_len,
-                                 max_prefix_len=p, softmax_scale=first.scale, num_splits=args.splits,
-                                 wg_row_blocks=args.wg_row_blocks, **strides)
+        off = torch.from_numpy(first.kv_offset.astype(np.int64)).cuda()
+        pl = torch.from_numpy(first.prefix_len.astype(np.int32)).cuda()
+        par = torch.from_numpy(np.ascontiguousarray(first.parent, dtype=np.int32)).cuda()
+        kin = torch.from_numpy(np.ascontiguousarray(first.kind, dtype=np.uint8)).cuda()
+        st = torch.zeros(B, dtype=torch.int32, device="cuda")
+        desc = tv.make_attn_desc(dtype=tv.TV_DTYPE_BF16 if bf16 else tv.TV_DTYPE_F32, B=B, M=m, Hq=wk.Hq, Hkv=wk.Hkv,
+                                 D=wk.D, soft_len=soft_len, max_prefix_len=p, softmax_scale=first.scale,
+                                 num_splits=args.splits, wg_row_blocks=args.wg_row_blocks, **strides)
         ws = torch.empty(max(tv.tv_attention_workspace_bytes(desc), 256), device="cuda", dtype=torch.uint8)
+        prep = torch.zeros(B * tv.TV_PREPARED_TREE_BYTES, device="cuda", dtype=torch.uint8)
 
         def run():
-            for l in range(L):
-                tv.tree_verify_attention(desc, q[l], kp[l], vp[l], off, pl, par, kin, o[l], None, st, ws)
+            # the tree is checked and its masks are built once per step, for all layers (Section 3.1 / Figure 4)
+            if bf16:
+                tv.tv_prepare_tree(par, kin, prep)
+            for l in range(n_layers):
+                tv.tree_verify_attention(desc, q[l], kp[l], vp[l], off, pl, par, kin, o[l], None, st, ws,
+                                         prepared_tree=prep if bf16 else None)
 
-        bytes_layer = 2 * (p + m) * wk.Hkv * wk.D * 2 + 2 * m * wk.Hq * wk.D * 2
-        flops_layer = 4 * m * wk.Hq * (p + m) * wk.D
+        elem = 2 if bf16 else 4
+        keys = [int(x) + m for x in first.prefix_len]
+        bytes_layer = sum(2 * k * wk.Hkv * wk.D * elem for k in keys) + 2 * B * m * wk.Hq * wk.D * elem
+        flops_layer = sum(4 * m * wk.Hq * k * wk.D for k in keys)
         rb, n_ranges = tv.tv_attention_plan(desc)
         return {"run": run, "first": first, "out": o, "M": m, "P": p, "bytes": bytes_layer, "flops": flops_layer,
-                "plan": {"rows_per_workgroup": 64 * rb, "key_ranges": n_ranges},
-                "keep": (kp, vp, q, off, pl, par, kin, st, ws)}
+                "layers": n_layers, "status": st,
+                "plan": {"rows_per_workgroup": 64 * rb if bf16 else 16, "key_ranges": n_ranges},
+                "keep": (kp, vp, q, off, pl, par, kin, st, ws, prep)}
 
     main_attn = attention_setup(WORKLOAD_INDEX)
     layer0, outs, M, P = main_attn["first"], main_attn["out"], main_attn["M"], main_attn["P"]
@@ -203,6 +225,20 @@ def main() -> int:
     ms_accept = timed(accept, args.steps, args.warmup, 16)
     ms_greedy = timed(accept_greedy, args.steps, args.warmup, 16)
     ms_accept16 = timed(accept_bf16, args.steps, args.warmup, 16)
+
+    # the same call on inputs whose walk is about as deep as the accepted lengths the paper reports (tau 3.5 - 5.3)
+    dacc = si.accept_case(WORKLOAD_INDEX, 1, child_boost=DEEP_WALK_BOOST)
+    dtl = torch.from_numpy(dacc.target_logits).cuda()
+    dtoken = torch.from_numpy(dacc.token).cuda()
+    dun = torch.from_numpy(dacc.uniforms).cuda()
+    d_n = torch.zeros(1, **i32)
+
+    def accept_deep():
+        tv.tree_accept(cdesc, dtl, None, dtoken, aparent, dun, ca, path, d_n, o_tok, o_kind, o_last, o_con, o_st, cws)
+
+    ms_accept_deep = timed(accept_deep, args.steps, args.warmup, 16)
+    torch.cuda.synchronize()
+    deep_tau = int(d_n[0]) + 1
     us_layer = ms_attn * 1e3 / L
 
     # ---- the steps around the pass: commit of the accepted path (all layers, one call), contemplate embedding -----
@@ -268,6 +304,31 @@ def main() -> int:
         del hm
         other = {"kv_head_major_pool_us_per_layer": round(us_hm, 3), "kv_head_major_output_identical": hm_same}
 
+    # ---- the other named configurations, a few layers each (parity cases: timed for information only) ----------
+    others = None
+    if not args.no_paper_layout:
+        others = {}
+        for idx in OTHER_WORKLOADS:
+            wk = si.WORKLOADS[idx]
+            # (enough layers for the pool to exceed the 256 MB last-level cache where the shape allows it)
+            ow = attention_setup(idx, n_layers={0: 4, 1: 32, 3: 4, 4: 8}[idx])
+            us = timed(ow["run"], max(args.steps // 5, 3), 2) * 1e3 / ow["layers"]
+            torch.cuda.synchronize()
+            gbps = ow["bytes"] / (us * 1e-6) / 1e9
+            ent = {"us_per_layer": round(us, 3), "batch": ow["first"].B, "max_prefix": ow["P"], "rows": ow["M"],
+                   "dtype": ow["first"].dtype, "plan": ow["plan"], "status_ok": bool((ow["status"] == 0).all()),
+                   "algorithmic_bytes_per_launch": ow["bytes"]}
+            if ow["first"].dtype == "bf16":
+                ent["roofline"] = {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                   "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None}
+            else:       # the small fp32 case runs on the plain fp32 path
+                tf = ow["flops"] / (us * 1e-6) / 1e12
+                ent["roofline"] = {"bound": "alu", "achieved": round(tf, 3), "peak": 157.3, "unit": "TFLOP/s",
+                                   "frac": round(tf / 157.3, 5), "traffic": None}
+            others[wk.name] = ent
+            del ow
+            torch.cuda.empty_cache()
+
     # ---- what the CPU-baseline leg compares with the oracle (layer 0's output; the acceptance result) -----------
     torch.cuda.synchronize()
     got0 = outs[0].float().cpu().numpy()[0].astype(np.float64)
@@ -278,9 +339,12 @@ def main() -> int:
 
     # ---- roofline of the dominant kernel (attention) ------------------------------------------------------
     bytes_layer, flops_layer = main_attn["bytes"], main_attn["flops"]
+    lib_version = int(tv.lib().tv_version())
+    traffic_bytes, traffic_stamp = measured_traffic(lib_version)
     achieved = bytes_layer / (us_layer * 1e-6) / 1e9
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic_bytes(),
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic_bytes,
+                "traffic_profile_library_version": traffic_stamp, "library_version": lib_version,
                 "kernel": "attn_bf16_kernel (+ combine), per layer launch",
                 "algorithmic_bytes_per_launch": bytes_layer,
                 "mfma_frac_of_bf16_peak": round(flops_layer / (us_layer * 1e-6) / 2.5e15, 4)}
@@ -294,7 +358,8 @@ def main() -> int:
         "visited_rows": n_visit, "algorithmic_bytes": n_visit * acc.V * 4,
         "frac_of_hbm_peak_on_algorithmic": round(n_visit * acc.V * 4 / (ms_accept * 1e-3) / 1e9 / HBM_PEAK_GBPS, 5),
         "greedy_us_per_step": round(ms_greedy * 1e3, 2),
-        "bf16_logits_us_per_step": round(ms_accept16 * 1e3, 2), "bf16_logits_bytes_moved": moved // 2}
+        "bf16_logits_us_per_step": round(ms_accept16 * 1e3, 2), "bf16_logits_bytes_moved": moved // 2,
+        "deep_walk": {"us_per_step": round(ms_accept_deep * 1e3, 2), "tau": deep_tau, "child_boost": DEEP_WALK_BOOST}}
 
     # ---- CPU oracle on the host cores, bounded sample (about 10 s of attention layers, 2 s of acceptance walks).
     #      The same leg compares what the GPU produced with what the oracle says (the only place the oracle is
@@ -346,6 +411,7 @@ def main() -> int:
         "tree_accept": accept_info,
         "contemplate_row_per_node": paper,
         "other_layouts": other,
+        "other_workloads": others,
         "around_the_pass": around,
         "verify_steps_per_s": round(1e3 / ms_step, 2),
         "attention_tb_per_s": round(achieved / 1e3, 3),

@@ -285,7 +285,9 @@ int tree_commit(
     const int32_t* path,            /* device [B,T]: from tree_accept */
     const int32_t* n_accepted,      /* device [B]: from tree_accept */
     const int32_t* node_row,        /* device [B,T]: new-row index of tree node i (i if the nodes come first, 2i if a
-                                       contemplate row follows each node), or NULL for the identity */
+                                       contemplate row follows each node), or NULL for the identity.  Rows must
+                                       increase along every accepted path (a child's row comes after its parent's, as
+                                       the attention call requires of the same rows): TV_STATUS_BAD_PATH otherwise */
     const void*    hidden,          /* device [B,M,d_model] or NULL: final hidden states of this step's rows */
     const int32_t* con_row,         /* device [B,C]: new-row index of contemplate row c; NULL iff hidden is NULL */
     const int32_t* selected_con,    /* device [B]: from tree_accept; NULL iff hidden is NULL */

@@ -194,7 +194,7 @@ using namespace tv;
 
 extern "C" {
 
-int tv_version(void) { return 200; }
+int tv_version(void) { return 210; }
 
 static std::atomic<int> g_wait_limit{0};
 

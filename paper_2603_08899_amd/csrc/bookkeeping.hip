@@ -43,6 +43,10 @@ __global__ __launch_bounds__(kCommitThreads) void commit_kernel(CommitArgs a) {
         if (bad) s_ok = 0;
     }
     __syncthreads();
+    // the rows of the path must increase with it: the chunked move below relies on every source lying at or behind
+    // its destination (row of entry j >= j)
+    if (n >= 0 && n < T && tid >= 1 && tid <= n && s_src[tid] <= s_src[tid - 1]) s_ok = 0;
+    __syncthreads();
     const bool ok = n >= 0 && n < T && s_ok != 0;
     const int P = a.prefix_len[b];
     if (l == 0 && which == 0 && tid == 0) {

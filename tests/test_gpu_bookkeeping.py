@@ -115,6 +115,17 @@ def test_commit_malformed_paths_are_flagged_and_nothing_moves():
     assert list(st) == [bk.STATUS_BAD_PATH] * 3 + [0] and list(nl) == [5, 6, 7, 11]
 
 
+def test_commit_rows_that_do_not_increase_along_the_path_are_flagged():
+    """A row map under which a child's row comes before its parent's contradicts the tree the attention ran over:
+    flagged, nothing moves (the path spans several chunks of the move)."""
+    T = 40
+    path = np.arange(T, dtype=np.int32)[None].repeat(2, axis=0)
+    node_row = np.tile(np.arange(T, dtype=np.int32), (2, 1))
+    node_row[0, 20], node_row[0, 21] = 21, 20                 # sequence 0: two neighbours of the path swapped
+    _, nl, st = _run_commit("bf16", 2, 2, T, T + 4, 8, 128, [10, 12], path, [T - 1, T - 1], node_row, seed=6)
+    assert list(st) == [bk.STATUS_BAD_PATH, 0] and list(nl) == [10, 12 + T]
+
+
 def test_commit_padded_and_head_major_pools():
     rng = np.random.default_rng(33)
     B, T = 3, 20
