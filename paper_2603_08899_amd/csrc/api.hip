@@ -95,8 +95,8 @@ static int plan_attention_uncached(const tv_attn_desc& d, AttnPlan* plan) {
     // pools larger than the last-level cache).  A workgroup takes
     //   t = fixed(rb) + rounds * per_round(rb)
     // with rounds = tiles of its longest key stream, fixed = launch, prologue and epilogue (larger shapes merge
-    // and store more rows), per_round = one 32-key tile per stream (64-row workgroups become request-bound on
-    // long runs); one workgroup runs per CU at a time; the second kernel adds 3.3 when n > 1.
+    // and store more rows), per_round = one 32-key tile per stream (a little more on long runs, where the clock
+    // settles lower); one workgroup runs per CU at a time; the second kernel adds 3.3 when n > 1.
     // The lengths are on the device, so the model prices two batches: every sequence at max_prefix_len
     // (all workgroups alike: whole waves of them, waves * t), and a ragged one whose lengths average 0.55 of the
     // longest, which is near max_prefix_len (U{512..8192} has that mean; see t_ragged below).  The choice is the candidate
@@ -113,11 +113,15 @@ static int plan_attention_uncached(const tv_attn_desc& d, AttnPlan* plan) {
         const int64_t wgs = (int64_t)d.B * d.Hkv * ((rb_needed + rb - 1) / rb) * n;
         const int64_t waves = (wgs + cus - 1) / cus;
         const int rounds = (n_tiles + n * streams - 1) / (n * streams);
-        const double fixed = rb == 1 ? 6.5 : rb == 2 ? 11.6 : 15.5;
+        // (64-row workgroups that all run at once - no more of them than CUs - start and step faster than when a
+        //  second wave of them follows: 5.2 + r * 1.5..1.68 against 6.5 + r * 1.6..1.85, both measured)
+        const bool at_once = wgs <= cus;
+        const double fixed = rb == 1 ? (at_once ? 5.2 : 6.5) : rb == 2 ? 11.6 : 15.5;
         auto per_round = [&](double r) {
+            if (rb == 1 && at_once) return 1.50 + 0.18 * (r <= 5 ? 0.0 : r >= 9 ? 1.0 : (r - 5) / 4.0);
             if (rb == 1) return 1.60 + 0.25 * (r <= 17 ? 0.0 : r >= 33 ? 1.0 : (r - 17) / 16.0);
-            if (rb == 2) return 1.02 + 0.23 * (r <= 9 ? 0.0 : r >= 33 ? 1.0 : (r - 9) / 24.0);
-            return 1.20;
+            if (rb == 2) return 1.12 + 0.30 * (r <= 9 ? 0.0 : r >= 17 ? 1.0 : (r - 9) / 8.0);
+            return 1.35 + 0.08 * (r <= 9 ? 0.0 : r >= 33 ? 1.0 : (r - 9) / 24.0);
         };
         auto wg_us = [&](double r) { return fixed + r * per_round(r); };
         const double combine = n > 1 ? 3.3 : 0.0;
