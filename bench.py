@@ -60,7 +60,9 @@ def main() -> int:
     ap.add_argument("--splits", type=int, default=0, help="key ranges per sequence (0 = library decides)")
     ap.add_argument("--wg-row-blocks", type=int, default=0, help="row blocks sharing a key stream (0 = library decides)")
     ap.add_argument("--no-paper-layout", action="store_true",
-                    help="skip the extra measurement of the paper's 120-row layout")
+                    help="skip the extra measurements of the paper's 120-row layout and of the head-major pool")
+    ap.add_argument("--others", default=",".join(str(i) for i in OTHER_WORKLOADS),
+                    help="indices of the other named workloads to time (comma separated; empty: none)")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run three plain device copies of this many MiB before the timed region "
                          "(a kernel of known traffic, to scale hardware counters of a profiler run)")
@@ -306,12 +308,13 @@ def main() -> int:
 
     # ---- the other named configurations, a few layers each (parity cases: timed for information only) ----------
     others = None
-    if not args.no_paper_layout:
+    other_indices = [int(x) for x in args.others.split(",") if x.strip() != ""]
+    if other_indices:
         others = {}
-        for idx in OTHER_WORKLOADS:
+        for idx in other_indices:
             wk = si.WORKLOADS[idx]
             # (enough layers for the pool to exceed the 256 MB last-level cache where the shape allows it)
-            ow = attention_setup(idx, n_layers={0: 4, 1: 32, 3: 4, 4: 8}[idx])
+            ow = attention_setup(idx, n_layers={0: 4, 1: 32, 3: 4, 4: 8}.get(idx, 8))
             us = timed(ow["run"], max(args.steps // 5, 3), 2) * 1e3 / ow["layers"]
             torch.cuda.synchronize()
             gbps = ow["bytes"] / (us * 1e-6) / 1e9
