@@ -366,6 +366,26 @@ __device__ __forceinline__ void law_after(int v, double p0, double q0, const Cha
     *q_out = q;
 }
 
+// Inclusive prefix sum over the lanes of a wave with data-parallel-primitive moves (no LDS crossbar round trips, which
+// a chain of six dependent shuffles pays one after the other): Hillis-Steele inside each row of 16 lanes, then lane 15
+// of rows 0 and 2 is added to rows 1 and 3, then lane 31 to rows 2 and 3.  Lanes without a source take 0.
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ double dpp_moved(double x) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)b, kCtrl, kRowMask, 0xf, false);
+    const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(b >> 32), kCtrl, kRowMask, 0xf, false);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+__device__ __forceinline__ double wave_prefix_sum(double x) {
+    x += dpp_moved<0x111, 0xf>(x);      // row_shr:1
+    x += dpp_moved<0x112, 0xf>(x);      // row_shr:2
+    x += dpp_moved<0x114, 0xf>(x);      // row_shr:4
+    x += dpp_moved<0x118, 0xf>(x);      // row_shr:8
+    x += dpp_moved<0x142, 0xa>(x);      // row_bcast:15 into rows 1 and 3
+    x += dpp_moved<0x143, 0xc>(x);      // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
 template <int kWaves>
 __device__ __forceinline__ double block_sum(double x, double* scratch /* kWaves doubles */) {
     x = wave_sum(x);
@@ -772,12 +792,7 @@ __device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared&
             pm[k] = (k < per && s < n_pieces) ? mass_of(s) : 0.0;
             mine += pm[k];
         }
-        double inc = mine;
-#pragma unroll
-        for (int o = 1; o < kWave; o <<= 1) {
-            const double t = __shfl_up(inc, o, kWave);
-            if (lane >= o) inc += t;
-        }
+        const double inc = wave_prefix_sum(mine);
         double run = inc - mine, base_c = 0.0;
         int cand = -1, has_mass = -1;
 #pragma unroll
@@ -839,12 +854,7 @@ __device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared&
     // the last entry of the piece that carries mass, and every wave's total (one LDS word per wave, no atomics)
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) last = max(last, __shfl_xor(last, o, kWave));
-    double inc = mine;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        const double t = __shfl_up(inc, o, kWave);
-        if (lane >= o) inc += t;
-    }
+    const double inc = wave_prefix_sum(mine);
     if (lane == kWave - 1) {
         sh.wave_tot[wave] = inc;
         sh.wave_last[wave] = last;
@@ -854,13 +864,9 @@ __device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared&
     static_assert(kDrawWaves <= kWave, "one lane per wave");
     const double w_tot = (lane < kDrawWaves) ? sh.wave_tot[lane] : 0.0;
     int piece_last = (lane < kDrawWaves) ? sh.wave_last[lane] : -1;
-    double w_inc = w_tot;
+    const double w_inc = wave_prefix_sum(w_tot);          // (lanes past the waves hold 0)
 #pragma unroll
-    for (int o = 1; o < kDrawWaves; o <<= 1) {
-        const double t = __shfl_up(w_inc, o, kWave);
-        if (lane >= o) w_inc += t;
-        piece_last = max(piece_last, __shfl_xor(piece_last, o, kWave));
-    }
+    for (int o = 1; o < kDrawWaves; o <<= 1) piece_last = max(piece_last, __shfl_xor(piece_last, o, kWave));
     const unsigned long long w_over = __ballot(lane < kDrawWaves && sh.base + w_inc > u);
     // (no wave's running sum exceeds u: the piece sums put the crossing here, the in-order sums round just below
     //  it, or the total itself rounds to u or less - the last entry that carries mass)
