@@ -39,9 +39,9 @@ def measured_traffic(library_version):
     try:
         for line in open(TRAFFIC_FILE):
             if line.startswith("traffic_bytes_per_launch"):
-                traffic = int(float(line.split("=")[1]))
+                traffic = int(float(line.split("=")[1].split()[0]))
             elif line.startswith("library_version"):
-                stamp = int(line.split("=")[1])
+                stamp = int(line.split("=")[1].split()[0])
     except OSError:
         pass
     if stamp != library_version:
