@@ -279,17 +279,30 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a
 // Statistics of one row merged from its ranges by a group of g consecutive lanes of one wave (g a power
 // of two, groups aligned to g; `sub` is the lane's index in its group).  Every lane of the wave calls
 // this; lanes whose group has no row pass active = false.  All lanes of a group return the result.
-__device__ __forceinline__ Red group_row_stat(const AcceptArgs& a, int b, int mat, int row, bool active,
-                                              int sub, int g, float it, bool want_sum, uint4* keep = nullptr) {
+constexpr int kStatBatch = 8;
+// the first batch of a lane's ranges of one row (ranges sub, sub + g, ...), requested and not looked at
+__device__ __forceinline__ void row_stat_request(const AcceptArgs& a, int b, int mat, int row, bool active, int sub,
+                                                 int g, uint4 (&raw)[kStatBatch]) {
+    const RowStat* st = a.stats + ((((int64_t)b * a.n_mat + mat) * a.T + (active ? row : 0)) * a.splits);
+#pragma unroll
+    for (int k = 0; k < kStatBatch; ++k) {
+        const int s = sub + k * g;
+        raw[k] = *reinterpret_cast<const uint4*>(st + ((active && s < a.splits) ? s : 0));
+    }
+}
+template <bool kRequested>
+__device__ __forceinline__ Red group_row_stat_impl(const AcceptArgs& a, int b, int mat, int row, bool active,
+                                                   int sub, int g, float it, bool want_sum, uint4* keep,
+                                                   const uint4 (&first)[kStatBatch]) {
     const RowStat* st = a.stats + ((((int64_t)b * a.n_mat + mat) * a.T + (active ? row : 0)) * a.splits);
     // A lane's ranges are sub, sub + g, ...  They are fetched kStatBatch at a time, 16 bytes each, all requested
-    // before the first is looked at (a loop of single loads would pay one memory round trip per range).
-    constexpr int kStatBatch = 8;
-    auto fetch = [&](int s0, RowStat (&x)[kStatBatch]) {
+    // before the first is looked at (a loop of single loads would pay one memory round trip per range); the
+    // caller may have requested the first batch already (row_stat_request).
+    auto fetch = [&](int s0, RowStat (&x)[kStatBatch], bool pre) {
 #pragma unroll
         for (int k = 0; k < kStatBatch; ++k) {
             const int s = s0 + k * g;
-            const uint4 w = *reinterpret_cast<const uint4*>(st + ((active && s < a.splits) ? s : 0));
+            const uint4 w = pre ? first[k] : *reinterpret_cast<const uint4*>(st + ((active && s < a.splits) ? s : 0));
             const bool live = active && s < a.splits;     // (an entry that is not there: never the max, no mass)
             if (keep && live) keep[s] = w;                // (the caller's copy of the row's ranges, in LDS)
             x[k].max_logit = live ? __uint_as_float(w.x) : -INFINITY;
@@ -298,7 +311,7 @@ __device__ __forceinline__ Red group_row_stat(const AcceptArgs& a, int b, int ma
         }
     };
     RowStat head[kStatBatch];            // the lane's first batch stays in registers for the second pass
-    fetch(sub, head);
+    fetch(sub, head, kRequested);
     float m = -INFINITY;
     int am = 0x7fffffff;
     auto take_max = [&](const RowStat (&x)[kStatBatch]) {
@@ -312,7 +325,7 @@ __device__ __forceinline__ Red group_row_stat(const AcceptArgs& a, int b, int ma
     take_max(head);
     for (int s0 = sub + kStatBatch * g; s0 < a.splits; s0 += kStatBatch * g) {
         RowStat x[kStatBatch];
-        fetch(s0, x);
+        fetch(s0, x, false);
         take_max(x);
     }
     for (int o = 1; o < g; o <<= 1) {
@@ -330,12 +343,17 @@ __device__ __forceinline__ Red group_row_stat(const AcceptArgs& a, int b, int ma
         add(head);
         for (int s0 = sub + kStatBatch * g; s0 < a.splits; s0 += kStatBatch * g) {
             RowStat x[kStatBatch];
-            fetch(s0, x);
+            fetch(s0, x, false);
             add(x);
         }
         for (int o = 1; o < g; o <<= 1) sum += __shfl_xor(sum, o, kWave);
     }
     return Red{m, am, sum};
+}
+__device__ __forceinline__ Red group_row_stat(const AcceptArgs& a, int b, int mat, int row, bool active,
+                                              int sub, int g, float it, bool want_sum, uint4* keep = nullptr) {
+    const uint4 none[kStatBatch] = {};
+    return group_row_stat_impl<false>(a, b, mat, row, active, sub, g, it, want_sum, keep, none);
 }
 
 // ---- the law at a node after a number of rejections, one vocabulary entry at a time -------------------
@@ -935,63 +953,153 @@ __global__ __launch_bounds__(kDrawThreads) void accept_sample_kernel(AcceptArgs 
 // One workgroup per sequence.  What its first loads hang on comes as leading arguments of their own, which are in
 // registers when a wave starts (kernel-argument preload, see the build flags): the argument block itself costs a
 // memory round trip.
+// The kernel-argument segment of accept_walk_kernel as the launch lays it out (arguments in order, each at its
+// natural alignment).
+struct WalkKernArgs {
+    const RowStat* stats;
+    const float* z_tok;
+    const int32_t* parent;
+    const int32_t* token;
+    const float* uniforms;
+    unsigned geometry;
+    float temperature;
+    AcceptArgs a;
+};
+static_assert(offsetof(WalkKernArgs, a) == 48, "kernel-argument layout of accept_walk_kernel");
+
 template <int kRule>
 __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat* stats, const float* z_tok,
                                                                    const int32_t* parent, const int32_t* token,
-                                                                   const float* uniforms, int n_nodes, int n_splits,
-                                                                   AcceptArgs a) {
-    a.stats = const_cast<RowStat*>(stats);
-    a.z_tok = const_cast<float*>(z_tok);
-    a.parent = parent;
-    a.token = token;
-    a.uniforms = uniforms;
-    a.T = n_nodes;
-    a.splits = n_splits;
+                                                                   const float* uniforms, unsigned geometry,
+                                                                   float temperature, AcceptArgs /* read below */) {
     __shared__ WalkShared sh;
     const int b = blockIdx.x;
-    const int T = a.T, V = a.V;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     // sample-and-match walks like greedy, with the node's sampled token in the place of the row's argmax
     constexpr bool kMatch = (kRule == TV_RULE_SAMPLE_MATCH);
     constexpr bool kGreedy = (kRule == TV_RULE_GREEDY) || kMatch;
     constexpr bool kDraft = (kRule == TV_RULE_DRAFT_WOR || kRule == TV_RULE_DRAFT_WR);
-    const float it = kGreedy ? 0.f : kLog2e / a.temperature;
+    const float it = kGreedy ? 0.f : kLog2e / temperature;
 
-    // everything the walk needs is requested in one go: the tree, the uniforms, what the earlier kernels left per
-    // node - by the workgroup's last waves - and (below, by its first waves) the reduced ranges of every row, so that
-    // the two sets of loads share one memory round trip
-    for (int i = kDrawThreads - 1 - tid; i < T; i += kDrawThreads) {
-        sh.parent[i] = a.parent[(int64_t)b * T + i];
-        sh.token[i] = a.token[(int64_t)b * T + i];
+    // The reduced ranges of every row are requested first, from the leading arguments alone (they are in registers
+    // when the wave starts); the argument block is read after that, so that its memory round trip runs under the
+    // requests' instead of in front of them.
+    AcceptArgs lead{};
+    lead.stats = const_cast<RowStat*>(stats);
+    lead.T = (int)(geometry & 0xffu);
+    lead.splits = (int)((geometry >> 8) & 0xfffu);
+    lead.n_mat = (int)(geometry >> 20);
+    const int T = lead.T;
+    const int n_rows = kMatch ? 0 : T * (kDraft ? 2 : 1);
+    int g = 1;                                   // lanes that share one row's ranges: one batch of loads per lane,
+    while ((lead.splits + g - 1) / g > 8 && g < kWave) g *= 2;                      // more lanes while there are spare ones
+    while (2 * g * n_rows <= kDrawThreads && lead.splits / (2 * g) >= 3 && g < kWave) g *= 2;
+    const int per_pass = kDrawThreads / g;
+    uint4 first_raw[kStatBatch];
+    {
+        const int r = tid / g;
+        const bool active = r < n_rows;
+        const int mat = (active && r >= T) ? 1 : 0, i = active ? r - mat * T : 0;
+        if (!kMatch) row_stat_request(lead, b, mat, i, active, tid % g, g, first_raw);
+    }
+    // ... and so is what the walk needs per node - the tree, the tokens, the uniforms, every child's token logit -
+    // by the workgroup's last waves (thread 1023 - i takes node i; kMaxRows < kDrawThreads), into registers for now
+    const int my_node = kDrawThreads - 1 - tid;
+    const bool has_node = my_node < T;
+    int r_parent = 0, r_token = 0;
+    float r_u0 = 0.f, r_u1 = 0.f, r_zp = 0.f;
+    if (has_node) {
+        r_parent = parent[(int64_t)b * T + my_node];
+        r_token = token[(int64_t)b * T + my_node];
         if (!kGreedy) {
-            sh.unif[i] = a.uniforms[(int64_t)b * 2 * T + i];
-            sh.unif[T + i] = a.uniforms[(int64_t)b * 2 * T + T + i];
-            sh.z_tok_p[i] = a.z_tok[((int64_t)b * a.n_mat) * T + i];             // (entry 0, the root's, is never read)
+            r_u0 = uniforms[(int64_t)b * 2 * T + my_node];
+            r_u1 = uniforms[(int64_t)b * 2 * T + T + my_node];
+            r_zp = z_tok[((int64_t)b * lead.n_mat) * T + my_node];               // (entry 0, the root's, is never read)
+        }
+    }
+    // the argument block, through a pointer the compiler cannot look through: none of its loads moves above this line
+    typedef const WalkKernArgs __attribute__((address_space(4)))* kernarg_ptr;
+    kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ka) : : "memory");
+    AcceptArgs a;
+    {
+        static_assert(sizeof(AcceptArgs) % 4 == 0, "copied word by word");
+        typedef const unsigned __attribute__((address_space(4)))* kernarg_words;
+        kernarg_words src = (kernarg_words)&ka->a;
+        unsigned* dst = reinterpret_cast<unsigned*>(&a);
+#pragma unroll
+        for (unsigned w = 0; w < sizeof(AcceptArgs) / 4; ++w) dst[w] = src[w];
+    }
+    a.stats = const_cast<RowStat*>(stats);
+    a.z_tok = const_cast<float*>(z_tok);
+    a.parent = parent;
+    a.token = token;
+    a.uniforms = uniforms;
+    a.T = lead.T;
+    a.splits = lead.splits;
+    a.n_mat = lead.n_mat;
+    a.temperature = temperature;
+    const int V = a.V;
+
+    // what hangs on the argument block: the draft rules' per-node results of the chain kernel, the sampled tokens,
+    // the contemplate rows' anchors (needed at the very end: fetched now, with everything else).  All of these
+    // loads are issued before the first value is stored, so that they share one memory round trip.
+    float r_zq = 0.f;
+    int r_abit = 0, r_sampled = 0;
+    double r_chain_z = 0.0;
+    if (has_node) {
+        if (kDraft) {
+            r_zq = a.z_tok[((int64_t)b * a.n_mat + 1) * T + my_node];
+            r_abit = a.accept_bit[(int64_t)b * T + my_node];
+            r_chain_z = a.chain_z[(int64_t)b * T + my_node];
+        }
+        if (kMatch) r_sampled = a.sampled[(int64_t)b * T + my_node];
+    }
+    constexpr int kConPer = kMaxRows / kWave;
+    int r_con[kConPer];
+    int n_con_here = 0;
+    if (wave == kDrawWaves - 1) {
+        n_con_here = (a.selected_con && a.con_anchor) ? min(a.C, kMaxRows) : 0;
+#pragma unroll
+        for (int j = 0; j < kConPer; ++j) {
+            const int i = j * kWave + (kWave - 1 - lane);
+            r_con[j] = (i < n_con_here) ? a.con_anchor[(int64_t)b * a.C + i] : -1;
+        }
+    }
+    if (has_node) {
+        sh.parent[my_node] = r_parent;
+        sh.token[my_node] = r_token;
+        if (!kGreedy) {
+            sh.unif[my_node] = r_u0;
+            sh.unif[T + my_node] = r_u1;
+            sh.z_tok_p[my_node] = r_zp;
             if (kDraft) {
-                sh.z_tok_q[i] = a.z_tok[((int64_t)b * a.n_mat + 1) * T + i];
-                sh.abit[i] = a.accept_bit[(int64_t)b * T + i];
-                sh.chain_z[i] = a.chain_z[(int64_t)b * T + i];
+                sh.z_tok_q[my_node] = r_zq;
+                sh.abit[my_node] = r_abit;
+                sh.chain_z[my_node] = r_chain_z;
             }
         }
-        if (kMatch) sh.argmax[i] = a.sampled[(int64_t)b * T + i];
+        if (kMatch) sh.argmax[my_node] = r_sampled;
     }
-    // the contemplate rows' anchors (needed at the very end: fetched now, with everything else)
-    const int n_con = (a.selected_con && a.con_anchor) ? min(a.C, kMaxRows) : 0;
-    for (int i = kDrawThreads - 1 - tid; i < n_con; i += kDrawThreads) sh.con_anchor[i] = a.con_anchor[(int64_t)b * a.C + i];
+    if (wave == kDrawWaves - 1) {
+#pragma unroll
+        for (int j = 0; j < kConPer; ++j) {
+            const int i = j * kWave + (kWave - 1 - lane);
+            if (i < n_con_here) sh.con_anchor[i] = r_con[j];
+        }
+    }
     const bool keep_ranges = !kGreedy && !kMatch && T * a.splits <= kKeptRanges;
     if (tid == 0) sh.ranges_kept = keep_ranges ? 1 : 0;
     if (!kMatch) {
-        const int n_rows = T * (kDraft ? 2 : 1);
-        int g = 1;                                   // lanes that share one row's ranges: one batch of loads per lane,
-        while ((a.splits + g - 1) / g > 8 && g < kWave) g *= 2;                      // more lanes while there are spare ones
-        while (2 * g * n_rows <= kDrawThreads && a.splits / (2 * g) >= 3 && g < kWave) g *= 2;
-        const int per_pass = kDrawThreads / g;
         for (int r0 = 0; r0 < n_rows; r0 += per_pass) {
+            if (r0 + (wave * kWave) / g >= n_rows) break;      // no row for this wave in this pass, nor in a later one
             const int r = r0 + tid / g;
             const bool active = r < n_rows;
             const int mat = (active && r >= T) ? 1 : 0, i = active ? r - mat * T : 0;
-            const Red st = group_row_stat(a, b, mat, i, active, tid % g, g, it, !kGreedy,
-                                          (keep_ranges && active && mat == 0) ? sh.ranges + i * a.splits : nullptr);
+            uint4* keep = (keep_ranges && active && mat == 0) ? sh.ranges + i * a.splits : nullptr;
+            const Red st = (r0 == 0)
+                ? group_row_stat_impl<true>(a, b, mat, i, active, tid % g, g, it, !kGreedy, keep, first_raw)
+                : group_row_stat_impl<false>(a, b, mat, i, active, tid % g, g, it, !kGreedy, keep, first_raw);
             if (active && tid % g == 0) {
                 if (mat == 0) {
                     sh.m_p[i] = st.m;
@@ -1140,6 +1248,7 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
         a.final_kind[b] = sh.rejected_any ? TV_FINAL_RESIDUAL : TV_FINAL_BONUS;
         a.last_node[b] = cur;
         if (a.selected_con) {
+            const int n_con = a.con_anchor ? min(a.C, kMaxRows) : 0;
             int sel = -1;
             for (int c = 0; c < n_con && sel < 0; ++c)
                 if (sh.con_anchor[c] == cur) sel = c;
@@ -1223,12 +1332,15 @@ hipError_t launch_accept(const AcceptArgs& a, hipStream_t s) {
     }
     if (a.rule == TV_RULE_SAMPLE_MATCH) accept_sample_kernel<<<dim3(a.T, a.B), kDrawThreads, 0, s>>>(a);
     const dim3 gw((unsigned)a.B);
+    static_assert(kMaxRows <= 0xff && kMaxPieces <= 0xfff && kMaxRows < kDrawThreads && kMaxRows % kWave == 0,
+                  "packed geometry argument of the walk kernel; one thread per node");
+    const unsigned geometry = (unsigned)a.T | ((unsigned)a.splits << 8) | ((unsigned)a.n_mat << 20);
     switch (a.rule) {
-        case TV_RULE_GREEDY: accept_walk_kernel<TV_RULE_GREEDY><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, a.T, a.splits, a); break;
-        case TV_RULE_SAMPLE_MATCH: accept_walk_kernel<TV_RULE_SAMPLE_MATCH><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, a.T, a.splits, a); break;
-        case TV_RULE_DETERMINISTIC: accept_walk_kernel<TV_RULE_DETERMINISTIC><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, a.T, a.splits, a); break;
-        case TV_RULE_DRAFT_WOR: accept_walk_kernel<TV_RULE_DRAFT_WOR><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, a.T, a.splits, a); break;
-        default: accept_walk_kernel<TV_RULE_DRAFT_WR><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, a.T, a.splits, a); break;
+        case TV_RULE_GREEDY: accept_walk_kernel<TV_RULE_GREEDY><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, geometry, a.temperature, a); break;
+        case TV_RULE_SAMPLE_MATCH: accept_walk_kernel<TV_RULE_SAMPLE_MATCH><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, geometry, a.temperature, a); break;
+        case TV_RULE_DETERMINISTIC: accept_walk_kernel<TV_RULE_DETERMINISTIC><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, geometry, a.temperature, a); break;
+        case TV_RULE_DRAFT_WOR: accept_walk_kernel<TV_RULE_DRAFT_WOR><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, geometry, a.temperature, a); break;
+        default: accept_walk_kernel<TV_RULE_DRAFT_WR><<<gw, kDrawThreads, 0, s>>>(a.stats, a.z_tok, a.parent, a.token, a.uniforms, geometry, a.temperature, a); break;
     }
     return hipGetLastError();
 }
