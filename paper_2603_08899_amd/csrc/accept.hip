@@ -404,6 +404,18 @@ __device__ __forceinline__ double wave_prefix_sum(double x) {
     return x;
 }
 
+// x of lane `src`, src the same in every lane (a register read, no LDS crossbar trip)
+__device__ __forceinline__ int lane_value(int x, int src) {
+    return __builtin_amdgcn_readlane(x, __builtin_amdgcn_readfirstlane(src));
+}
+__device__ __forceinline__ double lane_value(double x, int src) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    const int s = __builtin_amdgcn_readfirstlane(src);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, s);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), s);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
 template <int kWaves>
 __device__ __forceinline__ double block_sum(double x, double* scratch /* kWaves doubles */) {
     x = wave_sum(x);
@@ -737,6 +749,7 @@ struct WalkShared {
     ChainStep steps[kMaxRows];    // the rejections at the stop node, in order
     int rej_child[kMaxRows];      // ... the child each of them turned down
     double rej_p0[kMaxRows];      // ... and the target's own probability of its token
+    double p0[kMaxRows];          // deterministic rule: probability of node c's token under its parent's own law
     int con_anchor[kMaxRows];     // node of each contemplate row (the first kMaxRows of them)
     double red[kDrawWaves];
     double wave_tot[kDrawWaves];
@@ -824,8 +837,8 @@ __device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared&
         double base = 0.0;
         if (hit) {
             const int first = __ffsll((long long)hit) - 1;
-            piece = __shfl(cand, first, kWave);
-            base = __shfl(base_c, first, kWave);
+            piece = lane_value(cand, first);
+            base = lane_value(base_c, first);
         } else {
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) has_mass = max(has_mass, __shfl_xor(has_mass, o, kWave));
@@ -869,28 +882,31 @@ __device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared&
     int last;
     double pv[kDrawQuads * 4];
     const double mine = run_probs<kRule>(sh, zp, zq, node, v0, quads, it, pv, &last);
-    // the last entry of the piece that carries mass, and every wave's total (one LDS word per wave, no atomics)
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) last = max(last, __shfl_xor(last, o, kWave));
+    // every wave's total (one LDS word per wave, no atomics)
     const double inc = wave_prefix_sum(mine);
-    if (lane == kWave - 1) {
-        sh.wave_tot[wave] = inc;
-        sh.wave_last[wave] = last;
-    }
+    if (lane == kWave - 1) sh.wave_tot[wave] = inc;
     __syncthreads();
     // the wave in which the running sum crosses u (every wave finds the same one: lane w looks at wave w)
     static_assert(kDrawWaves <= kWave, "one lane per wave");
     const double w_tot = (lane < kDrawWaves) ? sh.wave_tot[lane] : 0.0;
-    int piece_last = (lane < kDrawWaves) ? sh.wave_last[lane] : -1;
     const double w_inc = wave_prefix_sum(w_tot);          // (lanes past the waves hold 0)
-#pragma unroll
-    for (int o = 1; o < kDrawWaves; o <<= 1) piece_last = max(piece_last, __shfl_xor(piece_last, o, kWave));
     const unsigned long long w_over = __ballot(lane < kDrawWaves && sh.base + w_inc > u);
-    // (no wave's running sum exceeds u: the piece sums put the crossing here, the in-order sums round just below
-    //  it, or the total itself rounds to u or less - the last entry that carries mass)
-    if (!w_over) return __shfl(piece_last, 0, kWave);
+    if (!w_over) {
+        // No wave's running sum exceeds u: the piece sums put the crossing here, the in-order sums round just below
+        // it, or the total itself rounds to u or less - the last entry of the piece that carries mass is taken.
+        // (Rare, and the same in every wave - all of them formed w_over from the same LDS words - so the barrier
+        //  below is met by the whole workgroup.)
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) last = max(last, __shfl_xor(last, o, kWave));
+        if (lane == kWave - 1) sh.wave_last[wave] = last;
+        __syncthreads();
+        int piece_last = (lane < kDrawWaves) ? sh.wave_last[lane] : -1;
+#pragma unroll
+        for (int o = 1; o < kDrawWaves; o <<= 1) piece_last = max(piece_last, __shfl_xor(piece_last, o, kWave));
+        return lane_value(piece_last, 0);
+    }
     const int w_star = __ffsll((long long)w_over) - 1;
-    const double before = sh.base + __shfl(w_inc - w_tot, w_star, kWave);
+    const double before = sh.base + lane_value(w_inc - w_tot, w_star);
     if (wave == w_star) {
         const unsigned long long over = __ballot(before + inc > u);       // not empty: the wave's total exceeds u
         const int l_star = __ffsll((long long)over) - 1;
@@ -1113,6 +1129,12 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
         }
     }
     __syncthreads();
+    // the target's own probability of every node's token at its parent, all nodes at once: the walk, one wave
+    // stepping from child to child, then only reads it (visible after the barriers of the checks below)
+    if (kRule == TV_RULE_DETERMINISTIC && tid >= 1 && tid < T) {
+        const int pc = sh.parent[tid];
+        if (pc >= 0 && pc < tid) sh.p0[tid] = unnorm_prob(sh.z_tok_p[tid], sh.m_p[pc], it) * sh.inv_s_p[pc];
+    }
     int bad = validate_tree(sh.parent, nullptr, T, &sh.flag);
     {
         int tok_bad = 0;
@@ -1139,6 +1161,11 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
     // the walk: wave 0, LDS only.  Every lane follows the same path (the tests are wave-uniform); the
     // lanes only share the search for a node's children, which a ballot over the parent array gives in
     // index order (a child's index exceeds its parent's).
+    // Deterministic rule: what the rejections at the current node did is also kept in registers, lane i holding
+    // rejection i (the first 64; the workgroup's copy in LDS holds all), so that replaying them for the next child
+    // and, later, for the pieces of the final law costs register reads instead of one LDS round trip per step.
+    int rg_tok = -1;
+    double rg_inv_ps = 0.0, rg_p0 = 0.0;
     if (wave == 0) {
         const int par_lo = (lane < T) ? sh.parent[lane] : -2;
         const int par_hi = (lane + kWave < T) ? sh.parent[lane + kWave] : -2;
@@ -1157,15 +1184,21 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
                 if (kGreedy) {
                     acc = (x == sh.argmax[cur]);
                 } else if (kRule == TV_RULE_DETERMINISTIC) {
-                    const double p0 = unnorm_prob(sh.z_tok_p[c], sh.m_p[cur], it) * sh.inv_s_p[cur];
-                    double p, q;
-                    law_after<kRule>(x, p0, 0.0, sh.steps, nrej, &p, &q);
+                    const double p0 = sh.p0[c];
+                    double p = p0;
+                    for (int i = 0; i < nrej; ++i) {         // (law_step of the deterministic rule, step by step)
+                        const int tk = (i < kWave) ? lane_value(rg_tok, i) : sh.steps[i].tok;
+                        const double ips = (i < kWave) ? lane_value(rg_inv_ps, i) : sh.steps[i].inv_ps;
+                        p = (x == tk) ? 0.0 : ((ips > 0.0) ? p * ips : p);
+                    }
                     acc = ((double)sh.unif[c] < p);
                     if (!acc) {
                         const double ps = 1.0 - p;       // mass of p left once x is removed
-                        sh.steps[nrej] = ChainStep{x, 0.0, 0.0, (ps > 0.0) ? 1.0 / ps : 0.0};
+                        const double ips = (ps > 0.0) ? 1.0 / ps : 0.0;
+                        sh.steps[nrej] = ChainStep{x, 0.0, 0.0, ips};
                         sh.rej_child[nrej] = c;
                         sh.rej_p0[nrej] = p0;
+                        if (lane == nrej) { rg_tok = x; rg_inv_ps = ips; rg_p0 = p0; }
                     }
                 } else {
                     acc = (sh.abit[c] != 0);
@@ -1219,20 +1252,41 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
                                           [&](int s) { return share_value(parts[s]) * inv_z; });
         } else {
             // the target's own law with the rejected tokens taken out (deterministic rule), scaled up accordingly:
-            // per range of the statistics kernel, the range's share minus the rejected tokens that lie in it
+            // per range of the statistics kernel, the range's share minus the rejected tokens that lie in it.
+            // (mass_of runs in wave 0 only, whose lanes hold the rejections; more than 64 of them: from LDS)
+            const bool in_regs = (kRule == TV_RULE_DETERMINISTIC) && wave == 0 && n <= kWave;
             double scale = 1.0;
-            if (kRule == TV_RULE_DETERMINISTIC)
-                for (int i = 0; i < n; ++i)
-                    if (sh.steps[i].inv_ps > 0.0) scale *= sh.steps[i].inv_ps;
+            int rg_first = 1;                    // rejection `lane` is the first one of its token (a token proposed twice)
+            if (kRule == TV_RULE_DETERMINISTIC) {
+                if (in_regs) {
+                    for (int i = 0; i < n; ++i) {
+                        const double ips = lane_value(rg_inv_ps, i);
+                        if (ips > 0.0) scale *= ips;
+                        if (lane > i && rg_tok == lane_value(rg_tok, i)) rg_first = 0;
+                    }
+                } else {
+                    for (int i = 0; i < n; ++i)
+                        if (sh.steps[i].inv_ps > 0.0) scale *= sh.steps[i].inv_ps;
+                }
+            }
             tok = draw_from_pieces<kRule>(a, sh, b, cur, u, it, a.splits, a.split_len, [&](int s) {
                 double m = range_mass(a, sh, b, cur, s, it);
                 if (kRule == TV_RULE_DETERMINISTIC) {
                     const int lo = s * a.split_len, hi = lo + a.split_len;
-                    for (int i = 0; i < n; ++i) {
-                        const int x = sh.steps[i].tok;
-                        bool first = (x >= lo && x < hi);
-                        for (int k = 0; k < i; ++k) first = first && (sh.steps[k].tok != x);     // (a token proposed twice)
-                        if (first) m -= sh.rej_p0[i];
+                    if (in_regs) {
+                        for (int i = 0; i < n; ++i) {
+                            const int x = lane_value(rg_tok, i);
+                            const int first = lane_value(rg_first, i);
+                            const double p0 = lane_value(rg_p0, i);
+                            if (first && x >= lo && x < hi) m -= p0;
+                        }
+                    } else {
+                        for (int i = 0; i < n; ++i) {
+                            const int x = sh.steps[i].tok;
+                            bool first = (x >= lo && x < hi);
+                            for (int k = 0; k < i; ++k) first = first && (sh.steps[k].tok != x);     // (a token proposed twice)
+                            if (first) m -= sh.rej_p0[i];
+                        }
                     }
                     m = fmax(m, 0.0) * scale;
                 }
