@@ -149,87 +149,138 @@ __device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w 
 __device__ __forceinline__ float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
 
 // ---- 1. statistics -----------------------------------------------------------------------------------
-template <bool kGreedy>
-__global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(AcceptArgs a) {
+// The kernel-argument segment of accept_stats_kernel as the launch lays it out.
+struct StatsKernArgs {
+    const void* target;
+    const void* draft;
+    int64_t row_stride;
+    unsigned geometry;       // T | n_mat << 8 | logits_bf16 << 10
+    int V;
+    int split_len;
+    float temperature;
+    AcceptArgs a;
+};
+static_assert(offsetof(StatsKernArgs, a) == 40, "kernel-argument layout of accept_stats_kernel");
+
+// The rest of a kernel's argument block, read through a pointer the compiler cannot look through: none of these
+// loads moves above the call, i.e. above the requests that were issued from the leading arguments (which are in
+// registers when a wave starts; the block itself costs a memory round trip).
+template <typename KernArgs>
+__device__ __forceinline__ AcceptArgs argument_block_after_requests() {
+    typedef const KernArgs __attribute__((address_space(4)))* kernarg_ptr;
+    kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ka) : : "memory");
+    AcceptArgs a;
+    static_assert(sizeof(AcceptArgs) % 4 == 0, "copied word by word");
+    typedef const unsigned __attribute__((address_space(4)))* kernarg_words;
+    kernarg_words src = (kernarg_words)&ka->a;
+    unsigned* dst = reinterpret_cast<unsigned*>(&a);
+#pragma unroll
+    for (unsigned w = 0; w < sizeof(AcceptArgs) / 4; ++w) dst[w] = src[w];
+    return a;
+}
+
+template <bool kGreedy, bool kBf16>
+__global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(const void* target, const void* draft,
+                                                                    int64_t row_stride, unsigned geometry, int V,
+                                                                    int split_len, float temperature,
+                                                                    AcceptArgs /* read below */) {
+    const int T = (int)(geometry & 0xffu), n_mat = (int)((geometry >> 8) & 3u);
+    constexpr bool is_bf16 = kBf16;
     const int split = blockIdx.x;
-    const int mat = blockIdx.y / a.T;
-    const int row = blockIdx.y % a.T;
+    const int mat = blockIdx.y / T;
+    const int row = blockIdx.y % T;
     const int b = blockIdx.z;
+    const Row lrow{static_cast<const unsigned char*>(mat == 0 ? target : draft) +
+                       ((int64_t)b * T + row) * row_stride * (is_bf16 ? 2 : 4), is_bf16};
+    const int begin = split * split_len;
+    const int end = min(V, begin + split_len);
+    const float it = kGreedy ? 0.f : kLog2e / temperature;
+
+    // Vector part: 16-byte pieces (four fp32 or eight bf16 entries), a batch of them per lane requested before the
+    // first is used (a range of the usual size is one or two batches, so the workgroup pays few memory round
+    // trips).  The first batch goes out before anything else, from the leading arguments alone.
+    constexpr int kInFlight = 8;
+    const int per = is_bf16 ? 8 : 4;
+    const unsigned char* first_entry = static_cast<const unsigned char*>(lrow.p) + (int64_t)begin * (is_bf16 ? 2 : 4);
+    const int n_pieces = aligned16(first_entry) ? (end - begin) / per : 0;
+    const uint4* pieces = reinterpret_cast<const uint4*>(first_entry);
+    auto request = [&](int i0, uint4 (&raw)[kInFlight]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < kInFlight; ++k) {
+            const int i = i0 + k * kStatThreads;
+            raw[k] = pieces[i < n_pieces ? i : i0];           // (i0 < n_pieces: the caller checks)
+        }
+    };
+    uint4 raw[kInFlight];
+    const bool any_piece = (int)threadIdx.x < n_pieces;
+    if (any_piece) request(threadIdx.x, raw);
+
+    AcceptArgs a = argument_block_after_requests<StatsKernArgs>();
+    a.target = target;
+    a.draft = draft;
+    a.row_stride = row_stride;
+    a.T = T;
+    a.n_mat = n_mat;
+    a.logits_bf16 = is_bf16 ? 1 : 0;
+    a.V = V;
+    a.split_len = split_len;
+    a.temperature = temperature;
+
     // this node's share slots of the sibling-chain kernel: "not published yet"
-    if (a.n_mat == 2 && mat == 0 && blockIdx.x == 0) {
-        unsigned long long* parts = a.chain_parts + ((int64_t)b * a.T + row) * a.chain_slices;
+    if (n_mat == 2 && mat == 0 && blockIdx.x == 0) {
+        unsigned long long* parts = a.chain_parts + ((int64_t)b * T + row) * a.chain_slices;
         for (int i = threadIdx.x; i < a.chain_slices; i += kStatThreads) parts[i] = 3ull;
     }
-    const Row lrow = logits_row(a, mat == 0 ? a.target : a.draft, b, row);
-    const int begin = split * a.split_len;
-    const int end = min(a.V, begin + a.split_len);
-    const float it = kGreedy ? 0.f : kLog2e / a.temperature;
 
     // The logit of every child's token in this (its parent's) row, picked out by the workgroup whose range holds it:
     // the walk then finds all of them in one small array instead of gathering them from the rows.  Thread c looks
-    // at node c, before the streaming starts, so that these few dependent loads run under it; a token outside the
-    // row is left alone (the walk flags the sequence).
-    if (!kGreedy && threadIdx.x >= 1 && (int)threadIdx.x < a.T) {
+    // at node c while the first batch is on its way, so that these few dependent loads run under it; a token outside
+    // the row is left alone (the walk flags the sequence).
+    if (!kGreedy && threadIdx.x >= 1 && (int)threadIdx.x < T) {
         const int c = threadIdx.x;
-        const int tok = a.token[(int64_t)b * a.T + c];
-        if (a.parent[(int64_t)b * a.T + c] == row && tok >= begin && tok < end)
-            a.z_tok[((int64_t)b * a.n_mat + mat) * a.T + c] = lrow[tok];
+        const int tok = a.token[(int64_t)b * T + c];
+        if (a.parent[(int64_t)b * T + c] == row && tok >= begin && tok < end)
+            a.z_tok[((int64_t)b * n_mat + mat) * T + c] = lrow[tok];
     }
 
     Red r{-INFINITY, 0x7fffffff, 0.0};
-    int v = begin;
-    // Vector part: every lane requests a batch of 16-byte pieces before it uses the first (a range of the usual
-    // size is one or two batches, so the workgroup pays few memory round trips).
-    constexpr int kInFlight = 8;
-    if (!lrow.bf16) {
-        const float* base = static_cast<const float*>(lrow.p);
-        if (aligned16(base + begin)) {
-            const int n4 = (end - begin) / 4;
-            const float4* b4 = reinterpret_cast<const float4*>(base + begin);
-            for (int i0 = threadIdx.x; i0 < n4; i0 += kInFlight * kStatThreads) {
-                float4 x[kInFlight];
-                int v0[kInFlight];
-                bool live[kInFlight];
+    auto consume = [&](int i0, const uint4 (&w)[kInFlight]) __attribute__((always_inline)) {
+        if (!is_bf16) {
+            float4 x[kInFlight];
+            int v0[kInFlight];
+            bool live[kInFlight];
 #pragma unroll
-                for (int k = 0; k < kInFlight; ++k) {
-                    const int i = i0 + k * kStatThreads;
-                    live[k] = i < n4;
-                    v0[k] = begin + 4 * i;
-                    x[k] = b4[live[k] ? i : i0];
-                }
-                red_push_batch<kGreedy, kInFlight>(r, x, v0, live, it);
+            for (int k = 0; k < kInFlight; ++k) {
+                const int i = i0 + k * kStatThreads;
+                live[k] = i < n_pieces;
+                v0[k] = begin + 4 * i;
+                x[k] = make_float4(__uint_as_float(w[k].x), __uint_as_float(w[k].y), __uint_as_float(w[k].z),
+                                   __uint_as_float(w[k].w));
             }
-            v = begin + 4 * n4;
-        }
-    } else {
-        const unsigned short* base = static_cast<const unsigned short*>(lrow.p);
-        if (aligned16(base + begin)) {                                      // eight entries per 16-byte piece
-            const int n8 = (end - begin) / 8;
-            const uint4* b8 = reinterpret_cast<const uint4*>(base + begin);
-            for (int i0 = threadIdx.x; i0 < n8; i0 += kInFlight * kStatThreads) {
-                uint4 y[kInFlight];
-                float4 x[2 * kInFlight];
-                int v0[2 * kInFlight];
-                bool live[2 * kInFlight];
+            red_push_batch<kGreedy, kInFlight>(r, x, v0, live, it);
+        } else {
+            float4 x[2 * kInFlight];
+            int v0[2 * kInFlight];
+            bool live[2 * kInFlight];
 #pragma unroll
-                for (int k = 0; k < kInFlight; ++k) {
-                    const int i = i0 + k * kStatThreads;
-                    live[2 * k] = live[2 * k + 1] = i < n8;
-                    v0[2 * k] = begin + 8 * i;
-                    v0[2 * k + 1] = begin + 8 * i + 4;
-                    y[k] = b8[i < n8 ? i : i0];
-                }
-#pragma unroll
-                for (int k = 0; k < kInFlight; ++k) {
-                    x[2 * k] = make_float4(bf16_lo(y[k].x), bf16_hi(y[k].x), bf16_lo(y[k].y), bf16_hi(y[k].y));
-                    x[2 * k + 1] = make_float4(bf16_lo(y[k].z), bf16_hi(y[k].z), bf16_lo(y[k].w), bf16_hi(y[k].w));
-                }
-                red_push_batch<kGreedy, 2 * kInFlight>(r, x, v0, live, it);
+            for (int k = 0; k < kInFlight; ++k) {
+                const int i = i0 + k * kStatThreads;
+                live[2 * k] = live[2 * k + 1] = i < n_pieces;
+                v0[2 * k] = begin + 8 * i;
+                v0[2 * k + 1] = begin + 8 * i + 4;
+                x[2 * k] = make_float4(bf16_lo(w[k].x), bf16_hi(w[k].x), bf16_lo(w[k].y), bf16_hi(w[k].y));
+                x[2 * k + 1] = make_float4(bf16_lo(w[k].z), bf16_hi(w[k].z), bf16_lo(w[k].w), bf16_hi(w[k].w));
             }
-            v = begin + 8 * n8;
+            red_push_batch<kGreedy, 2 * kInFlight>(r, x, v0, live, it);
         }
+    };
+    if (any_piece) consume(threadIdx.x, raw);
+    for (int i0 = threadIdx.x + kInFlight * kStatThreads; i0 < n_pieces; i0 += kInFlight * kStatThreads) {
+        request(i0, raw);
+        consume(i0, raw);
     }
-    for (int i = v + threadIdx.x; i < end; i += kStatThreads) red_push<kGreedy>(r, lrow[i], i, it);
+    for (int i = begin + per * n_pieces + threadIdx.x; i < end; i += kStatThreads) red_push<kGreedy>(r, lrow[i], i, it);
 
     // wave reduction: the maximum (lowest index on ties) first, then one rescale per lane and a plain sum
     float wm = r.m;
@@ -1033,19 +1084,7 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
             r_zp = z_tok[((int64_t)b * lead.n_mat) * T + my_node];               // (entry 0, the root's, is never read)
         }
     }
-    // the argument block, through a pointer the compiler cannot look through: none of its loads moves above this line
-    typedef const WalkKernArgs __attribute__((address_space(4)))* kernarg_ptr;
-    kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
-    asm volatile("" : "+s"(ka) : : "memory");
-    AcceptArgs a;
-    {
-        static_assert(sizeof(AcceptArgs) % 4 == 0, "copied word by word");
-        typedef const unsigned __attribute__((address_space(4)))* kernarg_words;
-        kernarg_words src = (kernarg_words)&ka->a;
-        unsigned* dst = reinterpret_cast<unsigned*>(&a);
-#pragma unroll
-        for (unsigned w = 0; w < sizeof(AcceptArgs) / 4; ++w) dst[w] = src[w];
-    }
+    AcceptArgs a = argument_block_after_requests<WalkKernArgs>();
     a.stats = const_cast<RowStat*>(stats);
     a.z_tok = const_cast<float*>(z_tok);
     a.parent = parent;
@@ -1371,8 +1410,14 @@ static int chain_resident_workgroups(int rule, size_t dyn_smem) {
 
 hipError_t launch_accept(const AcceptArgs& a, hipStream_t s) {
     const dim3 gs(a.splits, a.T * a.n_mat, a.B);
-    if (a.rule == TV_RULE_GREEDY) accept_stats_kernel<true><<<gs, kStatThreads, 0, s>>>(a);
-    else accept_stats_kernel<false><<<gs, kStatThreads, 0, s>>>(a);
+    static_assert(kMaxRows <= 0xff, "packed geometry argument of the statistics kernel");
+    const unsigned stat_geometry = (unsigned)a.T | ((unsigned)a.n_mat << 8) | ((a.logits_bf16 ? 1u : 0u) << 10);
+#define TV_LAUNCH_STATS(G, H) \
+    accept_stats_kernel<G, H><<<gs, kStatThreads, 0, s>>>(a.target, a.draft, a.row_stride, stat_geometry, a.V, a.split_len, \
+                                                          a.temperature, a)
+    if (a.rule == TV_RULE_GREEDY) { if (a.logits_bf16) TV_LAUNCH_STATS(true, true); else TV_LAUNCH_STATS(true, false); }
+    else { if (a.logits_bf16) TV_LAUNCH_STATS(false, true); else TV_LAUNCH_STATS(false, false); }
+#undef TV_LAUNCH_STATS
     if (a.rule == TV_RULE_DRAFT_WOR || a.rule == TV_RULE_DRAFT_WR) {
         // whole groups only; as many as the device holds at once (fewer when that is unknown: one group)
         const size_t dyn = (size_t)a.chain_slices * sizeof(unsigned long long);
