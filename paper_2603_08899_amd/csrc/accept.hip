@@ -162,24 +162,6 @@ struct StatsKernArgs {
 };
 static_assert(offsetof(StatsKernArgs, a) == 40, "kernel-argument layout of accept_stats_kernel");
 
-// The rest of a kernel's argument block, read through a pointer the compiler cannot look through: none of these
-// loads moves above the call, i.e. above the requests that were issued from the leading arguments (which are in
-// registers when a wave starts; the block itself costs a memory round trip).
-template <typename KernArgs>
-__device__ __forceinline__ AcceptArgs argument_block_after_requests() {
-    typedef const KernArgs __attribute__((address_space(4)))* kernarg_ptr;
-    kernarg_ptr ka = (kernarg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
-    asm volatile("" : "+s"(ka) : : "memory");
-    AcceptArgs a;
-    static_assert(sizeof(AcceptArgs) % 4 == 0, "copied word by word");
-    typedef const unsigned __attribute__((address_space(4)))* kernarg_words;
-    kernarg_words src = (kernarg_words)&ka->a;
-    unsigned* dst = reinterpret_cast<unsigned*>(&a);
-#pragma unroll
-    for (unsigned w = 0; w < sizeof(AcceptArgs) / 4; ++w) dst[w] = src[w];
-    return a;
-}
-
 template <bool kGreedy, bool kBf16>
 __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(const void* target, const void* draft,
                                                                     int64_t row_stride, unsigned geometry, int V,
@@ -216,7 +198,7 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(const void* 
     const bool any_piece = (int)threadIdx.x < n_pieces;
     if (any_piece) request(threadIdx.x, raw);
 
-    AcceptArgs a = argument_block_after_requests<StatsKernArgs>();
+    AcceptArgs a = kernarg_block_after_requests<AcceptArgs>(offsetof(StatsKernArgs, a));
     a.target = target;
     a.draft = draft;
     a.row_stride = row_stride;
@@ -1084,7 +1066,7 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
             r_zp = z_tok[((int64_t)b * lead.n_mat) * T + my_node];               // (entry 0, the root's, is never read)
         }
     }
-    AcceptArgs a = argument_block_after_requests<WalkKernArgs>();
+    AcceptArgs a = kernarg_block_after_requests<AcceptArgs>(offsetof(WalkKernArgs, a));
     a.stats = const_cast<RowStat*>(stats);
     a.z_tok = const_cast<float*>(z_tok);
     a.parent = parent;

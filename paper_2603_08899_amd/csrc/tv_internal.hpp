@@ -26,6 +26,26 @@ struct AttnPlan {
 
 int plan_attention(const tv_attn_desc& d, AttnPlan* plan);
 
+// A kernel's by-value argument struct, read through a pointer the compiler cannot look through: none of its loads
+// moves above the call, i.e. above the requests a kernel has issued from its leading scalar arguments (those are in
+// registers when a wave starts - kernel-argument preload, see the build flags - while the rest of the argument
+// segment costs a memory round trip, which then runs under the requests' own instead of in front of them).
+// `offset`: byte offset of the struct in the kernel-argument segment (arguments in order, natural alignment).
+template <typename Block>
+__device__ __forceinline__ Block kernarg_block_after_requests(unsigned offset) {
+    typedef const unsigned char __attribute__((address_space(4)))* kernarg_bytes;
+    typedef const unsigned __attribute__((address_space(4)))* kernarg_words;
+    static_assert(sizeof(Block) % 4 == 0 && alignof(Block) <= 8, "copied word by word");
+    kernarg_bytes ka = (kernarg_bytes)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(ka) : : "memory");
+    kernarg_words src = (kernarg_words)(ka + offset);
+    Block blk;
+    unsigned* dst = reinterpret_cast<unsigned*>(&blk);
+#pragma unroll
+    for (unsigned w = 0; w < sizeof(Block) / 4; ++w) dst[w] = src[w];
+    return blk;
+}
+
 struct AttnArgs {
     const void* q;
     const void* k;
