@@ -149,6 +149,29 @@ __device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w 
 __device__ __forceinline__ float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
 
 // ---- 1. statistics -----------------------------------------------------------------------------------
+// the pointers of an argument block that was read through kernarg_block_after_requests, as global pointers again
+__device__ __forceinline__ void global_pointers(AcceptArgs& a) {
+    a.target = global_pointer(a.target);
+    a.draft = global_pointer(a.draft);
+    a.token = global_pointer(a.token);
+    a.parent = global_pointer(a.parent);
+    a.uniforms = global_pointer(a.uniforms);
+    a.con_anchor = global_pointer(a.con_anchor);
+    a.path = global_pointer(a.path);
+    a.n_accepted = global_pointer(a.n_accepted);
+    a.final_token = global_pointer(a.final_token);
+    a.final_kind = global_pointer(a.final_kind);
+    a.last_node = global_pointer(a.last_node);
+    a.selected_con = global_pointer(a.selected_con);
+    a.status = global_pointer(a.status);
+    a.stats = global_pointer(a.stats);
+    a.z_tok = global_pointer(a.z_tok);
+    a.chain_z = global_pointer(a.chain_z);
+    a.accept_bit = global_pointer(a.accept_bit);
+    a.sampled = global_pointer(a.sampled);
+    a.chain_parts = global_pointer(a.chain_parts);
+}
+
 // The kernel-argument segment of accept_stats_kernel as the launch lays it out.
 struct StatsKernArgs {
     const void* target;
@@ -186,12 +209,16 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(const void* 
     const int per = is_bf16 ? 8 : 4;
     const unsigned char* first_entry = static_cast<const unsigned char*>(lrow.p) + (int64_t)begin * (is_bf16 ? 2 : 4);
     const int n_pieces = aligned16(first_entry) ? (end - begin) / per : 0;
-    const uint4* pieces = reinterpret_cast<const uint4*>(first_entry);
+    // (a pointer typed as global memory: the streaming loads are global loads, not flat ones)
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+    typedef const u32x4 __attribute__((address_space(1)))* global_pieces;
+    const global_pieces pieces = (global_pieces)(uintptr_t)first_entry;
     auto request = [&](int i0, uint4 (&raw)[kInFlight]) __attribute__((always_inline)) {
 #pragma unroll
         for (int k = 0; k < kInFlight; ++k) {
             const int i = i0 + k * kStatThreads;
-            raw[k] = pieces[i < n_pieces ? i : i0];           // (i0 < n_pieces: the caller checks)
+            const u32x4 w = pieces[i < n_pieces ? i : i0];    // (i0 < n_pieces: the caller checks)
+            raw[k] = make_uint4(w[0], w[1], w[2], w[3]);
         }
     };
     uint4 raw[kInFlight];
@@ -199,6 +226,7 @@ __global__ __launch_bounds__(kStatThreads) void accept_stats_kernel(const void* 
     if (any_piece) request(threadIdx.x, raw);
 
     AcceptArgs a = kernarg_block_after_requests<AcceptArgs>(offsetof(StatsKernArgs, a));
+    global_pointers(a);
     a.target = target;
     a.draft = draft;
     a.row_stride = row_stride;
@@ -1067,6 +1095,7 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
         }
     }
     AcceptArgs a = kernarg_block_after_requests<AcceptArgs>(offsetof(WalkKernArgs, a));
+    global_pointers(a);
     a.stats = const_cast<RowStat*>(stats);
     a.z_tok = const_cast<float*>(z_tok);
     a.parent = parent;
@@ -1206,13 +1235,15 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
                     acc = (x == sh.argmax[cur]);
                 } else if (kRule == TV_RULE_DETERMINISTIC) {
                     const double p0 = sh.p0[c];
+                    const float uc = sh.unif[c];             // (requested with the other two, not behind the replay)
+                    asm volatile("" : : "v"(uc));
                     double p = p0;
                     for (int i = 0; i < nrej; ++i) {         // (law_step of the deterministic rule, step by step)
                         const int tk = (i < kWave) ? lane_value(rg_tok, i) : sh.steps[i].tok;
                         const double ips = (i < kWave) ? lane_value(rg_inv_ps, i) : sh.steps[i].inv_ps;
                         p = (x == tk) ? 0.0 : ((ips > 0.0) ? p * ips : p);
                     }
-                    acc = ((double)sh.unif[c] < p);
+                    acc = ((double)uc < p);
                     if (!acc) {
                         const double ps = 1.0 - p;       // mass of p left once x is removed
                         const double ips = (ps > 0.0) ? 1.0 / ps : 0.0;

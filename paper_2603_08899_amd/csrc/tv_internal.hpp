@@ -31,6 +31,13 @@ int plan_attention(const tv_attn_desc& d, AttnPlan* plan);
 // registers when a wave starts - kernel-argument preload, see the build flags - while the rest of the argument
 // segment costs a memory round trip, which then runs under the requests' own instead of in front of them).
 // `offset`: byte offset of the struct in the kernel-argument segment (arguments in order, natural alignment).
+// A pointer that came out of such a struct is a plain (generic) pointer to the compiler; this says again that it
+// points to global memory, so that accesses through it are global loads and stores, not flat ones.
+template <typename T>
+__device__ __forceinline__ T* global_pointer(T* p) {
+    typedef T __attribute__((address_space(1)))* global_ptr;
+    return (T*)(global_ptr)(uintptr_t)p;          // (through the address value: a cast between pointers alone is dropped)
+}
 template <typename Block>
 __device__ __forceinline__ Block kernarg_block_after_requests(unsigned offset) {
     typedef const unsigned char __attribute__((address_space(4)))* kernarg_bytes;
