@@ -812,6 +812,7 @@ struct WalkShared {
     double rej_p0[kMaxRows];      // ... and the target's own probability of its token
     double p0[kMaxRows];          // deterministic rule: probability of node c's token under its parent's own law
     int con_anchor[kMaxRows];     // node of each contemplate row (the first kMaxRows of them)
+    int verdict[kMaxRows];        // TV_STATUS_* bits of each node's own checks
     double red[kDrawWaves];
     double wave_tot[kDrawWaves];
     int wave_last[kDrawWaves];
@@ -1133,6 +1134,12 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
         }
     }
     if (has_node) {
+        // this node's checks, on the values just fetched: the verdicts are in LDS with everything else, so that the
+        // one barrier below is all the checks cost (acceptance trees have exactly one root, node 0)
+        int verdict = 0;
+        if (r_parent < -1 || r_parent >= my_node || (my_node > 0 && r_parent < 0)) verdict |= TV_STATUS_BAD_PARENT;
+        if (r_token < 0 || r_token >= V) verdict |= TV_STATUS_BAD_TOKEN;
+        sh.verdict[my_node] = verdict;
         sh.parent[my_node] = r_parent;
         sh.token[my_node] = r_token;
         if (!kGreedy) {
@@ -1185,15 +1192,15 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
         const int pc = sh.parent[tid];
         if (pc >= 0 && pc < tid) sh.p0[tid] = unnorm_prob(sh.z_tok_p[tid], sh.m_p[pc], it) * sh.inv_s_p[pc];
     }
-    int bad = validate_tree(sh.parent, nullptr, T, &sh.flag);
+    // every wave gathers the nodes' verdicts for itself (two LDS reads per lane, one vote per status bit)
+    int bad = 0;
     {
-        int tok_bad = 0;
-        for (int i = tid; i < T; i += kDrawThreads)
-            if (sh.token[i] < 0 || sh.token[i] >= V) tok_bad = 1;
-        if (tok_bad) atomicOr(&sh.flag, TV_STATUS_BAD_TOKEN);
-        __syncthreads();
-        bad = sh.flag;
+        static_assert(kMaxRows <= 2 * kWave, "two nodes per lane");
+        const int v = ((lane < T) ? sh.verdict[lane] : 0) | ((lane + kWave < T) ? sh.verdict[lane + kWave] : 0);
+        if (__ballot(v & TV_STATUS_BAD_PARENT)) bad |= TV_STATUS_BAD_PARENT;
+        if (__ballot(v & TV_STATUS_BAD_TOKEN)) bad |= TV_STATUS_BAD_TOKEN;
     }
+    __syncthreads();             // (the probabilities formed above are visible to the walk)
     int32_t* path = a.path + (int64_t)b * T;
     if (bad) {
         for (int i = tid; i < T; i += kDrawThreads) path[i] = -1;
