@@ -70,6 +70,23 @@ def test_uncorrelated_draft_and_wide_star(rule):
     assert (got["n_accepted"] == 0).any()
 
 
+def test_deterministic_rule_more_than_64_rejected_siblings_and_repeated_tokens():
+    """A root with 100 children (and a node with 20 further down): the deterministic rule replays the rejections at a
+    node from one wave's registers up to 64 of them and from LDS beyond; several siblings propose the same token,
+    which is taken out of the law once.  Uncorrelated proposals: most walks reject everything at the root."""
+    star = np.array([-1] + [0] * 100 + [1] * 20 + [3, 3], dtype=np.int32)
+    inp = _batch(29, B=48, T=len(star), V=2048, rule=RULES["det"], temp=1.0, corr=0.0, tree=star)
+    inp.token[:, 10] = inp.token[:, 5]            # repeated proposals among the first 64 ...
+    inp.token[:, 90] = inp.token[:, 5]            # ... across the boundary ...
+    inp.token[:, 95] = inp.token[:, 80]           # ... and beyond it
+    got = _run_and_compare(inp)
+    assert (got["n_accepted"] == 0).sum() >= 8 and (got["n_accepted"] >= 1).any()
+    # the same tree with likelier children: deeper walks, rejections at the 20-child node as well
+    inp2 = _batch(30, B=48, T=len(star), V=2048, rule=RULES["det"], temp=1.0, corr=0.0, tree=star, boost=5.0)
+    inp2.token[:, 110] = inp2.token[:, 105]
+    _run_and_compare(inp2)
+
+
 def test_root_only_and_chain_trees():
     for rule in ("greedy", "det", "wor"):
         temp = 0.0 if rule == "greedy" else 1.0
