@@ -22,17 +22,59 @@ constexpr int kCommitChunk = kCommitThreads * kCommitHeld;      // pieces moved 
 // overlap (a destination may be the source of an earlier entry of the path), so a chunk of rows is read
 // completely before any of it is written.  Later sources lie strictly behind every earlier destination, so
 // chunks can follow each other without further ordering.
-__global__ __launch_bounds__(kCommitThreads) void commit_kernel(CommitArgs a) {
+// What the first loads hang on comes as leading scalar arguments (in registers when a wave starts); the argument
+// struct is read behind them.  The per-sequence scalars and the whole path are requested at once - the path
+// before its length is known - so that the kernel pays one memory round trip for them, one for the row map (if
+// there is one) and one for the rows.
+struct CommitKernArgs {
+    const int32_t* n_accepted;
+    const int32_t* path;
+    const int32_t* prefix_len;
+    const int64_t* kv_offset;
+    const int32_t* selected_con;
+    int T;
+    CommitArgs a;
+};
+static_assert(offsetof(CommitKernArgs, a) == 48, "kernel-argument layout of commit_kernel");
+
+__device__ __forceinline__ void global_pointers(CommitArgs& a) {
+    a.k = global_pointer(a.k);
+    a.v = global_pointer(a.v);
+    a.node_row = global_pointer(a.node_row);
+    a.hidden = global_pointer(a.hidden);
+    a.con_row = global_pointer(a.con_row);
+    a.f_out = global_pointer(a.f_out);
+    a.new_prefix_len = global_pointer(a.new_prefix_len);
+    a.status = global_pointer(a.status);
+}
+
+__global__ __launch_bounds__(kCommitThreads) void commit_kernel(const int32_t* n_accepted, const int32_t* path_in,
+                                                                const int32_t* prefix_len, const int64_t* kv_offset,
+                                                                const int32_t* selected_con, int T,
+                                                                CommitArgs /* read below */) {
     const int l = blockIdx.x, b = blockIdx.y, which = blockIdx.z;
-    const int tid = threadIdx.x, T = a.T;
+    const int tid = threadIdx.x;
     __shared__ int s_src[kMaxRows];
     __shared__ int s_ok;
-    const int n = a.n_accepted[b];
+    const int n = n_accepted[b];
+    const int P = prefix_len[b];
+    const int64_t kv_first = kv_offset[b];
+    const bool gathers_f = (l == 0 && which == 1);
+    const int sel = (gathers_f && selected_con) ? selected_con[b] : -1;      // (null: nothing to gather)
+    int node = -1, prev = -1;
+    if (tid < T) {                       // (the path array has T entries whatever its length)
+        node = path_in[(int64_t)b * T + tid];
+        prev = (tid > 0) ? path_in[(int64_t)b * T + tid - 1] : -1;
+    }
+    CommitArgs a = kernarg_block_after_requests<CommitArgs>(offsetof(CommitKernArgs, a));
+    global_pointers(a);
+    // (the workgroup that gathers f fetches every contemplate row's index now, not only the selected one's once
+    //  that is known: one round trip less in front of the copy)
+    __shared__ int s_con[kMaxRows];
+    if (gathers_f && a.hidden && tid < a.C && tid < kMaxRows) s_con[tid] = a.con_row[(int64_t)b * a.C + tid];
     if (tid == 0) s_ok = 1;
     __syncthreads();
     if (n >= 0 && n < T && tid <= n) {
-        const int node = a.path[(int64_t)b * T + tid];
-        const int prev = (tid > 0) ? a.path[(int64_t)b * T + tid - 1] : -1;
         bool bad = node < 0 || node >= T || node <= prev || (tid == 0 && node != 0);
         int row = -1;
         if (!bad) {
@@ -48,15 +90,14 @@ __global__ __launch_bounds__(kCommitThreads) void commit_kernel(CommitArgs a) {
     if (n >= 0 && n < T && tid >= 1 && tid <= n && s_src[tid] <= s_src[tid - 1]) s_ok = 0;
     __syncthreads();
     const bool ok = n >= 0 && n < T && s_ok != 0;
-    const int P = a.prefix_len[b];
     if (l == 0 && which == 0 && tid == 0) {
         a.status[b] = (n >= 0 && !ok) ? TV_STATUS_BAD_PATH : TV_STATUS_OK;
         a.new_prefix_len[b] = P + (ok ? n + 1 : 0);
     }
-    if (l == 0 && which == 1 && a.hidden) {
+    if (gathers_f && a.hidden) {
         // the future prediction that belongs to the last accepted token
-        const int c = a.selected_con[b];
-        const int row = (c >= 0 && c < a.C) ? a.con_row[(int64_t)b * a.C + c] : -1;
+        const int c = sel;
+        const int row = (c >= 0 && c < a.C) ? (c < kMaxRows ? s_con[c] : a.con_row[(int64_t)b * a.C + c]) : -1;
         const int pieces = a.d_model * a.elem / 16;
         uint4* dst = reinterpret_cast<uint4*>(static_cast<unsigned char*>(a.f_out) + (int64_t)b * a.d_model * a.elem);
         const uint4* src = (row >= 0 && row < a.M)
@@ -68,7 +109,7 @@ __global__ __launch_bounds__(kCommitThreads) void commit_kernel(CommitArgs a) {
     if (!ok) return;
 
     unsigned char* pool = static_cast<unsigned char*>(which ? a.v : a.k) +
-                          ((int64_t)l * a.layer_stride + (a.kv_offset[b] + P) * a.tok_stride) * a.elem;
+                          ((int64_t)l * a.layer_stride + (kv_first + P) * a.tok_stride) * a.elem;
     const int segs = a.D * a.elem / 16;                 // 16-byte pieces of one head's row
     const int per_row = a.Hkv * segs;
     auto piece = [&](int row, int rem) -> uint4* {
@@ -224,7 +265,8 @@ __global__ __launch_bounds__(kEmbedThreads) void embed_mix_kernel(EmbedArgs a) {
 }  // namespace
 
 hipError_t launch_commit(const CommitArgs& a, hipStream_t s) {
-    commit_kernel<<<dim3(a.n_layers, a.B, 2), kCommitThreads, 0, s>>>(a);
+    commit_kernel<<<dim3(a.n_layers, a.B, 2), kCommitThreads, 0, s>>>(a.n_accepted, a.path, a.prefix_len, a.kv_offset,
+                                                                    a.selected_con, a.T, a);
     return hipGetLastError();
 }
 
