@@ -295,7 +295,7 @@ def test_bf16_logits_full_vocabulary(index, mode, boost):
 
 
 # ---- seeded random draws over everything at once ----------------------------------------------------------------
-@pytest.mark.parametrize("seed", range(20))
+@pytest.mark.parametrize("seed", range(48))
 def test_random_configurations(seed):
     """Rule, temperature, batch size, tree size and shape, vocabulary size (any residue mod 8, below and above one
     4096-entry range), contemplate rows, padded logit rows and the logits' type, all drawn together."""

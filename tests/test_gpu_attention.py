@@ -389,7 +389,7 @@ def test_bf16_relabelling_rows_permutes_the_output(wg, splits):
     assert np.abs(lse2[0] - lse1[0][:, perm]).max() <= 1e-4
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(48))
 def test_bf16_random_configurations(seed):
     """Seeded random draws over everything the launch depends on at once: batch size, head grouping, tree size
     and layout, prefix lengths (some empty, some far below the bound), soft-prompt slots, a loose max_prefix_len,
@@ -421,7 +421,7 @@ def test_bf16_random_configurations(seed):
     _check(inp, out, lse, st)
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(24))
 def test_fp32_random_configurations(seed):
     rng = np.random.default_rng(9500 + seed)
     B = int(rng.choice([1, 2, 5]))

@@ -215,7 +215,7 @@ def test_embed_llama8b_widths():
     _run_embed("bf16", 8, 4096, 4096, 64, 4, seed=61)
 
 
-@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("seed", range(24))
 def test_commit_random_configurations(seed):
     """Everything tree_commit's launch depends on drawn together: type, layers, batch, tree size and row layout,
     head count and width, prefix lengths (some zero), pool padding or a head-major pool, flagged sequences."""
@@ -239,7 +239,7 @@ def test_commit_random_configurations(seed):
     _run_commit(dtype, L, B, T, M, Hkv, D, plen, path, n_acc, node_row, pad_tokens=pad, head_major=head_major, seed=seed)
 
 
-@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("seed", range(24))
 def test_embed_random_configurations(seed):
     rng = np.random.default_rng(5500 + seed)
     dtype = str(rng.choice(["f32", "bf16"]))
