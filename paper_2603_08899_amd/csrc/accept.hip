@@ -817,7 +817,7 @@ struct WalkShared {
     double wave_tot[kDrawWaves];
     int wave_last[kDrawWaves];
     double base;                  // mass of the final law in the pieces before the chosen one
-    int flag, cur, n_steps, rejected_any, len, tok_out;
+    int flag, cur, n_steps, rejected_any, len;
     int piece;
     int ranges_kept;              // the target rows' reduced ranges are in `ranges` (T * splits <= kKeptRanges)
     uint4 ranges[kKeptRanges];    // [node][range], as the statistics kernel wrote them
@@ -863,17 +863,15 @@ __device__ __forceinline__ double run_probs(const WalkShared& sh, const float (&
     return run;
 }
 
-// The first v at which the running sum of the law at `node` (after sh.n_steps rejections) exceeds u.  The law's
-// mass in each of n_pieces consecutive pieces of piece_len entries comes from mass_of(piece) - no pass over the
-// vocabulary - so only the piece that holds the crossing is read, by this one workgroup.  Every thread calls
-// this and gets the token (-1: the law has no mass at all).
-template <int kRule, typename MassFn>
-__device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared& sh, int b, int node, double u, float it,
-                                                int n_pieces, int piece_len, MassFn mass_of) {
-    constexpr bool kDraft = (kRule == TV_RULE_DRAFT_WOR || kRule == TV_RULE_DRAFT_WR);
-    const int V = a.V;
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    if (wave == 0) {
+// The first v at which the running sum of the law at `node` (after sh.n_steps rejections) exceeds u, in two
+// steps.  The law's mass in each of n_pieces consecutive pieces of piece_len entries comes from mass_of(piece) - no
+// pass over the vocabulary - so only the piece that holds the crossing is read, by this one workgroup.
+// Step 1, choose_piece: the 64 lanes of ONE wave find that piece and leave it (and the mass in front of it) in sh.
+// A workgroup barrier must follow before step 2.
+template <typename MassFn>
+__device__ __forceinline__ void choose_piece(WalkShared& sh, double u, int n_pieces, MassFn mass_of) {
+    const int lane = threadIdx.x & (kWave - 1);
+    {
         // prefix sum over the pieces in vocabulary order (a lane holds kPer consecutive ones), first piece at which
         // the running sum exceeds u; if rounding leaves the total at or below u, the last piece that carries mass
         constexpr int kPer = kMaxPieces / kWave;
@@ -910,12 +908,23 @@ __device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared&
         if (lane == 0) {
             sh.piece = piece;
             sh.base = base;
-            sh.tok_out = -1;
         }
     }
-    __syncthreads();
+}
+
+// Step 2, draw_in_piece: every thread of the workgroup calls this (after the barrier that follows choose_piece); the
+// token (-1: the law has no mass at all) is written to *out_tok by exactly one thread.
+template <int kRule>
+__device__ __forceinline__ void draw_in_piece(const AcceptArgs& a, WalkShared& sh, int b, int node, double u, float it,
+                                              int piece_len, int32_t* out_tok) {
+    constexpr bool kDraft = (kRule == TV_RULE_DRAFT_WOR || kRule == TV_RULE_DRAFT_WR);
+    const int V = a.V;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int piece = sh.piece;
-    if (piece < 0) return -1;
+    if (piece < 0) {
+        if (tid == 0) *out_tok = -1;
+        return;
+    }
 
     // the chosen piece, a contiguous run of quads per lane in vocabulary order
     const Row prow = logits_row(a, a.target, b, node);
@@ -965,7 +974,8 @@ __device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared&
         int piece_last = (lane < kDrawWaves) ? sh.wave_last[lane] : -1;
 #pragma unroll
         for (int o = 1; o < kDrawWaves; o <<= 1) piece_last = max(piece_last, __shfl_xor(piece_last, o, kWave));
-        return lane_value(piece_last, 0);
+        if (tid == 0) *out_tok = lane_value(piece_last, 0);
+        return;
     }
     const int w_star = __ffsll((long long)w_over) - 1;
     const double before = sh.base + lane_value(w_inc - w_tot, w_star);
@@ -983,11 +993,9 @@ __device__ __forceinline__ int draw_from_pieces(const AcceptArgs& a, WalkShared&
                 if (pv[e] > 0.0) lst = v0 + e;
                 if (fnd < 0 && run > u) fnd = v0 + e;
             }
-            sh.tok_out = (fnd >= 0) ? fnd : lst;
+            *out_tok = (fnd >= 0) ? fnd : lst;
         }
     }
-    __syncthreads();
-    return sh.tok_out;
 }
 
 // mass of range `s` of the target row at `node`, as a share of the row (statistics kernel's ranges)
@@ -1022,9 +1030,9 @@ __global__ __launch_bounds__(kDrawThreads) void accept_sample_kernel(AcceptArgs 
     }
     __syncthreads();
     const double u = (double)a.uniforms[(int64_t)b * 2 * a.T + a.T + i];
-    const int tok = draw_from_pieces<TV_RULE_SAMPLE_MATCH>(a, sh, b, i, u, it, a.splits, a.split_len,
-                                                           [&](int s) { return range_mass(a, sh, b, i, s, it); });
-    if (threadIdx.x == 0) a.sampled[(int64_t)b * a.T + i] = tok;
+    if (threadIdx.x < kWave) choose_piece(sh, u, a.splits, [&](int s) { return range_mass(a, sh, b, i, s, it); });
+    __syncthreads();
+    draw_in_piece<TV_RULE_SAMPLE_MATCH>(a, sh, b, i, u, it, a.split_len, a.sampled + (int64_t)b * a.T + i);
 }
 
 // ---- 3. walk + final draw ---------------------------------------------------------------------------------
@@ -1186,11 +1194,17 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
         }
     }
     __syncthreads();
-    // the target's own probability of every node's token at its parent, all nodes at once: the walk, one wave
-    // stepping from child to child, then only reads it (visible after the barriers of the checks below)
-    if (kRule == TV_RULE_DETERMINISTIC && tid >= 1 && tid < T) {
-        const int pc = sh.parent[tid];
-        if (pc >= 0 && pc < tid) sh.p0[tid] = unnorm_prob(sh.z_tok_p[tid], sh.m_p[pc], it) * sh.inv_s_p[pc];
+    // the target's own probability of every node's token at its parent, all nodes at once (two per lane): by the
+    // wave that walks, which then only reads them back - no barrier in between
+    if (kRule == TV_RULE_DETERMINISTIC && wave == 0) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const int c = lane + k * kWave;
+            if (c >= 1 && c < T) {
+                const int pc = sh.parent[c];
+                if (pc >= 0 && pc < c) sh.p0[c] = unnorm_prob(sh.z_tok_p[c], sh.m_p[pc], it) * sh.inv_s_p[pc];
+            }
+        }
     }
     // every wave gathers the nodes' verdicts for itself (two LDS reads per lane, one vote per status bit)
     int bad = 0;
@@ -1200,7 +1214,6 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
         if (__ballot(v & TV_STATUS_BAD_PARENT)) bad |= TV_STATUS_BAD_PARENT;
         if (__ballot(v & TV_STATUS_BAD_TOKEN)) bad |= TV_STATUS_BAD_TOKEN;
     }
-    __syncthreads();             // (the probabilities formed above are visible to the walk)
     int32_t* path = a.path + (int64_t)b * T;
     if (bad) {
         for (int i = tid; i < T; i += kDrawThreads) path[i] = -1;
@@ -1286,78 +1299,87 @@ __global__ __launch_bounds__(kDrawThreads) void accept_walk_kernel(const RowStat
         sh.len = len;
         sh.n_steps = nrej;
         sh.rejected_any = (nrej > 0);
+        if (!kGreedy) {
+            // ---- inverse CDF at the stop node, first step: the piece of the vocabulary that holds the crossing, found
+            //      by this wave right behind its walk (the other waves are still at the barrier below)
+            const double u = (double)sh.unif[T + cur];
+            const int n = nrej;
+            // the last rejection that changed the target's law (draft rules: one whose corrected law had mass)
+            int eff = -1;
+            if (kDraft)
+                for (int i = 0; i < n; ++i)
+                    if (sh.steps[i].inv_z > 0.0) eff = i;
+            if (kDraft && eff >= 0) {
+                // the corrected law after that rejection: its mass per slice of the sibling-chain kernel is that
+                // kernel's share of the normaliser, over the normaliser
+                const unsigned long long* parts = a.chain_parts + ((int64_t)b * T + sh.rej_child[eff]) * a.chain_slices;
+                const double inv_z = sh.steps[eff].inv_z;
+                choose_piece(sh, u, a.chain_slices, [&](int s) { return share_value(parts[s]) * inv_z; });
+            } else {
+                // the target's own law with the rejected tokens taken out (deterministic rule), scaled up accordingly:
+                // per range of the statistics kernel, the range's share minus the rejected tokens that lie in it
+                // (this wave's lanes hold the rejections; more than 64 of them: from LDS)
+                const bool in_regs = (kRule == TV_RULE_DETERMINISTIC) && n <= kWave;
+                double scale = 1.0;
+                int rg_first = 1;                // rejection `lane` is the first one of its token (a token proposed twice)
+                if (kRule == TV_RULE_DETERMINISTIC) {
+                    if (in_regs) {
+                        for (int i = 0; i < n; ++i) {
+                            const double ips = lane_value(rg_inv_ps, i);
+                            if (ips > 0.0) scale *= ips;
+                            if (lane > i && rg_tok == lane_value(rg_tok, i)) rg_first = 0;
+                        }
+                    } else {
+                        for (int i = 0; i < n; ++i)
+                            if (sh.steps[i].inv_ps > 0.0) scale *= sh.steps[i].inv_ps;
+                    }
+                }
+                choose_piece(sh, u, a.splits, [&](int s) {
+                    double m = range_mass(a, sh, b, cur, s, it);
+                    if (kRule == TV_RULE_DETERMINISTIC) {
+                        const int lo = s * a.split_len, hi = lo + a.split_len;
+                        if (in_regs) {
+                            for (int i = 0; i < n; ++i) {
+                                const int x = lane_value(rg_tok, i);
+                                const int first = lane_value(rg_first, i);
+                                const double p0 = lane_value(rg_p0, i);
+                                if (first && x >= lo && x < hi) m -= p0;
+                            }
+                        } else {
+                            for (int i = 0; i < n; ++i) {
+                                const int x = sh.steps[i].tok;
+                                bool first = (x >= lo && x < hi);
+                                for (int k = 0; k < i; ++k) first = first && (sh.steps[k].tok != x);     // (a token proposed twice)
+                                if (first) m -= sh.rej_p0[i];
+                            }
+                        }
+                        m = fmax(m, 0.0) * scale;
+                    }
+                    return m;
+                });
+            }
+        }
     }
     __syncthreads();
     const int cur = sh.cur;
 
-    int tok;
     if (kGreedy) {
-        tok = sh.argmax[cur];
+        if (tid == 0) a.final_token[b] = sh.argmax[cur];
     } else {
-        // ---- inverse CDF at the stop node: first v whose running sum of the final law exceeds u ---------------
+        // ---- second step: the chosen piece is read, by the whole workgroup; the thread that finds the crossing writes
+        //      the token
         const double u = (double)sh.unif[T + cur];
         const int n = sh.n_steps;
-        // the last rejection that changed the target's law (draft rules: one whose corrected law had mass)
-        int eff = -1;
+        bool corrected = false;          // (draft rules: the final law is a corrected one, cut into the chain kernel's slices)
         if (kDraft)
             for (int i = 0; i < n; ++i)
-                if (sh.steps[i].inv_z > 0.0) eff = i;
-        if (kDraft && eff >= 0) {
-            // the corrected law after that rejection: its mass per slice of the sibling-chain kernel is that
-            // kernel's share of the normaliser, over the normaliser
-            const unsigned long long* parts = a.chain_parts + ((int64_t)b * T + sh.rej_child[eff]) * a.chain_slices;
-            const double inv_z = sh.steps[eff].inv_z;
-            tok = draw_from_pieces<kRule>(a, sh, b, cur, u, it, a.chain_slices, kChainSlice,
-                                          [&](int s) { return share_value(parts[s]) * inv_z; });
-        } else {
-            // the target's own law with the rejected tokens taken out (deterministic rule), scaled up accordingly:
-            // per range of the statistics kernel, the range's share minus the rejected tokens that lie in it.
-            // (mass_of runs in wave 0 only, whose lanes hold the rejections; more than 64 of them: from LDS)
-            const bool in_regs = (kRule == TV_RULE_DETERMINISTIC) && wave == 0 && n <= kWave;
-            double scale = 1.0;
-            int rg_first = 1;                    // rejection `lane` is the first one of its token (a token proposed twice)
-            if (kRule == TV_RULE_DETERMINISTIC) {
-                if (in_regs) {
-                    for (int i = 0; i < n; ++i) {
-                        const double ips = lane_value(rg_inv_ps, i);
-                        if (ips > 0.0) scale *= ips;
-                        if (lane > i && rg_tok == lane_value(rg_tok, i)) rg_first = 0;
-                    }
-                } else {
-                    for (int i = 0; i < n; ++i)
-                        if (sh.steps[i].inv_ps > 0.0) scale *= sh.steps[i].inv_ps;
-                }
-            }
-            tok = draw_from_pieces<kRule>(a, sh, b, cur, u, it, a.splits, a.split_len, [&](int s) {
-                double m = range_mass(a, sh, b, cur, s, it);
-                if (kRule == TV_RULE_DETERMINISTIC) {
-                    const int lo = s * a.split_len, hi = lo + a.split_len;
-                    if (in_regs) {
-                        for (int i = 0; i < n; ++i) {
-                            const int x = lane_value(rg_tok, i);
-                            const int first = lane_value(rg_first, i);
-                            const double p0 = lane_value(rg_p0, i);
-                            if (first && x >= lo && x < hi) m -= p0;
-                        }
-                    } else {
-                        for (int i = 0; i < n; ++i) {
-                            const int x = sh.steps[i].tok;
-                            bool first = (x >= lo && x < hi);
-                            for (int k = 0; k < i; ++k) first = first && (sh.steps[k].tok != x);     // (a token proposed twice)
-                            if (first) m -= sh.rej_p0[i];
-                        }
-                    }
-                    m = fmax(m, 0.0) * scale;
-                }
-                return m;
-            });
-        }
+                if (sh.steps[i].inv_z > 0.0) corrected = true;
+        draw_in_piece<kRule>(a, sh, b, cur, u, it, corrected ? kChainSlice : a.split_len, a.final_token + b);
     }
     for (int i = tid; i < T; i += kDrawThreads) path[i] = sh.path[i];
     if (tid == 0) {
         a.status[b] = TV_STATUS_OK;
         a.n_accepted[b] = sh.len;
-        a.final_token[b] = tok;
         a.final_kind[b] = sh.rejected_any ? TV_FINAL_RESIDUAL : TV_FINAL_BONUS;
         a.last_node[b] = cur;
         if (a.selected_con) {
