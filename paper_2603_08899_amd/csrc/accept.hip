@@ -445,26 +445,6 @@ __device__ __forceinline__ void law_after(int v, double p0, double q0, const Cha
     *q_out = q;
 }
 
-// Inclusive prefix sum over the lanes of a wave with data-parallel-primitive moves (no LDS crossbar round trips, which
-// a chain of six dependent shuffles pays one after the other): Hillis-Steele inside each row of 16 lanes, then lane 15
-// of rows 0 and 2 is added to rows 1 and 3, then lane 31 to rows 2 and 3.  Lanes without a source take 0.
-template <int kCtrl, int kRowMask>
-__device__ __forceinline__ double dpp_moved(double x) {
-    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
-    const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)b, kCtrl, kRowMask, 0xf, false);
-    const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(b >> 32), kCtrl, kRowMask, 0xf, false);
-    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
-}
-__device__ __forceinline__ double wave_prefix_sum(double x) {
-    x += dpp_moved<0x111, 0xf>(x);      // row_shr:1
-    x += dpp_moved<0x112, 0xf>(x);      // row_shr:2
-    x += dpp_moved<0x114, 0xf>(x);      // row_shr:4
-    x += dpp_moved<0x118, 0xf>(x);      // row_shr:8
-    x += dpp_moved<0x142, 0xa>(x);      // row_bcast:15 into rows 1 and 3
-    x += dpp_moved<0x143, 0xc>(x);      // row_bcast:31 into rows 2 and 3
-    return x;
-}
-
 // x of lane `src`, src the same in every lane (a register read, no LDS crossbar trip)
 __device__ __forceinline__ int lane_value(int x, int src) {
     return __builtin_amdgcn_readlane(x, __builtin_amdgcn_readfirstlane(src));

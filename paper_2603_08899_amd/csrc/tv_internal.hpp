@@ -174,21 +174,56 @@ hipError_t launch_commit(const CommitArgs& a, hipStream_t s);
 hipError_t launch_embed(const EmbedArgs& a, hipStream_t s);
 
 // ---- small device helpers -------------------------------------------------------------------------
+// Wave-wide reductions with data-parallel-primitive moves (no LDS crossbar round trips, which a butterfly of six
+// dependent shuffles pays one after the other): an inclusive scan - Hillis-Steele inside each row of 16 lanes, then
+// lane 15 of rows 0 and 2 into rows 1 and 3, then lane 31 into rows 2 and 3 - leaves the result in lane 63, which
+// every lane then reads.  All lanes get the same bits.
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ int dpp_int(int old, int x) {
+    return __builtin_amdgcn_update_dpp(old, x, kCtrl, kRowMask, 0xf, false);      // lanes without a source keep `old`
+}
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ float dpp_or_zero(float x) { return __int_as_float(dpp_int<kCtrl, kRowMask>(0, __float_as_int(x))); }
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ float dpp_or_self(float x) {
+    return __int_as_float(dpp_int<kCtrl, kRowMask>(__float_as_int(x), __float_as_int(x)));
+}
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ double dpp_or_zero(double x) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    const unsigned lo = (unsigned)dpp_int<kCtrl, kRowMask>(0, (int)(unsigned)b);
+    const unsigned hi = (unsigned)dpp_int<kCtrl, kRowMask>(0, (int)(unsigned)(b >> 32));
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+__device__ __forceinline__ float last_lane(float x) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), kWave - 1)); }
+__device__ __forceinline__ double last_lane(double x) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)b, kWave - 1);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(b >> 32), kWave - 1);
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+// inclusive prefix sums over the lanes of a wave (lane l: x of lanes 0 .. l, added in that association)
+template <typename T>
+__device__ __forceinline__ T wave_prefix_sum(T x) {
+    x += dpp_or_zero<0x111, 0xf>(x);      // row_shr:1
+    x += dpp_or_zero<0x112, 0xf>(x);      // row_shr:2
+    x += dpp_or_zero<0x114, 0xf>(x);      // row_shr:4
+    x += dpp_or_zero<0x118, 0xf>(x);      // row_shr:8
+    x += dpp_or_zero<0x142, 0xa>(x);      // row_bcast:15 into rows 1 and 3
+    x += dpp_or_zero<0x143, 0xc>(x);      // row_bcast:31 into rows 2 and 3
+    return x;
+}
 __device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o, kWave));
-    return x;
+    x = fmaxf(x, dpp_or_self<0x111, 0xf>(x));
+    x = fmaxf(x, dpp_or_self<0x112, 0xf>(x));
+    x = fmaxf(x, dpp_or_self<0x114, 0xf>(x));
+    x = fmaxf(x, dpp_or_self<0x118, 0xf>(x));
+    x = fmaxf(x, dpp_or_self<0x142, 0xa>(x));
+    x = fmaxf(x, dpp_or_self<0x143, 0xc>(x));
+    return last_lane(x);
 }
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
-    return x;
-}
-__device__ __forceinline__ double wave_sum(double x) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
-    return x;
-}
+__device__ __forceinline__ float wave_sum(float x) { return last_lane(wave_prefix_sum(x)); }
+__device__ __forceinline__ double wave_sum(double x) { return last_lane(wave_prefix_sum(x)); }
 
 // Validates one sequence's parent/kind arrays (already in LDS) with the whole workgroup and
 // returns the TV_STATUS_* bits to every thread.  `flag` is one LDS word.
