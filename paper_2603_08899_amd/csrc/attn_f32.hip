@@ -17,10 +17,11 @@ constexpr int kWaves = kThreads / kWave;
 constexpr int kRowsPerWave = 4;
 constexpr int kRowsPerWg = kWaves * kRowsPerWave;
 constexpr int kTile = 64;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <int D>
 struct F32Smem {
-    float k[kTile][D + 1];        // +1: lanes read different keys at the same d
+    float k[kTile][D + 4];        // +4: rows stay 16-byte aligned and 16 lanes reading 16 bytes each at one d hit all banks
     float v[kTile][D];
     float q[kRowsPerWg][D];
     float p[kWaves][kRowsPerWave][kTile];
@@ -37,20 +38,42 @@ __global__ __launch_bounds__(kThreads) void attn_f32_kernel(AttnArgs a) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int M = a.M, g = h / a.G;
     constexpr int DPL = D / kWave;          // output columns per lane
+    constexpr int kQPer = kRowsPerWg * D / 4 / kThreads;      // 16-byte pieces of the query block per thread
+    constexpr int kTilePer = kTile * D / 4 / kThreads;        // ... of a K (or V) tile per thread
 
-    for (int i = tid; i < M; i += kThreads) {
-        sm.parent[i] = a.parent[(int64_t)b * M + i];
-        sm.kind[i] = a.kind[(int64_t)b * M + i];
-    }
-    __syncthreads();
-    int bad = validate_tree(sm.parent, sm.kind, M, &sm.flag);
+    // everything that does not hang on the prefix length is requested at once: the two per-sequence scalars, the
+    // tree, the query block (into registers)
     const int P = a.prefix_len[b];
-    if (P < a.soft_len || P < 0 || P > a.max_prefix_len) bad |= TV_STATUS_BAD_PREFIX;
-    if (rb == 0 && h == 0 && tid == 0) a.status[b] = bad;
-
+    const int64_t kv_first = a.kv_offset[b];
     const float* q = static_cast<const float*>(a.q);
     float* out = static_cast<float*>(a.out);
     const int row0 = rb * kRowsPerWg;
+    int r_parent = 0;
+    unsigned char r_kind = 0;
+    if (tid < M) {                           // (M <= kMaxRows < kThreads)
+        r_parent = a.parent[(int64_t)b * M + tid];
+        r_kind = a.kind[(int64_t)b * M + tid];
+    }
+    f32x4 r_q[kQPer];
+#pragma unroll
+    for (int k = 0; k < kQPer; ++k) {
+        const int idx = tid + k * kThreads, qi = idx / (D / 4), c4 = idx % (D / 4);
+        const int i = min(row0 + qi, M - 1);
+        r_q[k] = *reinterpret_cast<const f32x4*>(q + (((int64_t)b * M + i) * a.Hq + h) * D + c4 * 4);
+    }
+    if (tid < M) {
+        sm.parent[tid] = r_parent;
+        sm.kind[tid] = r_kind;
+    }
+#pragma unroll
+    for (int k = 0; k < kQPer; ++k) {
+        const int idx = tid + k * kThreads, qi = idx / (D / 4), c4 = idx % (D / 4);
+        *reinterpret_cast<f32x4*>(&sm.q[qi][c4 * 4]) = r_q[k];
+    }
+    __syncthreads();
+    int bad = validate_tree(sm.parent, sm.kind, M, &sm.flag);
+    if (P < a.soft_len || P < 0 || P > a.max_prefix_len) bad |= TV_STATUS_BAD_PREFIX;
+    if (rb == 0 && h == 0 && tid == 0) a.status[b] = bad;
     if (bad) {
         for (int idx = tid; idx < kRowsPerWg * D; idx += kThreads) {
             const int i = row0 + idx / D;
@@ -60,10 +83,19 @@ __global__ __launch_bounds__(kThreads) void attn_f32_kernel(AttnArgs a) {
         return;
     }
 
-    for (int idx = tid; idx < kRowsPerWg * D; idx += kThreads) {
-        const int i = min(row0 + idx / D, M - 1);
-        sm.q[idx / D][idx % D] = q[(((int64_t)b * M + i) * a.Hq + h) * D + idx % D];
+    const int Lk = P + M;
+    const float* kb = static_cast<const float*>(a.k) + kv_first * a.tok_stride + (int64_t)g * a.head_stride;
+    const float* vb = static_cast<const float*>(a.v) + kv_first * a.tok_stride + (int64_t)g * a.head_stride;
+    // a tile's 16-byte pieces, held in registers between their request and the moment the LDS tile is free
+    f32x4 r_k[kTilePer], r_v[kTilePer];
+#define TV_REQUEST_TILE(T0)                                                                            \
+    _Pragma("unroll") for (int k = 0; k < kTilePer; ++k) {                                             \
+        const int idx = tid + k * kThreads, key = idx / (D / 4), c4 = idx % (D / 4);                   \
+        const int64_t src = (int64_t)min((T0) + key, Lk - 1) * a.tok_stride + c4 * 4;                  \
+        r_k[k] = *reinterpret_cast<const f32x4*>(kb + src);                                           \
+        r_v[k] = *reinterpret_cast<const f32x4*>(vb + src);                                           \
     }
+    TV_REQUEST_TILE(0)
 
     // per-row state of this wave's rows (wave-uniform values live in every lane)
     int row[kRowsPerWave];
@@ -81,31 +113,40 @@ __global__ __launch_bounds__(kThreads) void attn_f32_kernel(AttnArgs a) {
         for (int c = 0; c < DPL; ++c) o[r][c] = 0.f;
     }
 
-    const int Lk = P + M;
-    const float* kb = static_cast<const float*>(a.k) + a.kv_offset[b] * a.tok_stride + (int64_t)g * a.head_stride;
-    const float* vb = static_cast<const float*>(a.v) + a.kv_offset[b] * a.tok_stride + (int64_t)g * a.head_stride;
-
     for (int t0 = 0; t0 < Lk; t0 += kTile) {
-        __syncthreads();       // previous tile fully consumed (and sm.q written, first time round)
-        for (int idx = tid; idx < kTile * (D / 4); idx += kThreads) {
-            const int key = idx / (D / 4), c4 = idx % (D / 4);
-            const int64_t src = (int64_t)min(t0 + key, Lk - 1) * a.tok_stride + c4 * 4;
-            const float4 kk = *reinterpret_cast<const float4*>(kb + src);
-            const float4 vv = *reinterpret_cast<const float4*>(vb + src);
-            sm.k[key][c4 * 4 + 0] = kk.x; sm.k[key][c4 * 4 + 1] = kk.y;
-            sm.k[key][c4 * 4 + 2] = kk.z; sm.k[key][c4 * 4 + 3] = kk.w;
-            *reinterpret_cast<float4*>(&sm.v[key][c4 * 4]) = vv;
+        __syncthreads();       // previous tile fully consumed
+#pragma unroll
+        for (int k = 0; k < kTilePer; ++k) {
+            const int idx = tid + k * kThreads, key = idx / (D / 4), c4 = idx % (D / 4);
+            *reinterpret_cast<f32x4*>(&sm.k[key][c4 * 4]) = r_k[k];
+            *reinterpret_cast<f32x4*>(&sm.v[key][c4 * 4]) = r_v[k];
+        }
+        if (t0 + kTile < Lk) {                                // the next tile travels while this one is worked on
+            TV_REQUEST_TILE(t0 + kTile)
         }
         __syncthreads();
 
+        // scores: lane = key; the key's row and the four query rows are read 16 bytes at a time
         const int kg = t0 + lane;          // this lane's key
+        float sc[kRowsPerWave];
+#pragma unroll
+        for (int r = 0; r < kRowsPerWave; ++r) sc[r] = 0.f;
+#pragma unroll 4
+        for (int d = 0; d < D; d += 4) {
+            const float4 kk = *reinterpret_cast<const float4*>(&sm.k[lane][d]);
+#pragma unroll
+            for (int r = 0; r < kRowsPerWave; ++r) {
+                const float4 qq = *reinterpret_cast<const float4*>(&sm.q[wave * kRowsPerWave + r][d]);
+                // (one chain per row, d ascending: the order of the plain loop)
+                sc[r] = fmaf(qq.x, kk.x, sc[r]);
+                sc[r] = fmaf(qq.y, kk.y, sc[r]);
+                sc[r] = fmaf(qq.z, kk.z, sc[r]);
+                sc[r] = fmaf(qq.w, kk.w, sc[r]);
+            }
+        }
 #pragma unroll
         for (int r = 0; r < kRowsPerWave; ++r) {
-            const float* qr = sm.q[wave * kRowsPerWave + r];
-            float s = 0.f;
-#pragma unroll 8
-            for (int d = 0; d < D; ++d) s = fmaf(qr[d], sm.k[lane][d], s);
-            s *= a.scale;
+            float s = sc[r] * a.scale;
             bool vis;
             if (kg < P) vis = (kg >= a.soft_len) || is_con[r];
             else if (kg < Lk) {
@@ -126,12 +167,22 @@ __global__ __launch_bounds__(kThreads) void attn_f32_kernel(AttnArgs a) {
         // same wave wrote and reads sm.p: LDS operations of one wave complete in order
         __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        for (int key = 0; key < kTile; ++key) {
+        // values: lane = output column; four keys' weights per read, keys ascending
+        for (int key = 0; key < kTile; key += 4) {
+            float4 pw[kRowsPerWave];
+#pragma unroll
+            for (int r = 0; r < kRowsPerWave; ++r) pw[r] = *reinterpret_cast<const float4*>(&sm.p[wave][r][key]);
 #pragma unroll
             for (int c = 0; c < DPL; ++c) {
-                const float vv = sm.v[key][c * kWave + lane];
+                const float v0 = sm.v[key][c * kWave + lane], v1 = sm.v[key + 1][c * kWave + lane];
+                const float v2 = sm.v[key + 2][c * kWave + lane], v3 = sm.v[key + 3][c * kWave + lane];
 #pragma unroll
-                for (int r = 0; r < kRowsPerWave; ++r) o[r][c] = fmaf(sm.p[wave][r][key], vv, o[r][c]);
+                for (int r = 0; r < kRowsPerWave; ++r) {
+                    o[r][c] = fmaf(pw[r].x, v0, o[r][c]);
+                    o[r][c] = fmaf(pw[r].y, v1, o[r][c]);
+                    o[r][c] = fmaf(pw[r].z, v2, o[r][c]);
+                    o[r][c] = fmaf(pw[r].w, v3, o[r][c]);
+                }
             }
         }
     }
@@ -147,6 +198,8 @@ __global__ __launch_bounds__(kThreads) void attn_f32_kernel(AttnArgs a) {
         if (a.lse && lane == 0) a.lse[((int64_t)b * a.Hq + h) * M + i] = m[r] + logf(l[r]);
     }
 }
+
+#undef TV_REQUEST_TILE
 
 template <int D>
 hipError_t launch_f32(const AttnArgs& a, hipStream_t s) {
